@@ -1,0 +1,153 @@
+/*
+ * libwagma — the per-iteration hot path of WAGMA-SGD (wait-avoiding group
+ * model averaging, arXiv 2005.00124) for P model replicas that live as P rows
+ * in the HBM of one AMD MI355X (gfx950).
+ *
+ * One call of wagma_step() is one iteration t of Algorithm 2, lines 6-17, for
+ * all P processes at once:
+ *   lines 6-7   local update  m' = mu*m + g,  W' = W - lr*m'   (heavy-ball SGD)
+ *   lines 9-14  group model average over the groups of Algorithm 1, with the
+ *               stale rule (W_sum + W')/(S+1) for late processes, whose
+ *               contribution to W_sum is their send buffer ("pub")
+ *   lines 15-16 global average over all P when (t+1) mod tau == 0
+ *   Section 4   (execution snapshot): the send buffer is refreshed with W'.
+ *
+ * Conventions common to all entry points
+ *   - Plain C ABI.  "device" pointers are HIP device memory on the GPU that was
+ *     current when the context was created; "host" pointers are ordinary host
+ *     memory.  The library never takes ownership of a caller's buffer.
+ *   - Every function returns WAGMA_OK (0) or a negative error code; nothing is
+ *     thrown, nothing aborts, and on error no caller buffer has been modified.
+ *   - A context is not thread-safe; different contexts are independent.
+ *   - Layout of w, g, m, pub: P rows of ld floats (row-major, row p at
+ *     base + p*ld), fp32, base 16-byte aligned, ld = wagma_row_stride(ctx)
+ *     (a multiple of 4, >= n).  Columns [0, n) carry the model.  Columns
+ *     [n, ld) are padding: the library may read them and may overwrite columns
+ *     [n, 4*ceil(n/4)) with unspecified values; it never lets padding
+ *     influence columns [0, n).
+ */
+#ifndef WAGMA_H
+#define WAGMA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define WAGMA_OK 0
+#define WAGMA_EINVAL (-1) /* bad argument: P or S not a power of two, S > P, n < 1,
+                             tau < 0, NULL or misaligned pointer, negative iter, ... */
+#define WAGMA_EHIP (-2)   /* a HIP runtime call failed; see wagma_last_hip_error() */
+#define WAGMA_ENOMEM (-3) /* host or device allocation failed in wagma_create */
+
+#define WAGMA_MAX_P 1024 /* largest supported number of processes */
+
+typedef struct wagma_ctx wagma_ctx; /* opaque; owned by the library */
+
+/*
+ * Create a context for P processes in groups of S on models of n parameters,
+ * with a global average every tau iterations (Algorithm 2, inputs; P and S
+ * powers of two with S <= P as Section 3.3 assumes).
+ *   out  host pointer that receives the context.
+ *   P    1 <= P <= WAGMA_MAX_P, power of two.      S  1 <= S <= P, power of two.
+ *   n    >= 1.     tau  >= 0; 0 = never average globally, 1 = every iteration.
+ * Builds the group-schedule table (Algorithm 1 for every distinct iteration
+ * residue) with a kernel on the current device, keeps it in device memory and
+ * mirrors it on the host.  Synchronises the device once.  Chooses the row
+ * stride ld.
+ */
+int wagma_create(wagma_ctx** out, int P, int S, int64_t n, int tau);
+
+/* Frees the tables and the context.  Does not touch caller buffers.  The
+ * caller must have synchronised every stream that still runs a wagma_step of
+ * this context.  NULL is accepted. */
+int wagma_destroy(wagma_ctx* ctx);
+
+/* Row stride ld in floats chosen by wagma_create (>= n, multiple of 4), or a
+ * negative error code.  The caller allocates P*ld floats per buffer. */
+int64_t wagma_row_stride(const wagma_ctx* ctx);
+
+/* Override the row stride (before the first step): ld >= 4*ceil(n/4), ld % 4 == 0. */
+int wagma_set_row_stride(wagma_ctx* ctx, int64_t ld);
+
+/* Number of distinct group schedules: the schedule of iteration t equals that
+ * of iteration t + period.  period = G / gcd(g, G) with G = log2 P, g = log2 S
+ * (the starting phase of Algorithm 1, line 3, is (t*g) mod G). */
+int wagma_schedule_period(const wagma_ctx* ctx);
+
+/*
+ * Group schedule of iteration iter (Algorithm 1; iter is the paper's 0-based t).
+ *   dev_table   host pointer receiving a DEVICE pointer to P int32, or NULL.
+ *   host_table  host pointer receiving a HOST pointer to the same P int32, or NULL.
+ * Entry k*S + e is the rank of member e of group k.  Groups are listed by
+ * ascending smallest member; member e differs from the smallest member in the
+ * phase bits selected by the binary digits of e (digit r <-> phase r of
+ * Algorithm 1), so e and e^1 exchange in the first butterfly phase.
+ * For an iteration that ends in the global average ((iter+1) mod tau == 0) the
+ * table is the single group 0..P-1.
+ * Both pointers stay valid until wagma_destroy and must not be written.
+ */
+int wagma_group_schedule(const wagma_ctx* ctx, int64_t iter,
+                         const int32_t** dev_table, const int32_t** host_table);
+
+/* 1 if iteration iter ends in the global average, 0 if in group averages,
+ * negative on error (Algorithm 2, line 8). */
+int wagma_is_global_iteration(const wagma_ctx* ctx, int64_t iter);
+
+/*
+ * One iteration of Algorithm 2 (lines 6-17) for all P processes, enqueued on
+ * `stream`; returns without waiting for the GPU.
+ *   w     device, in/out  P x ld   models W_t -> W_{t+1}
+ *   g     device, in      P x ld   local gradients G_t (never written)
+ *   m     device, in/out  P x ld   momentum state
+ *   pub   device, in/out  P x ld   send buffers: read for late processes (their
+ *                                  contribution to the group sum), then set to W'_t.
+ *                                  Must be initialised (e.g. to W_0) before the first
+ *                                  step in which a process is late.
+ *   stale_mask  host, ceil(P/64) words; bit p of the mask set = process p is late
+ *               in this iteration.  NULL = nobody is late.  Read before the call
+ *               returns; ignored in a global iteration (Section 4: all processes
+ *               contribute equally aged models at the synchronisation point).
+ *   lr, mu      learning rate and momentum coefficient.
+ *   iter        the paper's 0-based t; selects the groups and group/global.
+ *               Calls may come in any order of iter: the context keeps no
+ *               iteration state, so resuming is passing the right iter.
+ *   stream      a hipStream_t (NULL = the default stream).
+ * Arithmetic is IEEE fp32: both update lines are one fused multiply-add each,
+ * the group (or global) sum is a balanced pairwise tree over the member order
+ * of wagma_group_schedule, 1/S and 1/P are exact, 1/(S+1) is a true division.
+ * No allocation, no host<->device copy and no synchronisation happen here.
+ */
+int wagma_step(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub,
+               const uint64_t* stale_mask, float lr, float mu, int64_t iter,
+               void* stream);
+
+/*
+ * Seeded lateness model (not from the paper, whose lateness is physical; its
+ * simulation delays random ranks, Section 6.2): process p is late in iteration
+ * iter iff the upper 32 bits of a 64-bit hash of (seed, iter, p) are below
+ * `threshold` = floor(q * 2^32).  Integer arithmetic only.
+ *   mask_words  host, out, ceil(P/64) words in the layout wagma_step takes.
+ */
+int wagma_stale_mask(const wagma_ctx* ctx, uint64_t seed, int64_t iter,
+                     uint32_t threshold, uint64_t* mask_words);
+
+/* Tuning knobs; the defaults are the measured best on MI355X.  Results do not
+ * depend on them (same summation order in every variant). */
+#define WAGMA_OPT_BLOCK 1        /* threads per workgroup: 128, 256, 512 or 1024      */
+#define WAGMA_OPT_NONTEMPORAL 2  /* 0/1: non-temporal hint on loads and stores        */
+#define WAGMA_OPT_FORCE_STREAM 3 /* 0/1: use the row-streaming kernel for every S     */
+#define WAGMA_OPT_XCD_SWIZZLE 4  /* 0/1: give each of the 8 XCDs a contiguous column range */
+int wagma_set_option(wagma_ctx* ctx, int option, int64_t value);
+
+/* Text for an error code (static storage). */
+const char* wagma_strerror(int code);
+
+/* The hipError_t (as int) of the last failed HIP call in this thread, 0 if none. */
+int wagma_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WAGMA_H */

@@ -1,0 +1,369 @@
+/*
+ * CPU oracle for the WAGMA-SGD per-iteration hot path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain, single-threaded
+ * reference that the GPU library is checked against.  It shares no code,
+ * header, table or constant generator with the HIP library, and only the
+ * tests, the smoke check and the benchmark's cpu_baseline leg may use it.
+ *
+ * Every function follows the paper (arXiv 2005.00124) in the paper's own
+ * order and notation:
+ *   - oracle_grouping_unionfind : Algorithm 1 (dynamic grouping), literally,
+ *                                 with a union-find over the P processes.
+ *   - oracle_member_table       : the butterfly phases of Section 3.3 (the
+ *                                 text after Algorithm 1) turned into an
+ *                                 ordered member list per group.
+ *   - oracle_step_f32 / _f64    : Algorithm 2 lines 6-17 for one iteration t
+ *                                 on P model replicas held as P rows.
+ *   - oracle_stale_mask         : the seeded stand-in for "which processes
+ *                                 are late in iteration t" (not in the paper;
+ *                                 a counter-based integer hash).
+ *
+ * Readings of the paper taken here (each is also pinned by a CPU test):
+ *   - Algorithm 1 line 6: the mask of a phase is 1 << shift, built afresh in
+ *     every phase (the printed "mask <<= shift" would accumulate; only the
+ *     afresh reading reproduces the printed P=8,S=4 groups of iteration 1).
+ *   - Algorithm 2 line 8: iteration t is a global one iff (t+1) mod tau == 0;
+ *     tau == 0 means "never".
+ *   - U() in Algorithm 2 line 6 is heavy-ball momentum SGD:
+ *       m' = mu*m + g,  w' = w - lr*m'   (each one fused multiply-add).
+ *   - The sum inside a group is taken in butterfly-phase order: a balanced
+ *     pairwise tree over the member list, first phase = adjacent members.
+ *     The global sum is the same tree over ranks 0..P-1.
+ *   - 1/S and 1/P are exact powers of two (a multiply); 1/(S+1) is a true
+ *     IEEE division applied after the addition W_sum + W'.
+ *   - The send buffer ("pub") of every process holds W' of the last
+ *     iteration: pub <- W' at the end of every iteration, global ones too.
+ *
+ * Build: gcc -O2 -ffp-contract=off -fno-fast-math -shared -fPIC ... -lm
+ * (no contraction, no fast-math, no flush-to-zero: IEEE fp32 throughout).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+
+#define ORACLE_OK 0
+#define ORACLE_EINVAL (-1)
+#define ORACLE_ENOMEM (-2)
+
+/* log2 of a power of two, or -1. */
+static int exact_log2(int64_t x)
+{
+    int l = 0;
+    if (x < 1)
+        return -1;
+    while ((x & 1) == 0) {
+        x >>= 1;
+        ++l;
+    }
+    return x == 1 ? l : -1;
+}
+
+static int uf_find(int32_t *parent, int p)
+{
+    while (parent[p] != p)
+        p = parent[p];
+    return p;
+}
+
+/*
+ * Algorithm 1, taken literally: every process starts as its own group; for
+ * each of the log2(S) phases, every pair p == p XOR mask is an equivalence
+ * and the two groups holding them are merged.
+ * rep[p] receives the smallest member of p's group (the group's name).
+ */
+int oracle_grouping_unionfind(int P, int S, int64_t t, int32_t *rep)
+{
+    int global_phases = exact_log2(P);
+    int group_phases = exact_log2(S);
+    if (global_phases < 0 || group_phases < 0 || S > P || t < 0 || !rep)
+        return ORACLE_EINVAL;
+
+    int32_t *parent = (int32_t *)malloc(sizeof(int32_t) * (size_t)P);
+    if (!parent)
+        return ORACLE_ENOMEM;
+    for (int p = 0; p < P; ++p)
+        parent[p] = p; /* make each process an individual group */
+
+    int shift = 0;
+    if (global_phases > 0)
+        shift = (int)((t * (int64_t)group_phases) % global_phases);
+
+    for (int r = 1; r <= group_phases; ++r) {
+        int mask = 1 << shift;
+        for (int p = 0; p < P; ++p) {
+            int q = p ^ mask; /* equivalence relation p == q */
+            int group_p = uf_find(parent, p);
+            int group_q = uf_find(parent, q);
+            if (group_p != group_q) {
+                /* merge; the smaller name survives so that the final
+                 * representative is the smallest member */
+                if (group_p < group_q)
+                    parent[group_q] = group_p;
+                else
+                    parent[group_p] = group_q;
+            }
+        }
+        shift = (shift + 1) % global_phases;
+    }
+    for (int p = 0; p < P; ++p)
+        rep[p] = uf_find(parent, p);
+    free(parent);
+    return ORACLE_OK;
+}
+
+/*
+ * The bit positions of the butterfly phases executed in iteration t, in the
+ * order Algorithm 1 visits them.  bits[] must hold log2(S) entries.
+ */
+static void phase_bits(int global_phases, int group_phases, int64_t t, int *bits)
+{
+    int shift = 0;
+    if (global_phases > 0)
+        shift = (int)((t * (int64_t)group_phases) % global_phases);
+    for (int r = 0; r < group_phases; ++r) {
+        bits[r] = shift;
+        shift = (shift + 1) % global_phases;
+    }
+}
+
+/*
+ * Ordered member list of every group in iteration t.
+ * table[k*S + e] = rank of member e of the k-th group.  Groups are listed by
+ * ascending smallest member.  Inside a group, member e differs from the
+ * smallest member in exactly the phase bits selected by the binary digits of
+ * e: digit r of e switches the bit of phase r.  So members e and e^1 are the
+ * pair that exchanges in the first phase, e and e^2 in the second, and so on:
+ * a balanced pairwise sum over e = 0..S-1 is the butterfly's own order.
+ */
+int oracle_member_table(int P, int S, int64_t t, int32_t *table)
+{
+    int global_phases = exact_log2(P);
+    int group_phases = exact_log2(S);
+    int bits[32];
+    if (global_phases < 0 || group_phases < 0 || S > P || t < 0 || !table)
+        return ORACLE_EINVAL;
+    phase_bits(global_phases, group_phases, t, bits);
+
+    int all_bits = 0;
+    for (int r = 0; r < group_phases; ++r)
+        all_bits |= 1 << bits[r];
+
+    int k = 0;
+    for (int base = 0; base < P; ++base) {
+        if (base & all_bits)
+            continue; /* not the smallest member of its group */
+        for (int e = 0; e < S; ++e) {
+            int p = base;
+            for (int r = 0; r < group_phases; ++r)
+                if ((e >> r) & 1)
+                    p |= 1 << bits[r];
+            table[k * S + e] = p;
+        }
+        ++k;
+    }
+    return k == P / S ? ORACLE_OK : ORACLE_EINVAL;
+}
+
+/* Is iteration t one that ends in the global average (Algorithm 2 line 8)? */
+int oracle_is_global_iteration(int tau, int64_t t)
+{
+    return tau > 0 && ((t + 1) % tau) == 0;
+}
+
+/* Balanced pairwise sum of count = 2^k values, adjacent pairs first. */
+static float tree_sum_f32(const float *c, int count)
+{
+    if (count == 1)
+        return c[0];
+    float left = tree_sum_f32(c, count / 2);
+    float right = tree_sum_f32(c + count / 2, count / 2);
+    return left + right;
+}
+
+static double tree_sum_f64(const double *c, int count)
+{
+    if (count == 1)
+        return c[0];
+    double left = tree_sum_f64(c, count / 2);
+    double right = tree_sum_f64(c + count / 2, count / 2);
+    return left + right;
+}
+
+static int mask_bit(const uint64_t *stale_mask, int p)
+{
+    if (!stale_mask)
+        return 0;
+    return (int)((stale_mask[p >> 6] >> (p & 63)) & 1u);
+}
+
+/*
+ * One iteration t of Algorithm 2 (lines 6-17) for all P replicas, fp32.
+ * w, g, m, pub: P rows of ld floats, n used columns.  w, m, pub are updated
+ * in place; g is read only.  stale_mask: bit p set = process p is late in
+ * this iteration (NULL = nobody).
+ */
+int oracle_step_f32(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
+                    float *w, const float *g, float *m, float *pub,
+                    const uint64_t *stale_mask, float lr, float mu)
+{
+    if (exact_log2(P) < 0 || exact_log2(S) < 0 || S > P || n < 1 || ld < n ||
+        tau < 0 || t < 0 || !w || !g || !m || !pub)
+        return ORACLE_EINVAL;
+
+    int32_t *table = (int32_t *)malloc(sizeof(int32_t) * (size_t)P);
+    float *w_prime = (float *)malloc(sizeof(float) * (size_t)P);
+    float *contrib = (float *)malloc(sizeof(float) * (size_t)P);
+    if (!table || !w_prime || !contrib) {
+        free(table);
+        free(w_prime);
+        free(contrib);
+        return ORACLE_ENOMEM;
+    }
+    int global = oracle_is_global_iteration(tau, t);
+    if (!global)
+        oracle_member_table(P, S, t, table);
+
+    for (int64_t j = 0; j < n; ++j) {
+        /* lines 6-7: local update of every replica */
+        for (int i = 0; i < P; ++i) {
+            int64_t at = (int64_t)i * ld + j;
+            float m_new = fmaf(mu, m[at], g[at]);
+            w_prime[i] = fmaf(-lr, m_new, w[at]);
+            m[at] = m_new;
+        }
+        if (global) {
+            /* lines 15-16: everybody contributes W', staleness ignored */
+            float sum = tree_sum_f32(w_prime, P);
+            float avg = sum * (1.0f / (float)P);
+            for (int i = 0; i < P; ++i)
+                w[(int64_t)i * ld + j] = avg;
+        } else {
+            /* lines 9-14 */
+            for (int k = 0; k < P / S; ++k) {
+                const int32_t *member = table + (int64_t)k * S;
+                for (int e = 0; e < S; ++e) {
+                    int p = member[e];
+                    contrib[e] = mask_bit(stale_mask, p)
+                                     ? pub[(int64_t)p * ld + j] /* send buffer */
+                                     : w_prime[p];
+                }
+                float w_sum = tree_sum_f32(contrib, S);
+                for (int e = 0; e < S; ++e) {
+                    int p = member[e];
+                    int64_t at = (int64_t)p * ld + j;
+                    if (!mask_bit(stale_mask, p))
+                        w[at] = w_sum * (1.0f / (float)S);
+                    else
+                        w[at] = (w_sum + w_prime[p]) / (float)(S + 1);
+                }
+            }
+        }
+        /* the send buffer now holds this iteration's locally updated model */
+        for (int i = 0; i < P; ++i)
+            pub[(int64_t)i * ld + j] = w_prime[i];
+    }
+    free(table);
+    free(w_prime);
+    free(contrib);
+    return ORACLE_OK;
+}
+
+/* The same iteration carried in fp64 (a shadow used to bound rounding). */
+int oracle_step_f64(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
+                    double *w, const double *g, double *m, double *pub,
+                    const uint64_t *stale_mask, double lr, double mu)
+{
+    if (exact_log2(P) < 0 || exact_log2(S) < 0 || S > P || n < 1 || ld < n ||
+        tau < 0 || t < 0 || !w || !g || !m || !pub)
+        return ORACLE_EINVAL;
+
+    int32_t *table = (int32_t *)malloc(sizeof(int32_t) * (size_t)P);
+    double *w_prime = (double *)malloc(sizeof(double) * (size_t)P);
+    double *contrib = (double *)malloc(sizeof(double) * (size_t)P);
+    if (!table || !w_prime || !contrib) {
+        free(table);
+        free(w_prime);
+        free(contrib);
+        return ORACLE_ENOMEM;
+    }
+    int global = oracle_is_global_iteration(tau, t);
+    if (!global)
+        oracle_member_table(P, S, t, table);
+
+    for (int64_t j = 0; j < n; ++j) {
+        for (int i = 0; i < P; ++i) {
+            int64_t at = (int64_t)i * ld + j;
+            double m_new = mu * m[at] + g[at];
+            w_prime[i] = w[at] - lr * m_new;
+            m[at] = m_new;
+        }
+        if (global) {
+            double avg = tree_sum_f64(w_prime, P) / (double)P;
+            for (int i = 0; i < P; ++i)
+                w[(int64_t)i * ld + j] = avg;
+        } else {
+            for (int k = 0; k < P / S; ++k) {
+                const int32_t *member = table + (int64_t)k * S;
+                for (int e = 0; e < S; ++e) {
+                    int p = member[e];
+                    contrib[e] = mask_bit(stale_mask, p)
+                                     ? pub[(int64_t)p * ld + j]
+                                     : w_prime[p];
+                }
+                double w_sum = tree_sum_f64(contrib, S);
+                for (int e = 0; e < S; ++e) {
+                    int p = member[e];
+                    int64_t at = (int64_t)p * ld + j;
+                    if (!mask_bit(stale_mask, p))
+                        w[at] = w_sum / (double)S;
+                    else
+                        w[at] = (w_sum + w_prime[p]) / (double)(S + 1);
+                }
+            }
+        }
+        for (int i = 0; i < P; ++i)
+            pub[(int64_t)i * ld + j] = w_prime[i];
+    }
+    free(table);
+    free(w_prime);
+    free(contrib);
+    return ORACLE_OK;
+}
+
+/*
+ * Seeded lateness: process p is late in iteration t iff the upper 32 bits of
+ * a 64-bit integer hash of (seed, t, p) fall below `threshold`
+ * (threshold = floor(q * 2^32) for a late probability q).  Integer only, so
+ * any two implementations agree bit for bit.
+ * The hash is two rounds of the public splitmix64 output function
+ * (Steele, Lea, Flood 2014; Vigna's splitmix64.c), keyed by t and then p.
+ */
+static uint64_t splitmix_finish(uint64_t z)
+{
+    z ^= z >> 30;
+    z *= UINT64_C(0xBF58476D1CE4E5B9);
+    z ^= z >> 27;
+    z *= UINT64_C(0x94D049BB133111EB);
+    z ^= z >> 31;
+    return z;
+}
+
+int oracle_stale_mask(uint64_t seed, int64_t t, int P, uint32_t threshold,
+                      uint64_t *mask_words)
+{
+    if (P < 1 || t < 0 || !mask_words)
+        return ORACLE_EINVAL;
+    int words = (P + 63) / 64;
+    for (int k = 0; k < words; ++k)
+        mask_words[k] = 0;
+    uint64_t per_iter =
+        splitmix_finish(seed + UINT64_C(0x9E3779B97F4A7C15) * ((uint64_t)t + 1u));
+    for (int p = 0; p < P; ++p) {
+        uint64_t h = splitmix_finish(
+            per_iter + UINT64_C(0xD1B54A32D192ED03) * ((uint64_t)p + 1u));
+        if ((uint32_t)(h >> 32) < threshold)
+            mask_words[p >> 6] |= UINT64_C(1) << (p & 63);
+    }
+    return ORACLE_OK;
+}

@@ -1,0 +1,150 @@
+"""ctypes front end of the plain-C CPU oracle (``wagma_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: used by ``tests/``, by the smoke check and by the
+benchmark's ``cpu_baseline`` leg.  Nothing in the product package imports it,
+and it imports nothing from the product package.
+
+Arrays are numpy, row-major ``(P, ld)`` with ``n <= ld`` used columns, updated
+in place exactly as Algorithm 2 (lines 6-17) of the paper updates W, the
+momentum state and the send buffer.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "wagma_oracle.c")
+_LIB = os.path.join(_HERE, "libwagma_oracle.so")
+
+# No contraction, no fast-math: the oracle is IEEE fp32 with explicit fmaf.
+CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-std=c99", "-Wall",
+          "-shared", "-fPIC"]
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (always when ``force``), return the path."""
+    stale = (not os.path.exists(_LIB)
+             or os.path.getmtime(_LIB) < os.path.getmtime(_SRC))
+    if force or stale:
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.run(["gcc", *CFLAGS, "-o", tmp, _SRC, "-lm"], check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    lib = ctypes.CDLL(build())
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    u64p = ctypes.POINTER(ctypes.c_uint64)
+    f32p = ctypes.POINTER(ctypes.c_float)
+    f64p = ctypes.POINTER(ctypes.c_double)
+    lib.oracle_grouping_unionfind.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int64, i32p]
+    lib.oracle_member_table.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int64, i32p]
+    lib.oracle_is_global_iteration.argtypes = [ctypes.c_int, ctypes.c_int64]
+    lib.oracle_step_f32.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
+                                    ctypes.c_int, ctypes.c_int64, f32p, f32p, f32p, f32p, u64p,
+                                    ctypes.c_float, ctypes.c_float]
+    lib.oracle_step_f64.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
+                                    ctypes.c_int, ctypes.c_int64, f64p, f64p, f64p, f64p, u64p,
+                                    ctypes.c_double, ctypes.c_double]
+    lib.oracle_stale_mask.argtypes = [ctypes.c_uint64, ctypes.c_int64, ctypes.c_int,
+                                      ctypes.c_uint32, u64p]
+    for f in (lib.oracle_grouping_unionfind, lib.oracle_member_table,
+              lib.oracle_is_global_iteration, lib.oracle_step_f32,
+              lib.oracle_step_f64, lib.oracle_stale_mask):
+        f.restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise ValueError("%s failed with oracle error %d" % (what, rc))
+
+
+def grouping_unionfind(P: int, S: int, t: int) -> np.ndarray:
+    """Algorithm 1 run literally; entry p = smallest member of p's group."""
+    rep = np.empty(P, dtype=np.int32)
+    _check(_load().oracle_grouping_unionfind(
+        P, S, t, rep.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))), "grouping_unionfind")
+    return rep
+
+
+def member_table(P: int, S: int, t: int) -> np.ndarray:
+    """(P/S, S) table: ordered members of every group of iteration t."""
+    table = np.empty(P, dtype=np.int32)
+    _check(_load().oracle_member_table(
+        P, S, t, table.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))), "member_table")
+    return table.reshape(P // S, S)
+
+
+def is_global_iteration(tau: int, t: int) -> bool:
+    return bool(_load().oracle_is_global_iteration(tau, t))
+
+
+def mask_words(stale) -> np.ndarray | None:
+    """Pack an iterable of late ranks / a bool vector / uint64 words into words."""
+    if stale is None:
+        return None
+    a = np.asarray(stale)
+    if a.dtype == np.uint64:
+        return np.ascontiguousarray(a)
+    if a.dtype == np.bool_:
+        ranks = np.nonzero(a)[0]
+        P = a.size
+    else:
+        raise TypeError("stale must be None, a bool vector of length P or uint64 words")
+    words = np.zeros((P + 63) // 64, dtype=np.uint64)
+    for p in ranks:
+        words[p >> 6] |= np.uint64(1) << np.uint64(p & 63)
+    return words
+
+
+def _step(fn, ctype, dtype, P, S, tau, t, w, g, m, pub, stale, lr, mu, n=None):
+    for name, a in (("w", w), ("g", g), ("m", m), ("pub", pub)):
+        if a.dtype != dtype or a.ndim != 2 or a.shape[0] != P or not a.flags.c_contiguous:
+            raise ValueError("%s must be a C-contiguous (P, ld) %s array" % (name, dtype))
+        if a.shape != w.shape:
+            raise ValueError("w, g, m, pub must share one shape")
+    ld = w.shape[1]
+    n = ld if n is None else n
+    words = mask_words(stale)
+    if words is not None and words.size != (P + 63) // 64:
+        raise ValueError("stale mask must hold ceil(P/64) words")
+    ptr = ctypes.POINTER(ctype)
+    _check(fn(P, S, n, ld, tau, t,
+              w.ctypes.data_as(ptr), g.ctypes.data_as(ptr), m.ctypes.data_as(ptr),
+              pub.ctypes.data_as(ptr),
+              None if words is None else words.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64)),
+              lr, mu), "step")
+
+
+def step_f32(P, S, tau, t, w, g, m, pub, stale, lr, mu, n=None) -> None:
+    """One iteration of Algorithm 2 (lines 6-17) in fp32, in place."""
+    _step(_load().oracle_step_f32, ctypes.c_float, np.float32,
+          P, S, tau, t, w, g, m, pub, stale, lr, mu, n)
+
+
+def step_f64(P, S, tau, t, w, g, m, pub, stale, lr, mu, n=None) -> None:
+    """The same iteration carried in fp64 (rounding shadow)."""
+    _step(_load().oracle_step_f64, ctypes.c_double, np.float64,
+          P, S, tau, t, w, g, m, pub, stale, lr, mu, n)
+
+
+def stale_mask(seed: int, t: int, P: int, threshold: int) -> np.ndarray:
+    """uint64 words, bit p set = process p late in iteration t."""
+    words = np.zeros((P + 63) // 64, dtype=np.uint64)
+    _check(_load().oracle_stale_mask(
+        seed, t, P, threshold, words.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64))),
+        "stale_mask")
+    return words
