@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""Benchmark of the WAGMA-SGD hot path on one MI355X.
+
+A step is one wagma_step(): local momentum-SGD update of all P replicas, group model average
+with the lateness rule (or the global average every tau-th iteration), send-buffer refresh
+(Algorithm 2 lines 6-17 with the groups of Algorithm 1).  All inputs are resident in HBM before
+the timed region.  Prints ONE JSON line on stdout; progress goes to stderr.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1..5] [--opt NAME=VALUE ...]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
+
+OPTS = {"block": 1, "nontemporal": 2, "force_stream": 3, "xcd_swizzle": 4, "tile_major": 5, "waves": 6}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def popcount(words) -> int:
+    return sum(bin(int(x)).count("1") for x in words)
+
+
+def cpu_baseline(wl, columns: int, iters: int):
+    """The CPU oracle as it stands, one thread, on a column slice of the same workload
+    (columns are independent, so a slice is the same work per replica-parameter)."""
+    import numpy as np
+    import torch
+    from oracle import wagma_oracle as orc
+    from paper_2005_00124_amd import workloads as wk
+
+    P = wl.P
+    gen = wk.make_generator(wl.seed, "cpu")
+    row = torch.empty(columns)
+    row.normal_(0.0, 0.05, generator=gen)
+    w = np.repeat(row.numpy()[None, :], P, axis=0).copy()
+    m = np.zeros_like(w)
+    pub = w.copy()
+    g = torch.empty((P, columns)).normal_(0.0, wl.grad_std, generator=gen).numpy()
+    masks = [orc.stale_mask(wl.seed, t, P, wl.stale_threshold) for t in range(iters)]
+    orc.step_f32(P, wl.S, wl.tau, 0, w.copy(), g, m.copy(), pub.copy(), masks[0], wl.lr, wl.mu)  # warm
+    t0 = time.perf_counter()
+    for t in range(iters):
+        orc.step_f32(P, wl.S, wl.tau, t, w, g, m, pub, masks[t], wl.lr, wl.mu)
+    dt = time.perf_counter() - t0
+    return {"value": P * columns * iters / dt, "unit": "replica-params/s", "cores": 1,
+            "kind": "oracle",
+            "sample": "%d-column slice of all %d rows, %d iterations (group and global, same masks), "
+                      "%.1f s single-threaded" % (columns, P, iters, dt)}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", type=int, default=4, help="1..5; 4 = the headline P=64 S=8 25.6M")
+    ap.add_argument("--opt", action="append", default=[], help="tuning knob NAME=VALUE (%s)" % ", ".join(OPTS))
+    ap.add_argument("--ld", type=int, default=None, help="row stride override (floats)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-columns", type=int, default=131072)
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU only (the P workers are rows in one GPU's HBM); "
+            "--gpus %d is not supported" % args.gpus)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2005_00124_amd import wagma as lw
+    from paper_2005_00124_amd import workloads as wk
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible; the HIP path has no CPU fallback")
+        return 2
+    if not os.path.exists(lw.LIB_PATH):
+        from paper_2005_00124_amd import build
+        build.build()
+
+    wl = wk.workload(args.workload)
+    K = wl.iters if args.steps is None else args.steps
+    W = args.warmup
+    P, S, n = wl.P, wl.S, wl.n
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    ctx = lw.Wagma(P, S, n, wl.tau)
+    if args.ld:
+        ctx.set_row_stride(args.ld)
+    for kv in args.opt:
+        k, v = kv.split("=")
+        ctx.set_option(OPTS[k], int(v))
+    ld = ctx.ld
+    log("workload %d: %s  n=%d ld=%d  buffers 4 x %.2f GB" % (wl.index, wl.name, n, ld, P * ld * 4 / 1e9))
+    w, g, m, pub = ctx.alloc()
+    wk.fill_initial_state(wl, w, m, pub)
+    wk.fill_gradients(wl, 0, g)       # one gradient slab, reused: generating it is not part of the path
+    masks = [ctx.stale_mask(wl.seed, t, wl.stale_threshold) for t in range(max(K, W))]
+    stream = torch.cuda.current_stream()
+
+    for t in range(W):
+        ctx.step(w, g, m, pub, masks[t], wl.lr, wl.mu, t)
+    torch.cuda.synchronize()
+
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(K)]
+    ends = [torch.cuda.Event(enable_timing=True) for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(K):
+        starts[t].record(stream)
+        ctx.step(w, g, m, pub, masks[t], wl.lr, wl.mu, t)
+        ends[t].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms = [starts[t].elapsed_time(ends[t]) for t in range(K)]
+    is_global = [ctx.is_global(t) for t in range(K)]
+    grp = [t for t in range(K) if not is_global[t]]
+    glb = [t for t in range(K) if is_global[t]]
+    late = [0 if is_global[t] else popcount(masks[t]) for t in range(K)]
+    # algorithmic bytes: read w, g, m and write w, m, pub for every replica-parameter
+    # (24 B), plus a 4 B send-buffer read for every late replica-parameter
+    bytes_of = [n * (24 * P + 4 * late[t]) for t in range(K)]
+    grp_ms = sum(ms[t] for t in grp)
+    glb_ms = sum(ms[t] for t in glb)
+    assert torch.isfinite(w[:, :n]).all()
+
+    if grp:
+        dom, dom_ts = "group step (S=%d member rows in registers)" % S, grp
+    else:
+        dom, dom_ts = "global step (rows streamed)", glb
+    dom_ms = sum(ms[t] for t in dom_ts)
+    achieved = sum(bytes_of[t] for t in dom_ts) / (dom_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                "avg_launch_ms": dom_ms / len(dom_ts), "launches": len(dom_ts),
+                "algorithmic_bytes_per_launch": sum(bytes_of[t] for t in dom_ts) / len(dom_ts),
+                "traffic": None}
+    out = {
+        "metric": "replica-params averaged/sec", "value": P * n * K / wall, "unit": "replica-params/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": wall * 1e3 / K,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "P": P, "S": S, "n": n, "ld": ld, "tau": wl.tau,
+                   "late_probability": wl.q, "global_steps_in_run": len(glb),
+                   "options": args.opt},
+        "hbm_gbs_all_steps": sum(bytes_of) / ((grp_ms + glb_ms) * 1e-3) / 1e9,
+        "group_step_ms": (grp_ms / len(grp)) if grp else None,
+        "global_step_ms": (glb_ms / len(glb)) if glb else None,
+        "global_step_gbs": (sum(bytes_of[t] for t in glb) / (glb_ms * 1e-3) / 1e9) if glb else None,
+        "roofline": roofline,
+    }
+    ctx.destroy()
+    del w, g, m, pub
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        log("timing the CPU oracle on a slice ...")
+        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_columns, min(K, wl.iters))
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

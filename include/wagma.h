@@ -51,7 +51,7 @@ typedef struct wagma_ctx wagma_ctx; /* opaque; owned by the library */
  * powers of two with S <= P as Section 3.3 assumes).
  *   out  host pointer that receives the context.
  *   P    1 <= P <= WAGMA_MAX_P, power of two.      S  1 <= S <= P, power of two.
- *   n    >= 1.     tau  >= 0; 0 = never average globally, 1 = every iteration.
+ *   n    1 <= n <= 2^31.     tau  >= 0; 0 = never average globally, 1 = every iteration.
  * Builds the group-schedule table (Algorithm 1 for every distinct iteration
  * residue) with a kernel on the current device, keeps it in device memory and
  * mirrors it on the host.  Synchronises the device once.  Chooses the row
@@ -135,10 +135,14 @@ int wagma_stale_mask(const wagma_ctx* ctx, uint64_t seed, int64_t iter,
 
 /* Tuning knobs; the defaults are the measured best on MI355X.  Results do not
  * depend on them (same summation order in every variant). */
-#define WAGMA_OPT_BLOCK 1        /* threads per workgroup: 128, 256, 512 or 1024      */
+#define WAGMA_OPT_BLOCK 1        /* threads per workgroup: 256 or 512                    */
 #define WAGMA_OPT_NONTEMPORAL 2  /* 0/1: non-temporal hint on loads and stores        */
 #define WAGMA_OPT_FORCE_STREAM 3 /* 0/1: use the row-streaming kernel for every S     */
-#define WAGMA_OPT_XCD_SWIZZLE 4  /* 0/1: give each of the 8 XCDs a contiguous column range */
+#define WAGMA_OPT_XCD_SWIZZLE 4  /* 0/1: give each of the 8 XCDs a contiguous range of workgroups */
+#define WAGMA_OPT_TILE_MAJOR 5   /* 0/1: consecutive workgroups walk the groups of one column
+                                    tile (1) or the column tiles of one group (0)          */
+#define WAGMA_OPT_WAVES 6        /* 2..4: wavefronts per SIMD the register budget of the
+                                    S >= 8 kernels allows                                  */
 int wagma_set_option(wagma_ctx* ctx, int option, int64_t value);
 
 /* Text for an error code (static storage). */

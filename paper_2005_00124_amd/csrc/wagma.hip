@@ -1,0 +1,645 @@
+// libwagma: the per-iteration hot path of WAGMA-SGD (arXiv 2005.00124,
+// Algorithm 2 lines 6-17 with the groups of Algorithm 1) for P model replicas
+// stored as P rows in one MI355X's HBM.  gfx950 only.
+//
+// Work decomposition.  Every operation of the step is elementwise in the
+// parameter index; only the P rows interact.  A thread therefore owns one
+// 16-byte column slice (4 consecutive parameters) of one group and does the
+// whole iteration for it: it loads W, G and the momentum of every member row
+// (plus the send buffer of late members), applies the local update, sums the
+// contributions in butterfly-phase order, and stores W, momentum and send
+// buffer.  Each element is read once and written once, by one thread, so the
+// in-place update needs no synchronisation, no LDS and no second buffer, and a
+// wavefront's accesses are 1 KiB contiguous per row.  The step is bound by HBM
+// bandwidth (about 0.25 flop per byte): no matrix cores are involved.
+//
+// Two kernels cover all group sizes:
+//   step_rows_in_registers<S>  S <= 8 member rows are held in registers
+//                              (3*S independent 128-bit loads in flight per lane).
+//   step_rows_streamed         any S >= 8: member rows are streamed 8 at a time,
+//                              the partial sums kept on a log2(S/8)-deep pairwise
+//                              stack; late members re-read their own W' from the
+//                              send buffer they just wrote.
+// The global average (Algorithm 2 lines 15-16) is the same computation with
+// one group of all P ranks in natural order and nobody late.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "wagma.h"
+
+namespace {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr int kMaskWords = WAGMA_MAX_P / 64;
+constexpr int kChunk = 8;       // rows per chunk of the streaming kernel
+constexpr int kStackDepth = 7;  // log2(WAGMA_MAX_P / kChunk)
+constexpr int kNumXcd = 8;      // accelerator complex dies of an MI355X
+constexpr int64_t kMaxN = int64_t(1) << 31;
+
+thread_local int g_last_hip_error = 0;
+
+struct StepParams {
+    float* w;
+    const float* g;
+    float* m;
+    float* pub;
+    const int32_t* table;  // P ranks, group-major, butterfly member order
+    int64_t ld;            // row stride in floats
+    int64_t nvec;          // 16-byte column slices per row = ceil(n/4)
+    int64_t tiles;         // workgroups per group = ceil(nvec / block)
+    int64_t blocks;        // groups * tiles (grid may be padded beyond this)
+    uint64_t late[kMaskWords];
+    float lr;
+    float mu;
+    float inv_members;     // 1/S (or 1/P): exact, a power of two
+    float members_plus_1;  // S + 1
+    int members;           // S, or P in a global iteration
+    int log2_chunks;       // log2(members / kChunk) for the streaming kernel
+    int swizzle;           // 1: contiguous block range per XCD
+    int tile_major;        // 1: consecutive blocks walk the groups of one column tile
+};
+
+template <bool NT>
+__device__ __forceinline__ v4f load4(const float* p)
+{
+    if (NT)
+        return __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+    return *reinterpret_cast<const v4f*>(p);
+}
+
+template <bool NT>
+__device__ __forceinline__ void store4(float* p, v4f v)
+{
+    if (NT)
+        __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(p));
+    else
+        *reinterpret_cast<v4f*>(p) = v;
+}
+
+// a*b + c with one rounding per lane (Algorithm 2 lines 6-7 are two of these).
+__device__ __forceinline__ v4f fma4(float a, v4f b, v4f c)
+{
+    v4f r;
+    r.x = __builtin_fmaf(a, b.x, c.x);
+    r.y = __builtin_fmaf(a, b.y, c.y);
+    r.z = __builtin_fmaf(a, b.z, c.z);
+    r.w = __builtin_fmaf(a, b.w, c.w);
+    return r;
+}
+
+__device__ __forceinline__ bool is_late(const StepParams& p, int rank)
+{
+    return (p.late[rank >> 6] >> (rank & 63)) & 1u;
+}
+
+// Balanced pairwise sum of N = 2^k values: adjacent members first, i.e. the
+// butterfly phases of Section 3.3 in the order Algorithm 1 runs them.
+template <int N>
+__device__ __forceinline__ v4f tree_sum(const v4f* c)
+{
+    if constexpr (N == 1) {
+        return c[0];
+    } else {
+        v4f left = tree_sum<N / 2>(c);
+        v4f right = tree_sum<N / 2>(c + N / 2);
+        return left + right;
+    }
+}
+
+// Which (group, column tile) does this workgroup own?  Workgroups are handed
+// to the 8 XCDs round-robin; with `swizzle` each XCD instead walks one
+// contiguous eighth of the work.  Returns false for padding workgroups.
+__device__ __forceinline__ bool decode_block(const StepParams& p, int64_t& group, int64_t& tile)
+{
+    int64_t b = blockIdx.x;
+    if (p.swizzle) {
+        const int64_t per_xcd = (p.blocks + kNumXcd - 1) / kNumXcd;
+        b = (b % kNumXcd) * per_xcd + b / kNumXcd;
+    }
+    if (b >= p.blocks)
+        return false;
+    if (p.tile_major) {
+        const int64_t groups = p.blocks / p.tiles;
+        group = b % groups;
+        tile = b / groups;
+    } else {
+        group = b / p.tiles;
+        tile = b % p.tiles;
+    }
+    return true;
+}
+
+template <int S, bool NT, int BLOCK, int WAVES>
+__global__ void __launch_bounds__(BLOCK, WAVES) step_rows_in_registers(const StepParams p)
+{
+    int64_t group, tile;
+    if (!decode_block(p, group, tile))
+        return;
+    const int64_t col = tile * BLOCK + threadIdx.x;
+    if (col >= p.nvec)
+        return;
+    const int32_t* member = p.table + group * S;
+    // Row bases are wave-uniform (scalar registers); the lane adds one 32-bit offset.
+    const uint32_t lane_at = (uint32_t)col * 4u;
+
+    bool late[S];
+    int64_t row_at[S];
+    v4f wv[S], gv[S], mv[S], contrib[S];
+#pragma unroll
+    for (int e = 0; e < S; ++e) {
+        const int rank = member[e];
+        row_at[e] = (int64_t)rank * p.ld;
+        late[e] = is_late(p, rank);
+        wv[e] = load4<NT>(p.w + row_at[e] + lane_at);
+        gv[e] = load4<NT>(p.g + row_at[e] + lane_at);
+        mv[e] = load4<NT>(p.m + row_at[e] + lane_at);
+    }
+#pragma unroll
+    for (int e = 0; e < S; ++e)
+        if (late[e])
+            contrib[e] = load4<NT>(p.pub + row_at[e] + lane_at);  // send buffer of a late process
+
+#pragma unroll
+    for (int e = 0; e < S; ++e) {
+        const v4f m_new = fma4(p.mu, mv[e], gv[e]);
+        wv[e] = fma4(-p.lr, m_new, wv[e]);  // W'
+        store4<NT>(p.m + row_at[e] + lane_at, m_new);
+        store4<NT>(p.pub + row_at[e] + lane_at, wv[e]);
+        if (!late[e])
+            contrib[e] = wv[e];
+    }
+    const v4f w_sum = tree_sum<S>(contrib);
+#pragma unroll
+    for (int e = 0; e < S; ++e) {
+        v4f out;
+        if (late[e])
+            out = (w_sum + wv[e]) / p.members_plus_1;
+        else
+            out = w_sum * p.inv_members;
+        store4<NT>(p.w + row_at[e] + lane_at, out);
+    }
+}
+
+template <bool NT, int BLOCK, int WAVES>
+__global__ void __launch_bounds__(BLOCK, WAVES) step_rows_streamed(const StepParams p)
+{
+    int64_t group, tile;
+    if (!decode_block(p, group, tile))
+        return;
+    const int64_t col = tile * BLOCK + threadIdx.x;
+    if (col >= p.nvec)
+        return;
+    const int32_t* member = p.table + group * p.members;
+    const uint32_t lane_at = (uint32_t)col * 4u;
+    const int chunks = p.members / kChunk;
+
+    v4f stack[kStackDepth];
+    v4f acc;
+    for (int c = 0; c < chunks; ++c) {
+        int64_t row_at[kChunk];
+        bool late[kChunk];
+        v4f wv[kChunk], gv[kChunk], mv[kChunk], contrib[kChunk];
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i) {
+            const int rank = member[c * kChunk + i];
+            row_at[i] = (int64_t)rank * p.ld;
+            late[i] = is_late(p, rank);
+            wv[i] = load4<NT>(p.w + row_at[i] + lane_at);
+            gv[i] = load4<NT>(p.g + row_at[i] + lane_at);
+            mv[i] = load4<NT>(p.m + row_at[i] + lane_at);
+        }
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i)
+            if (late[i])
+                contrib[i] = load4<NT>(p.pub + row_at[i] + lane_at);
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i) {
+            const v4f m_new = fma4(p.mu, mv[i], gv[i]);
+            wv[i] = fma4(-p.lr, m_new, wv[i]);
+            store4<NT>(p.m + row_at[i] + lane_at, m_new);
+            store4<NT>(p.pub + row_at[i] + lane_at, wv[i]);
+            if (!late[i])
+                contrib[i] = wv[i];
+        }
+        acc = tree_sum<kChunk>(contrib);
+        // Binary-counter carry: after chunk c the stack holds one partial sum per set
+        // bit of c+1, so equal-sized neighbours are always added left + right.
+        bool carry = true;
+#pragma unroll
+        for (int l = 0; l < kStackDepth; ++l) {
+            if (carry) {
+                if ((c >> l) & 1) {
+                    acc = stack[l] + acc;
+                } else {
+                    stack[l] = acc;
+                    carry = false;
+                }
+            }
+        }
+    }
+    v4f w_sum = acc;
+#pragma unroll
+    for (int l = 0; l < kStackDepth; ++l)
+        if (l == p.log2_chunks)
+            w_sum = stack[l];
+    const v4f fresh = w_sum * p.inv_members;
+
+    for (int e = 0; e < p.members; ++e) {
+        const int rank = member[e];
+        const int64_t row_at = (int64_t)rank * p.ld;
+        v4f out = fresh;
+        if (is_late(p, rank)) {
+            // W' of this member: this thread stored it to the send buffer above.
+            const v4f w_prime = load4<false>(p.pub + row_at + lane_at);
+            out = (w_sum + w_prime) / p.members_plus_1;
+        }
+        store4<NT>(p.w + row_at + lane_at, out);
+    }
+}
+
+// Schedule table: rows 0..period-1 hold the groups of iterations t = residue
+// (mod period) after Algorithm 1; row `period` is the single group 0..P-1 of a
+// global iteration.  Slot k*S + e of a row is member e of the group with the
+// k-th smallest base.  The phase bits are b_r = (t*g + r) mod G, r = 0..g-1
+// (Algorithm 1 lines 3, 6, 14); the base has those bits clear and the bits of k
+// spread over the remaining positions; member e sets phase bit b_r iff digit r
+// of e is set.
+__global__ void build_schedule_table(int32_t* table, int P, int G, int g, int period)
+{
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (period + 1) * P)
+        return;
+    const int residue = idx / P;
+    const int slot = idx % P;
+    if (residue == period) {
+        table[idx] = slot;
+        return;
+    }
+    const int k = slot >> g;
+    const int e = slot & ((1 << g) - 1);
+    int phase_mask = 0, member_bits = 0;
+    for (int r = 0; r < g; ++r) {
+        const int b = (residue * g + r) % G;
+        phase_mask |= 1 << b;
+        if ((e >> r) & 1)
+            member_bits |= 1 << b;
+    }
+    int base = 0, rest = k;
+    for (int bit = 0; bit < G; ++bit) {
+        if (!((phase_mask >> bit) & 1)) {
+            base |= (rest & 1) << bit;
+            rest >>= 1;
+        }
+    }
+    table[idx] = base | member_bits;
+}
+
+int exact_log2(int64_t x)
+{
+    if (x < 1 || (x & (x - 1)) != 0)
+        return -1;
+    int l = 0;
+    while ((int64_t(1) << l) < x)
+        ++l;
+    return l;
+}
+
+int gcd_int(int a, int b)
+{
+    while (b) {
+        const int r = a % b;
+        a = b;
+        b = r;
+    }
+    return a;
+}
+
+int hip_failed(hipError_t e)
+{
+    g_last_hip_error = (int)e;
+    return WAGMA_EHIP;
+}
+
+// WAVES = resident wavefronts per SIMD the register allocation must allow
+// (2, 3 or 4: at most 256, 168 or 128 vector registers per lane).
+template <int S, bool NT, int BLOCK, int WAVES>
+void launch_registers(const StepParams& p, unsigned grid, hipStream_t stream)
+{
+    hipLaunchKernelGGL((step_rows_in_registers<S, NT, BLOCK, WAVES>), dim3(grid), dim3(BLOCK), 0,
+                       stream, p);
+}
+
+template <bool NT, int BLOCK, int WAVES>
+void launch_variant(const StepParams& p, bool streamed, unsigned grid, hipStream_t stream)
+{
+    if (streamed) {
+        hipLaunchKernelGGL((step_rows_streamed<NT, BLOCK, WAVES>), dim3(grid), dim3(BLOCK), 0,
+                           stream, p);
+        return;
+    }
+    switch (p.members) {
+    case 1: launch_registers<1, NT, BLOCK, 4>(p, grid, stream); break;
+    case 2: launch_registers<2, NT, BLOCK, 4>(p, grid, stream); break;
+    case 4: launch_registers<4, NT, BLOCK, 4>(p, grid, stream); break;
+    default: launch_registers<8, NT, BLOCK, WAVES>(p, grid, stream); break;
+    }
+}
+
+template <bool NT, int BLOCK>
+void launch_waves(const StepParams& p, bool streamed, int waves, unsigned grid, hipStream_t stream)
+{
+    switch (waves) {
+    case 2: launch_variant<NT, BLOCK, 2>(p, streamed, grid, stream); break;
+    case 3: launch_variant<NT, BLOCK, 3>(p, streamed, grid, stream); break;
+    default: launch_variant<NT, BLOCK, 4>(p, streamed, grid, stream); break;
+    }
+}
+
+template <bool NT>
+void launch_block(const StepParams& p, bool streamed, int block, int waves, unsigned grid,
+                  hipStream_t stream)
+{
+    if (block == 512)
+        launch_waves<NT, 512>(p, streamed, waves, grid, stream);
+    else
+        launch_waves<NT, 256>(p, streamed, waves, grid, stream);
+}
+
+}  // namespace
+
+struct wagma_ctx {
+    int P, S, G, g, tau, period, device;
+    int64_t n, ld;
+    int32_t* d_table;  // (period + 1) * P, device
+    int32_t* h_table;  // host mirror
+    int opt_block, opt_nontemporal, opt_force_stream, opt_swizzle, opt_tile_major, opt_waves;
+};
+
+extern "C" {
+
+int wagma_create(wagma_ctx** out, int P, int S, int64_t n, int tau)
+{
+    if (!out)
+        return WAGMA_EINVAL;
+    *out = nullptr;
+    const int G = exact_log2(P), g = exact_log2(S);
+    // lanes address their column with a 32-bit float offset inside a row
+    if (G < 0 || g < 0 || P > WAGMA_MAX_P || S > P || n < 1 || tau < 0 || n > kMaxN)
+        return WAGMA_EINVAL;
+
+    wagma_ctx* ctx = new (std::nothrow) wagma_ctx();
+    if (!ctx)
+        return WAGMA_ENOMEM;
+    ctx->P = P;
+    ctx->S = S;
+    ctx->G = G;
+    ctx->g = g;
+    ctx->tau = tau;
+    ctx->n = n;
+    ctx->period = (g == 0 || G == 0) ? 1 : G / gcd_int(g, G);
+    // Rows start on 256-byte boundaries so that every wavefront access is aligned.
+    ctx->ld = (n + 63) / 64 * 64;
+    ctx->opt_block = 256;
+    ctx->opt_nontemporal = 1;
+    ctx->opt_force_stream = 0;
+    ctx->opt_swizzle = 0;
+    ctx->opt_tile_major = 0;
+    ctx->opt_waves = 3;
+    ctx->d_table = nullptr;
+    ctx->h_table = nullptr;
+
+    const size_t entries = (size_t)(ctx->period + 1) * (size_t)P;
+    hipError_t e = hipGetDevice(&ctx->device);
+    if (e != hipSuccess) {
+        delete ctx;
+        return hip_failed(e);
+    }
+    ctx->h_table = (int32_t*)std::malloc(entries * sizeof(int32_t));
+    if (!ctx->h_table) {
+        delete ctx;
+        return WAGMA_ENOMEM;
+    }
+    e = hipMalloc((void**)&ctx->d_table, entries * sizeof(int32_t));
+    if (e != hipSuccess) {
+        std::free(ctx->h_table);
+        delete ctx;
+        g_last_hip_error = (int)e;
+        return e == hipErrorOutOfMemory ? WAGMA_ENOMEM : WAGMA_EHIP;
+    }
+    const unsigned threads = 256;
+    const unsigned grid = (unsigned)((entries + threads - 1) / threads);
+    hipLaunchKernelGGL(build_schedule_table, dim3(grid), dim3(threads), 0, (hipStream_t) nullptr,
+                       ctx->d_table, P, G, g, ctx->period);
+    e = hipGetLastError();
+    if (e == hipSuccess)
+        e = hipMemcpy(ctx->h_table, ctx->d_table, entries * sizeof(int32_t), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) {
+        (void)hipFree(ctx->d_table);
+        std::free(ctx->h_table);
+        delete ctx;
+        return hip_failed(e);
+    }
+    *out = ctx;
+    return WAGMA_OK;
+}
+
+int wagma_destroy(wagma_ctx* ctx)
+{
+    if (!ctx)
+        return WAGMA_OK;
+    int rc = WAGMA_OK;
+    if (ctx->d_table) {
+        const hipError_t e = hipFree(ctx->d_table);
+        if (e != hipSuccess)
+            rc = hip_failed(e);
+    }
+    std::free(ctx->h_table);
+    delete ctx;
+    return rc;
+}
+
+int64_t wagma_row_stride(const wagma_ctx* ctx)
+{
+    return ctx ? ctx->ld : (int64_t)WAGMA_EINVAL;
+}
+
+int wagma_set_row_stride(wagma_ctx* ctx, int64_t ld)
+{
+    if (!ctx || ld % 4 != 0 || ld < (ctx->n + 3) / 4 * 4 || ld > 2 * kMaxN)
+        return WAGMA_EINVAL;
+    ctx->ld = ld;
+    return WAGMA_OK;
+}
+
+int wagma_schedule_period(const wagma_ctx* ctx)
+{
+    return ctx ? ctx->period : WAGMA_EINVAL;
+}
+
+int wagma_is_global_iteration(const wagma_ctx* ctx, int64_t iter)
+{
+    if (!ctx || iter < 0 || iter == INT64_MAX)
+        return WAGMA_EINVAL;
+    return (ctx->tau > 0 && (iter + 1) % ctx->tau == 0) ? 1 : 0;
+}
+
+int wagma_group_schedule(const wagma_ctx* ctx, int64_t iter, const int32_t** dev_table,
+                         const int32_t** host_table)
+{
+    const int global = wagma_is_global_iteration(ctx, iter);
+    if (global < 0)
+        return global;
+    const int64_t row = global ? ctx->period : iter % ctx->period;
+    if (dev_table)
+        *dev_table = ctx->d_table + row * ctx->P;
+    if (host_table)
+        *host_table = ctx->h_table + row * ctx->P;
+    return WAGMA_OK;
+}
+
+int wagma_step(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub,
+               const uint64_t* stale_mask, float lr, float mu, int64_t iter, void* stream)
+{
+    const int global = wagma_is_global_iteration(ctx, iter);
+    if (global < 0)
+        return global;
+    if (!w || !g || !m || !pub)
+        return WAGMA_EINVAL;
+    if ((((uintptr_t)w) | ((uintptr_t)g) | ((uintptr_t)m) | ((uintptr_t)pub)) & 15u)
+        return WAGMA_EINVAL;
+    int device = -1;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess)
+        return hip_failed(e);
+    if (device != ctx->device)
+        return WAGMA_EINVAL;
+
+    StepParams p;
+    p.w = w;
+    p.g = g;
+    p.m = m;
+    p.pub = pub;
+    p.ld = ctx->ld;
+    p.nvec = (ctx->n + 3) / 4;
+    p.lr = lr;
+    p.mu = mu;
+    p.members = global ? ctx->P : ctx->S;
+    p.inv_members = 1.0f / (float)p.members;
+    p.members_plus_1 = (float)(p.members + 1);
+    p.swizzle = ctx->opt_swizzle;
+    p.tile_major = ctx->opt_tile_major;
+    const int32_t* table = nullptr;
+    wagma_group_schedule(ctx, iter, &table, nullptr);
+    p.table = table;
+    std::memset(p.late, 0, sizeof(p.late));
+    if (!global && stale_mask) {
+        const int words = (ctx->P + 63) / 64;
+        for (int k = 0; k < words; ++k)
+            p.late[k] = stale_mask[k];
+        if (ctx->P < 64)
+            p.late[0] &= (UINT64_C(1) << ctx->P) - 1;
+    }
+
+    const bool streamed = p.members > kChunk || (ctx->opt_force_stream && p.members == kChunk);
+    p.log2_chunks = streamed ? exact_log2(p.members / kChunk) : 0;
+    const int block = ctx->opt_block;
+    p.tiles = (p.nvec + block - 1) / block;
+    p.blocks = (int64_t)(ctx->P / p.members) * p.tiles;
+    int64_t grid = p.blocks;
+    if (p.swizzle)
+        grid = (grid + kNumXcd - 1) / kNumXcd * kNumXcd;
+    if (grid > 0x7fffffff)
+        return WAGMA_EINVAL;
+
+    if (ctx->opt_nontemporal)
+        launch_block<true>(p, streamed, block, ctx->opt_waves, (unsigned)grid, (hipStream_t)stream);
+    else
+        launch_block<false>(p, streamed, block, ctx->opt_waves, (unsigned)grid, (hipStream_t)stream);
+    e = hipGetLastError();
+    if (e != hipSuccess)
+        return hip_failed(e);
+    return WAGMA_OK;
+}
+
+// 64-bit finaliser of the public splitmix64 generator (Steele, Lea, Flood 2014).
+static uint64_t mix64(uint64_t z)
+{
+    z = (z ^ (z >> 30)) * UINT64_C(0xBF58476D1CE4E5B9);
+    z = (z ^ (z >> 27)) * UINT64_C(0x94D049BB133111EB);
+    return z ^ (z >> 31);
+}
+
+int wagma_stale_mask(const wagma_ctx* ctx, uint64_t seed, int64_t iter, uint32_t threshold,
+                     uint64_t* mask_words)
+{
+    if (!ctx || iter < 0 || !mask_words)
+        return WAGMA_EINVAL;
+    const int words = (ctx->P + 63) / 64;
+    const uint64_t iter_key = mix64(seed + ((uint64_t)iter + 1) * UINT64_C(0x9E3779B97F4A7C15));
+    for (int k = 0; k < words; ++k) {
+        uint64_t word = 0;
+        for (int b = 0; b < 64 && k * 64 + b < ctx->P; ++b) {
+            const uint64_t rank = (uint64_t)(k * 64 + b);
+            const uint64_t h = mix64(iter_key + (rank + 1) * UINT64_C(0xD1B54A32D192ED03));
+            if ((uint32_t)(h >> 32) < threshold)
+                word |= UINT64_C(1) << b;
+        }
+        mask_words[k] = word;
+    }
+    return WAGMA_OK;
+}
+
+int wagma_set_option(wagma_ctx* ctx, int option, int64_t value)
+{
+    if (!ctx)
+        return WAGMA_EINVAL;
+    switch (option) {
+    case WAGMA_OPT_BLOCK:
+        if (value != 256 && value != 512)
+            return WAGMA_EINVAL;
+        ctx->opt_block = (int)value;
+        return WAGMA_OK;
+    case WAGMA_OPT_NONTEMPORAL:
+        ctx->opt_nontemporal = value != 0;
+        return WAGMA_OK;
+    case WAGMA_OPT_FORCE_STREAM:
+        ctx->opt_force_stream = value != 0;
+        return WAGMA_OK;
+    case WAGMA_OPT_XCD_SWIZZLE:
+        ctx->opt_swizzle = value != 0;
+        return WAGMA_OK;
+    case WAGMA_OPT_TILE_MAJOR:
+        ctx->opt_tile_major = value != 0;
+        return WAGMA_OK;
+    case WAGMA_OPT_WAVES:
+        if (value < 2 || value > 4)
+            return WAGMA_EINVAL;
+        ctx->opt_waves = (int)value;
+        return WAGMA_OK;
+    default:
+        return WAGMA_EINVAL;
+    }
+}
+
+const char* wagma_strerror(int code)
+{
+    switch (code) {
+    case WAGMA_OK: return "success";
+    case WAGMA_EINVAL: return "invalid argument";
+    case WAGMA_EHIP: return "HIP runtime error (see wagma_last_hip_error)";
+    case WAGMA_ENOMEM: return "out of memory";
+    default: return "unknown libwagma error";
+    }
+}
+
+int wagma_last_hip_error(void)
+{
+    return g_last_hip_error;
+}
+
+}  // extern "C"

@@ -1,0 +1,227 @@
+"""Thin ctypes binding of the libwagma C-ABI (``include/wagma.h``).
+
+Argument marshalling only: every step of the path runs in the HIP kernels of
+``libwagma.so``.  PyTorch tensors are used as device allocations (their
+``data_ptr()``) and for the current HIP stream; nothing is computed in Python
+and there is no CPU fallback — ``load()`` raises if the library is not built.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libwagma.so")
+
+WAGMA_OK, WAGMA_EINVAL, WAGMA_EHIP, WAGMA_ENOMEM = 0, -1, -2, -3
+WAGMA_MAX_P = 1024
+WAGMA_OPT_BLOCK, WAGMA_OPT_NONTEMPORAL, WAGMA_OPT_FORCE_STREAM = 1, 2, 3
+WAGMA_OPT_XCD_SWIZZLE, WAGMA_OPT_TILE_MAJOR, WAGMA_OPT_WAVES = 4, 5, 6
+
+# name -> (restype, argtypes): every symbol include/wagma.h declares
+_i32pp = ctypes.POINTER(ctypes.POINTER(ctypes.c_int32))
+_u64p = ctypes.POINTER(ctypes.c_uint64)
+SYMBOLS = {
+    "wagma_create": (ctypes.c_int, [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_int,
+                                    ctypes.c_int64, ctypes.c_int]),
+    "wagma_destroy": (ctypes.c_int, [ctypes.c_void_p]),
+    "wagma_row_stride": (ctypes.c_int64, [ctypes.c_void_p]),
+    "wagma_set_row_stride": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int64]),
+    "wagma_schedule_period": (ctypes.c_int, [ctypes.c_void_p]),
+    "wagma_group_schedule": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int64, _i32pp, _i32pp]),
+    "wagma_is_global_iteration": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int64]),
+    "wagma_step": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                  ctypes.c_void_p, _u64p, ctypes.c_float, ctypes.c_float,
+                                  ctypes.c_int64, ctypes.c_void_p]),
+    "wagma_stale_mask": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int64,
+                                        ctypes.c_uint32, _u64p]),
+    "wagma_set_option": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64]),
+    "wagma_strerror": (ctypes.c_char_p, [ctypes.c_int]),
+    "wagma_last_hip_error": (ctypes.c_int, []),
+}
+
+_lib = None
+
+
+class WagmaError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        text = load().wagma_strerror(code).decode()
+        hip = load().wagma_last_hip_error() if code == WAGMA_EHIP else 0
+        super().__init__("%s: %s (code %d%s)" % (what, text, code, ", hipError %d" % hip if hip else ""))
+
+
+def load() -> ctypes.CDLL:
+    """Load libwagma.so; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "libwagma.so is not built: run `python -m paper_2005_00124_amd.build` "
+                "(there is no CPU fallback)")
+        # PyTorch ships its own HIP runtime (same soname).  Import it first so that this
+        # library binds to the runtime that owns the tensors and streams it is handed.
+        import torch  # noqa: F401
+        lib = ctypes.CDLL(LIB_PATH)
+        for name, (restype, argtypes) in SYMBOLS.items():
+            fn = getattr(lib, name)
+            fn.restype, fn.argtypes = restype, argtypes
+        _lib = lib
+    return _lib
+
+
+def _check(code: int, what: str) -> None:
+    if code != WAGMA_OK:
+        raise WagmaError(code, what)
+
+
+def _ptr(x) -> int:
+    return x if isinstance(x, int) else x.data_ptr()
+
+
+def _current_stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+# ---- the C-ABI, one function per entry point, same names -------------------
+
+def wagma_create(P: int, S: int, n: int, tau: int) -> int:
+    out = ctypes.c_void_p()
+    _check(load().wagma_create(ctypes.byref(out), P, S, n, tau), "wagma_create")
+    return out.value
+
+
+def wagma_destroy(ctx: int) -> None:
+    _check(load().wagma_destroy(ctx), "wagma_destroy")
+
+
+def wagma_row_stride(ctx: int) -> int:
+    ld = load().wagma_row_stride(ctx)
+    if ld < 0:
+        raise WagmaError(int(ld), "wagma_row_stride")
+    return int(ld)
+
+
+def wagma_set_row_stride(ctx: int, ld: int) -> None:
+    _check(load().wagma_set_row_stride(ctx, ld), "wagma_set_row_stride")
+
+
+def wagma_schedule_period(ctx: int) -> int:
+    period = load().wagma_schedule_period(ctx)
+    if period < 0:
+        raise WagmaError(period, "wagma_schedule_period")
+    return period
+
+
+def wagma_is_global_iteration(ctx: int, it: int) -> bool:
+    rc = load().wagma_is_global_iteration(ctx, it)
+    if rc < 0:
+        raise WagmaError(rc, "wagma_is_global_iteration")
+    return bool(rc)
+
+
+def wagma_group_schedule(ctx: int, it: int, P: int):
+    """Returns (device pointer as int, host table as a read-only int32 numpy view of P entries)."""
+    dev = ctypes.POINTER(ctypes.c_int32)()
+    host = ctypes.POINTER(ctypes.c_int32)()
+    _check(load().wagma_group_schedule(ctx, it, ctypes.byref(dev), ctypes.byref(host)),
+           "wagma_group_schedule")
+    table = np.ctypeslib.as_array(host, shape=(P,))
+    table.flags.writeable = False
+    return ctypes.cast(dev, ctypes.c_void_p).value, table
+
+
+def wagma_step(ctx: int, w, g, m, pub, stale_mask: Optional[np.ndarray], lr: float, mu: float,
+               it: int, stream: Optional[int] = None) -> None:
+    """w, g, m, pub: torch CUDA tensors (or raw device addresses).  stale_mask: uint64 words or None."""
+    mask = None
+    if stale_mask is not None:
+        stale_mask = np.ascontiguousarray(stale_mask, dtype=np.uint64)
+        mask = stale_mask.ctypes.data_as(_u64p)
+    if stream is None:
+        stream = _current_stream()
+    _check(load().wagma_step(ctx, _ptr(w), _ptr(g), _ptr(m), _ptr(pub), mask, lr, mu, it, stream),
+           "wagma_step")
+
+
+def wagma_stale_mask(ctx: int, seed: int, it: int, threshold: int, P: int) -> np.ndarray:
+    words = np.zeros((P + 63) // 64, dtype=np.uint64)
+    _check(load().wagma_stale_mask(ctx, seed, it, threshold, words.ctypes.data_as(_u64p)),
+           "wagma_stale_mask")
+    return words
+
+
+def wagma_set_option(ctx: int, option: int, value: int) -> None:
+    _check(load().wagma_set_option(ctx, option, value), "wagma_set_option")
+
+
+# ---- convenience wrapper ------------------------------------------------------
+
+class Wagma:
+    """Owns one wagma_ctx; checks tensor shapes on the host before a kernel sees them."""
+
+    def __init__(self, P: int, S: int, n: int, tau: int):
+        self.P, self.S, self.n, self.tau = P, S, n, tau
+        self.ctx = wagma_create(P, S, n, tau)
+
+    @property
+    def ld(self) -> int:
+        return wagma_row_stride(self.ctx)
+
+    def set_row_stride(self, ld: int) -> None:
+        wagma_set_row_stride(self.ctx, ld)
+
+    def set_option(self, option: int, value: int) -> None:
+        wagma_set_option(self.ctx, option, value)
+
+    @property
+    def period(self) -> int:
+        return wagma_schedule_period(self.ctx)
+
+    def is_global(self, it: int) -> bool:
+        return wagma_is_global_iteration(self.ctx, it)
+
+    def group_schedule(self, it: int):
+        return wagma_group_schedule(self.ctx, it, self.P)
+
+    def stale_mask(self, seed: int, it: int, threshold: int) -> np.ndarray:
+        return wagma_stale_mask(self.ctx, seed, it, threshold, self.P)
+
+    def alloc(self, device="cuda"):
+        """Four (P, ld) fp32 device buffers w, g, m, pub (uninitialised)."""
+        import torch
+        return tuple(torch.empty((self.P, self.ld), dtype=torch.float32, device=device)
+                     for _ in range(4))
+
+    def _validate(self, *tensors) -> None:
+        import torch
+        ld = self.ld
+        for t in tensors:
+            if not isinstance(t, torch.Tensor):
+                raise TypeError("expected torch tensors")
+            if (t.dtype != torch.float32 or not t.is_cuda or t.dim() != 2
+                    or t.shape[0] != self.P or t.shape[1] != ld or not t.is_contiguous()):
+                raise ValueError("buffers must be contiguous CUDA fp32 tensors of shape (P, ld) = (%d, %d)"
+                                 % (self.P, ld))
+
+    def step(self, w, g, m, pub, stale_mask, lr: float, mu: float, it: int,
+             stream: Optional[int] = None) -> None:
+        self._validate(w, g, m, pub)
+        if stale_mask is not None and len(stale_mask) != (self.P + 63) // 64:
+            raise ValueError("stale_mask must hold ceil(P/64) words")
+        wagma_step(self.ctx, w, g, m, pub, stale_mask, lr, mu, it, stream)
+
+    def destroy(self) -> None:
+        if self.ctx:
+            wagma_destroy(self.ctx)
+            self.ctx = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.destroy()

@@ -1,0 +1,68 @@
+"""The C-ABI library loads and exports every symbol include/wagma.h declares; host-only
+argument checks answer without a GPU.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2005_00124_amd import wagma as libwagma
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(libwagma.LIB_PATH):
+        from paper_2005_00124_amd import build
+        build.build()
+    return libwagma.load()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "wagma.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(wagma_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported_and_bound(lib):
+    names = declared_symbols()
+    assert "wagma_step" in names and "wagma_create" in names and len(names) >= 12
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(libwagma.SYMBOLS) == names
+
+
+def test_header_constants_match_binding():
+    text = open(os.path.join(ROOT, "include", "wagma.h")).read()
+    for name in ("WAGMA_OK", "WAGMA_EINVAL", "WAGMA_EHIP", "WAGMA_ENOMEM", "WAGMA_MAX_P",
+                 "WAGMA_OPT_BLOCK", "WAGMA_OPT_NONTEMPORAL", "WAGMA_OPT_FORCE_STREAM",
+                 "WAGMA_OPT_XCD_SWIZZLE", "WAGMA_OPT_TILE_MAJOR", "WAGMA_OPT_WAVES"):
+        value = re.search(r"#define\s+%s\s+\(?(-?\d+)\)?" % name, text).group(1)
+        assert int(value) == getattr(libwagma, name), name
+
+
+def test_host_side_argument_checks(lib):
+    out = ctypes.c_void_p()
+    bad = [(6, 2, 10, 1), (8, 3, 10, 1), (4, 8, 10, 1), (0, 1, 10, 1), (2048, 2, 10, 1),
+           (4, 2, 0, 1), (4, 2, 10, -1), (4, 0, 10, 1)]
+    for P, S, n, tau in bad:
+        assert lib.wagma_create(ctypes.byref(out), P, S, n, tau) == libwagma.WAGMA_EINVAL
+        assert out.value is None
+    assert lib.wagma_create(None, 4, 2, 10, 1) == libwagma.WAGMA_EINVAL
+    assert lib.wagma_destroy(None) == libwagma.WAGMA_OK
+    assert lib.wagma_row_stride(None) == libwagma.WAGMA_EINVAL
+    assert lib.wagma_schedule_period(None) == libwagma.WAGMA_EINVAL
+    assert lib.wagma_is_global_iteration(None, 0) == libwagma.WAGMA_EINVAL
+    assert lib.wagma_step(None, None, None, None, None, None, 0.1, 0.9, 0, None) == libwagma.WAGMA_EINVAL
+    assert lib.wagma_set_option(None, 1, 256) == libwagma.WAGMA_EINVAL
+    assert lib.wagma_strerror(0) == b"success"
+    assert b"invalid" in lib.wagma_strerror(libwagma.WAGMA_EINVAL)
+    assert b"unknown" in lib.wagma_strerror(-99)
+
+
+def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(libwagma, "_lib", None)
+    monkeypatch.setattr(libwagma, "LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        libwagma.load()

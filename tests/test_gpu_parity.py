@@ -1,0 +1,352 @@
+"""GPU parity: libwagma (through its C-ABI) against the CPU oracle on the same seeded inputs.
+
+Bar: group schedules and lateness masks bit-exact; w, m and pub bit-exact too, because the
+kernels take the oracle's summation order (the looser bound of 1e-6 * max|w| is asserted as
+well, against the fp64 shadow).  Each case prints its name before touching the GPU.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import wagma_oracle as orc
+from paper_2005_00124_amd import wagma as lw
+from paper_2005_00124_amd import workloads as wk
+
+pytestmark = pytest.mark.gpu
+
+LR, MU = 0.1, 0.9
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def bits(a):
+    return np.ascontiguousarray(a).view(np.uint32)
+
+
+def assert_same_bits(have, want, what):
+    if not np.array_equal(bits(have), bits(want)):
+        bad = np.argwhere(bits(have) != bits(want))
+        i = tuple(bad[0])
+        raise AssertionError("%s differs at %d places, first at %s: gpu %r oracle %r"
+                             % (what, len(bad), i, have[i], want[i]))
+
+
+def random_state(P, ld, n, seed, device="cuda"):
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    w = torch.randn((P, ld), generator=gen, device=device) * 0.05
+    m = torch.randn((P, ld), generator=gen, device=device) * 0.01
+    pub = torch.randn((P, ld), generator=gen, device=device) * 0.05
+    g = torch.empty((P, ld), device=device)
+    return w, g, m, pub, gen
+
+
+def run_case(P, S, n, tau, iters, q, seed, options=(), ld=None, t0=0):
+    say("case P=%d S=%d n=%d tau=%d iters=%d q=%.2f seed=%d options=%s ld=%s"
+        % (P, S, n, tau, iters, q, seed, options, ld))
+    with lw.Wagma(P, S, n, tau) as ctx:
+        if ld is not None:
+            ctx.set_row_stride(ld)
+        for opt, val in options:
+            ctx.set_option(opt, val)
+        ld = ctx.ld
+        w, g, m, pub, gen = random_state(P, ld, n, seed)
+        ow, om, opub = (x.cpu().numpy().copy() for x in (w, m, pub))
+        thr = min(int(q * 2 ** 32), 2 ** 32 - 1)
+        pad0 = (n + 3) // 4 * 4
+        keep_pad = [x[:, pad0:].clone() for x in (w, m, pub)]
+        for t in range(t0, t0 + iters):
+            g.normal_(0.0, 1e-2, generator=gen)
+            og = g.cpu().numpy()
+            mask = ctx.stale_mask(seed, t, thr)
+            assert np.array_equal(mask, orc.stale_mask(seed, t, P, thr))
+            if t % 5 == 3:                       # everybody late, the degenerate extreme
+                mask = orc.mask_words(np.ones(P, dtype=bool))
+            ctx.step(w, g, m, pub, mask, LR, MU, t)
+            orc.step_f32(P, S, tau, t, ow, og, om, opub, mask, LR, MU, n=n)
+            torch.cuda.synchronize()
+            for have, want, what in ((w, ow, "w"), (m, om, "m"), (pub, opub, "pub")):
+                assert_same_bits(have.cpu().numpy()[:, :n], want[:, :n], "%s at t=%d" % (what, t))
+        for x, k in zip((w, m, pub), keep_pad):
+            assert torch.equal(x[:, pad0:], k), "padding beyond 4*ceil(n/4) was written"
+        assert torch.equal(g.cpu(), torch.from_numpy(og)), "g was written"
+
+
+# ------------------------------------------------------------------ schedules and masks
+
+def test_schedule_tables_match_algorithm_1():
+    sizes = [1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024]
+    for P in sizes:
+        for S in [s for s in sizes if s <= P]:
+            with lw.Wagma(P, S, 16, 3) as ctx:
+                G, g = int(math.log2(P)), int(math.log2(S))
+                period = 1 if g == 0 or G == 0 else G // math.gcd(g, G)
+                assert ctx.period == period
+                for t in range(min(4 * period, 24)):
+                    dev, host = ctx.group_schedule(t)
+                    if orc.is_global_iteration(3, t):
+                        assert ctx.is_global(t)
+                        want = np.arange(P, dtype=np.int32)
+                    else:
+                        assert not ctx.is_global(t)
+                        want = orc.member_table(P, S, t).ravel()
+                        rep = orc.grouping_unionfind(P, S, t)        # Algorithm 1, literal
+                        for grp in host.reshape(P // S, S):
+                            assert len({int(rep[p]) for p in grp}) == 1
+                    assert np.array_equal(host, want), (P, S, t)
+    say("schedule tables: all (P,S) up to 1024 match")
+
+
+def test_device_table_equals_host_mirror():
+    """The table the kernels read is the one the host mirror shows."""
+    import ctypes
+    import os
+    hip = ctypes.CDLL(os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so"))
+    hip.hipMemcpy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
+    for P, S in [(64, 8), (32, 8), (1024, 32), (4, 2)]:
+        with lw.Wagma(P, S, 16, 4) as ctx:
+            for t in range(8):
+                dev, host = ctx.group_schedule(t)
+                out = np.empty(P, dtype=np.int32)
+                assert hip.hipMemcpy(out.ctypes.data, dev, P * 4, 2) == 0
+                assert np.array_equal(out, host)
+
+
+def test_stale_masks_bit_exact():
+    for P in (1, 4, 16, 64, 128, 1024):
+        with lw.Wagma(P, 1, 16, 0) as ctx:
+            for seed in (0, 200500128, 2 ** 64 - 1):
+                for t in (0, 1, 49, 10 ** 9):
+                    for thr in (0, 1 << 30, 858993459, 2 ** 32 - 1):
+                        assert np.array_equal(ctx.stale_mask(seed, t, thr),
+                                              orc.stale_mask(seed, t, P, thr))
+
+
+# ------------------------------------------------------------------ step parity, small sizes
+
+@pytest.mark.parametrize("P,S", [(1, 1), (2, 1), (2, 2), (4, 2), (4, 4), (8, 4), (8, 8), (16, 4),
+                                 (16, 16), (32, 8), (64, 8), (64, 64), (64, 2), (128, 16),
+                                 (256, 32), (1024, 32)])
+def test_step_bit_exact_small(P, S):
+    n = 5000 if P <= 64 else 1030
+    run_case(P, S, n, tau=4, iters=9, q=0.3, seed=P * 7 + S)
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 63, 64, 65, 255, 1023, 1025, 4097, 70001])
+def test_step_ragged_sizes(n):
+    run_case(8, 4, n, tau=3, iters=4, q=0.25, seed=n)
+    run_case(16, 16, n, tau=3, iters=4, q=0.25, seed=n + 1)
+
+
+def test_step_row_stride_variants():
+    run_case(8, 4, 1001, tau=3, iters=4, q=0.25, seed=1, ld=1004)      # tightest legal stride
+    run_case(8, 8, 1001, tau=3, iters=4, q=0.25, seed=2, ld=1004 + 4 * 37)
+    run_case(64, 8, 3000, tau=0, iters=4, q=0.25, seed=3, ld=4096)
+
+
+OPTION_SETS = [
+    ((lw.WAGMA_OPT_BLOCK, 512),),
+    ((lw.WAGMA_OPT_NONTEMPORAL, 0),),
+    ((lw.WAGMA_OPT_FORCE_STREAM, 1),),
+    ((lw.WAGMA_OPT_XCD_SWIZZLE, 1),),
+    ((lw.WAGMA_OPT_TILE_MAJOR, 1),),
+    ((lw.WAGMA_OPT_WAVES, 2),),
+    ((lw.WAGMA_OPT_WAVES, 4),),
+    ((lw.WAGMA_OPT_BLOCK, 512), (lw.WAGMA_OPT_XCD_SWIZZLE, 1), (lw.WAGMA_OPT_TILE_MAJOR, 1),
+     (lw.WAGMA_OPT_FORCE_STREAM, 1), (lw.WAGMA_OPT_WAVES, 4), (lw.WAGMA_OPT_NONTEMPORAL, 0)),
+]
+
+
+@pytest.mark.parametrize("options", OPTION_SETS)
+def test_step_every_launch_variant(options):
+    run_case(64, 8, 20011, tau=4, iters=5, q=0.3, seed=11, options=options)
+    run_case(32, 8, 4099, tau=3, iters=4, q=0.3, seed=12, options=options)
+    run_case(64, 32, 4099, tau=3, iters=4, q=0.3, seed=13, options=options)
+
+
+def test_degenerate_parameters():
+    run_case(8, 1, 2049, tau=0, iters=5, q=0.5, seed=21)       # S=1: no averaging, late rule /2
+    run_case(8, 8, 2049, tau=0, iters=5, q=0.0, seed=22)       # S=P, never global
+    run_case(8, 2, 2049, tau=1, iters=5, q=0.5, seed=23)       # always global
+    run_case(16, 4, 2049, tau=10, iters=3, q=1.0, seed=24)     # everybody late every iteration
+    run_case(16, 4, 2049, tau=10, iters=4, q=0.2, seed=25, t0=10 ** 12)   # huge iteration numbers
+
+
+def test_subnormals_and_specials():
+    """Gradual underflow is kept; infinities and NaNs flow as IEEE says."""
+    P, S, n = 4, 2, 8
+    with lw.Wagma(P, S, n, 0) as ctx:
+        ld = ctx.ld
+        tiny = np.float32(2.0 ** -149)
+        host = np.zeros((P, ld), dtype=np.float32)
+        host[:, 0] = [3 * tiny, 5 * tiny, 7 * tiny, 9 * tiny]
+        host[:, 1] = [np.inf, 1.0, -np.inf, 1.0]
+        host[:, 2] = [np.nan, 1.0, 2.0, 3.0]
+        host[:, 3] = [1e-39, -1e-39, 3e-39, 1e-38]
+        w = torch.from_numpy(host).cuda()
+        g = torch.zeros_like(w)
+        m = torch.zeros_like(w)
+        pub = w.clone()
+        ow, og, om, opub = host.copy(), np.zeros_like(host), np.zeros_like(host), host.copy()
+        for t in range(2):
+            mask = orc.mask_words(np.array([False, True, False, False]))
+            ctx.step(w, g, m, pub, mask, LR, MU, t)
+            orc.step_f32(P, S, 0, t, ow, og, om, opub, mask, LR, MU, n=n)
+            torch.cuda.synchronize()
+            assert_same_bits(w.cpu().numpy()[:, :n], ow[:, :n], "w")
+        assert ow[0, 0] != 0.0
+
+
+def test_resume_is_stateless():
+    """10 iterations straight == 5, destroy, create, 5 more (the context keeps no iteration state)."""
+    P, S, n, tau = 16, 4, 3001, 5
+    outs = []
+    for split in (False, True):
+        ctx = lw.Wagma(P, S, n, tau)
+        w, g, m, pub, gen = random_state(P, ctx.ld, n, 77)
+        for t in range(10):
+            if split and t == 5:
+                ctx.destroy()
+                ctx = lw.Wagma(P, S, n, tau)
+            g.normal_(0.0, 1e-2, generator=gen)
+            ctx.step(w, g, m, pub, ctx.stale_mask(5, t, 1 << 30), LR, MU, t)
+        torch.cuda.synchronize()
+        outs.append([x.cpu() for x in (w, m, pub)])
+        ctx.destroy()
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
+def test_errors_leave_buffers_alone():
+    P, S, n = 8, 4, 100
+    with lw.Wagma(P, S, n, 3) as ctx:
+        w, g, m, pub, _ = random_state(P, ctx.ld, n, 5)
+        before = [x.clone() for x in (w, g, m, pub)]
+        lib = lw.load()
+        ptrs = [x.data_ptr() for x in (w, g, m, pub)]
+        assert lib.wagma_step(ctx.ctx, ptrs[0] + 4, ptrs[1], ptrs[2], ptrs[3], None, LR, MU, 0, None) == lw.WAGMA_EINVAL
+        assert lib.wagma_step(ctx.ctx, ptrs[0], None, ptrs[2], ptrs[3], None, LR, MU, 0, None) == lw.WAGMA_EINVAL
+        assert lib.wagma_step(ctx.ctx, ptrs[0], ptrs[1], ptrs[2], ptrs[3], None, LR, MU, -1, None) == lw.WAGMA_EINVAL
+        with pytest.raises(lw.WagmaError):
+            ctx.set_row_stride(n - 4)
+        with pytest.raises(lw.WagmaError):
+            ctx.set_row_stride(n + 1)
+        with pytest.raises(lw.WagmaError):
+            ctx.set_option(lw.WAGMA_OPT_BLOCK, 100)
+        with pytest.raises(ValueError):
+            ctx.step(w[:, :-4], g, m, pub, None, LR, MU, 0)
+        torch.cuda.synchronize()
+        for x, k in zip((w, g, m, pub), before):
+            assert torch.equal(x, k)
+
+
+def test_runs_on_a_side_stream():
+    P, S, n = 16, 4, 50000
+    with lw.Wagma(P, S, n, 0) as ctx:
+        w, g, m, pub, gen = random_state(P, ctx.ld, n, 9)
+        g.normal_(0.0, 1e-2, generator=gen)
+        ow, og, om, opub = (x.cpu().numpy().copy() for x in (w, g, m, pub))
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            ctx.step(w, g, m, pub, None, LR, MU, 0)          # picks up torch's current stream
+            ctx.step(w, g, m, pub, None, LR, MU, 1, stream=side.cuda_stream)
+        side.synchronize()
+        for t in range(2):
+            orc.step_f32(P, S, 0, t, ow, og, om, opub, None, LR, MU, n=n)
+        assert_same_bits(w.cpu().numpy()[:, :n], ow[:, :n], "w")
+
+
+# ------------------------------------------------------------------ the five workloads
+
+def test_workload_1_full_tensors():
+    """P=4, S=2, n=1,048,576, 10 iterations, nobody late: every element, every iteration."""
+    wl = wk.workload(1)
+    say("workload 1 full:", wl.name)
+    with lw.Wagma(wl.P, wl.S, wl.n, wl.tau) as ctx:
+        w, g, m, pub = ctx.alloc()
+        wk.fill_initial_state(wl, w, m, pub)
+        ow, om, opub = (x.cpu().numpy().copy() for x in (w, m, pub))
+        w64, m64, pub64 = (x.astype(np.float64) for x in (ow, om, opub))
+        n = wl.n
+        for t in range(wl.iters):
+            wk.fill_gradients(wl, t, g)
+            og = g.cpu().numpy()
+            mask = ctx.stale_mask(wl.seed, t, wl.stale_threshold)
+            assert not mask.any()
+            ctx.step(w, g, m, pub, mask, wl.lr, wl.mu, t)
+            orc.step_f32(wl.P, wl.S, wl.tau, t, ow, og, om, opub, mask, wl.lr, wl.mu, n=n)
+            orc.step_f64(wl.P, wl.S, wl.tau, t, w64, og.astype(np.float64), m64, pub64, mask,
+                         float(np.float32(wl.lr)), float(np.float32(wl.mu)), n=n)
+            torch.cuda.synchronize()
+            hw = w.cpu().numpy()
+            assert_same_bits(hw[:, :n], ow[:, :n], "w at t=%d" % t)
+            assert_same_bits(m.cpu().numpy()[:, :n], om[:, :n], "m at t=%d" % t)
+            assert_same_bits(pub.cpu().numpy()[:, :n], opub[:, :n], "pub at t=%d" % t)
+            assert np.abs(hw[:, :n] - w64[:, :n]).max() <= 1e-6 * np.abs(w64[:, :n]).max()
+            if ctx.is_global(t):
+                assert torch.equal(w[1:, :n], w[:1, :n].expand(wl.P - 1, n))
+            else:
+                _, host = ctx.group_schedule(t)
+                for grp in host.reshape(-1, wl.S):
+                    assert torch.equal(w[int(grp[0]), :n], w[int(grp[1]), :n])
+
+
+def sampled_parity(index, iters=None, count=40000):
+    """Full-size run in bench.py's launch configuration; the oracle follows a column sample
+    (columns are independent of one another) through every iteration."""
+    wl = wk.workload(index)
+    iters = wl.iters if iters is None else iters
+    say("workload %d sampled: %s, %d iterations, %d columns" % (index, wl.name, iters, count))
+    P, S, n = wl.P, wl.S, wl.n
+    with lw.Wagma(P, S, n, wl.tau) as ctx:
+        w, g, m, pub = ctx.alloc()
+        wk.fill_initial_state(wl, w, m, pub)
+        cols = wk.sample_columns(n, count, wl.seed).cuda()
+        ow, om, opub = (np.ascontiguousarray(x[:, cols].cpu().numpy()) for x in (w, m, pub))
+        w64, m64, pub64 = (x.astype(np.float64) for x in (ow, om, opub))
+        worst = 0.0
+        for t in range(iters):
+            wk.fill_gradients(wl, t, g)
+            og = np.ascontiguousarray(g[:, cols].cpu().numpy())
+            mask = ctx.stale_mask(wl.seed, t, wl.stale_threshold)
+            assert np.array_equal(mask, orc.stale_mask(wl.seed, t, P, wl.stale_threshold))
+            _, host = ctx.group_schedule(t)
+            if not ctx.is_global(t):
+                assert np.array_equal(host, orc.member_table(P, S, t).ravel())
+            ctx.step(w, g, m, pub, mask, wl.lr, wl.mu, t)
+            orc.step_f32(P, S, wl.tau, t, ow, og, om, opub, mask, wl.lr, wl.mu)
+            orc.step_f64(P, S, wl.tau, t, w64, og.astype(np.float64), m64, pub64, mask,
+                         float(np.float32(wl.lr)), float(np.float32(wl.mu)))
+            torch.cuda.synchronize()
+            for have, want, what in ((w, ow, "w"), (m, om, "m"), (pub, opub, "pub")):
+                assert_same_bits(have[:, cols].cpu().numpy(), want, "%s at t=%d" % (what, t))
+            worst = max(worst, float(np.abs(ow - w64).max() / np.abs(w64).max()))
+            # properties of the whole tensors
+            if ctx.is_global(t):
+                assert bool((w[:, :n] == w[:1, :n]).all()), "replicas differ after a global average"
+        say("workload %d: bit-exact on %d columns x %d iterations; |f32-f64|/max|w| <= %.2e"
+            % (index, cols.numel(), iters, worst))
+        assert worst <= 1e-6
+    del w, g, m, pub
+    torch.cuda.empty_cache()
+
+
+def test_workload_2_sampled():
+    sampled_parity(2)
+
+
+def test_workload_3_sampled():
+    sampled_parity(3)
+
+
+def test_workload_4_sampled():
+    sampled_parity(4)
+
+
+def test_workload_5_sampled():
+    sampled_parity(5, count=20000)
