@@ -18,7 +18,8 @@ import time
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 
-OPTS = {"block": 1, "nontemporal": 2, "force_stream": 3, "xcd_swizzle": 4, "tile_major": 5, "waves": 6}
+OPTS = {"block": 1, "nontemporal": 2, "force_stream": 3, "xcd_swizzle": 4, "tile_major": 5, "waves": 6,
+        "stripe_log2": 7, "xcd_chunk_log2": 8}
 
 
 def log(*a):
@@ -65,6 +66,8 @@ def main() -> int:
     ap.add_argument("--workload", type=int, default=4, help="1..5; 4 = the headline P=64 S=8 25.6M")
     ap.add_argument("--opt", action="append", default=[], help="tuning knob NAME=VALUE (%s)" % ", ".join(OPTS))
     ap.add_argument("--ld", type=int, default=None, help="row stride override (floats)")
+    ap.add_argument("--plain-alloc", action="store_true",
+                    help="ordinary torch allocations instead of the library's HBM-region-aware allocator")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-columns", type=int, default=131072)
     args = ap.parse_args()
@@ -101,7 +104,14 @@ def main() -> int:
         ctx.set_option(OPTS[k], int(v))
     ld = ctx.ld
     log("workload %d: %s  n=%d ld=%d  buffers 4 x %.2f GB" % (wl.index, wl.name, n, ld, P * ld * 4 / 1e9))
-    w, g, m, pub = ctx.alloc()
+    if args.plain_alloc:
+        w, g, m, pub = ctx.alloc()
+        placement = "torch allocations"
+    else:
+        w, g, m, pub = ctx.alloc_placed()     # w, m, pub in different HBM regions
+        info = ctx.placement_info()
+        placement = "wagma_alloc_buffers: %(regions)d regions after %(candidates)d candidates" % info
+        log("placement:", info)
     wk.fill_initial_state(wl, w, m, pub)
     wk.fill_gradients(wl, 0, g)       # one gradient slab, reused: generating it is not part of the path
     masks = [ctx.stale_mask(wl.seed, t, wl.stale_threshold) for t in range(max(K, W))]
@@ -152,15 +162,15 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "P": P, "S": S, "n": n, "ld": ld, "tau": wl.tau,
                    "late_probability": wl.q, "global_steps_in_run": len(glb),
-                   "options": args.opt},
+                   "options": args.opt, "allocation": placement},
         "hbm_gbs_all_steps": sum(bytes_of) / ((grp_ms + glb_ms) * 1e-3) / 1e9,
         "group_step_ms": (grp_ms / len(grp)) if grp else None,
         "global_step_ms": (glb_ms / len(glb)) if glb else None,
         "global_step_gbs": (sum(bytes_of[t] for t in glb) / (glb_ms * 1e-3) / 1e9) if glb else None,
         "roofline": roofline,
     }
-    ctx.destroy()
     del w, g, m, pub
+    ctx.destroy()
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a slice ...")

@@ -62,6 +62,8 @@ struct StepParams {
     int log2_chunks;       // log2(members / kChunk) for the streaming kernel
     int swizzle;           // 1: contiguous block range per XCD
     int tile_major;        // 1: consecutive blocks walk the groups of one column tile
+    int stripe_log2;       // log2 of the distance, in KiB, between a workgroup's wavefronts
+    int xcd_chunk_log2;    // log2 of the run of consecutive tiles one XCD works on (0: 1 tile)
 };
 
 template <bool NT>
@@ -111,10 +113,15 @@ __device__ __forceinline__ v4f tree_sum(const v4f* c)
     }
 }
 
-// Which (group, column tile) does this workgroup own?  Workgroups are handed
-// to the 8 XCDs round-robin; with `swizzle` each XCD instead walks one
-// contiguous eighth of the work.  Returns false for padding workgroups.
-__device__ __forceinline__ bool decode_block(const StepParams& p, int64_t& group, int64_t& tile)
+// Which group and which 16-byte column slice does this lane own?  Workgroups are
+// handed to the 8 XCDs round-robin; with `swizzle` each XCD instead walks one
+// contiguous eighth of the work.  A wavefront always owns 64 consecutive slices
+// (1 KiB per row).  The wavefronts of workgroup `tile` sit 2^stripe_log2 KiB apart
+// and consecutive workgroups fill the gaps, so that a workgroup's simultaneous
+// requests to one row hit addresses one stripe apart (stripe_log2 = 0: the plain
+// contiguous tile).  Returns false for lanes and workgroups beyond the end.
+template <int BLOCK>
+__device__ __forceinline__ bool decode_block(const StepParams& p, int64_t& group, int64_t& col)
 {
     int64_t b = blockIdx.x;
     if (p.swizzle) {
@@ -123,6 +130,7 @@ __device__ __forceinline__ bool decode_block(const StepParams& p, int64_t& group
     }
     if (b >= p.blocks)
         return false;
+    int64_t tile;
     if (p.tile_major) {
         const int64_t groups = p.blocks / p.tiles;
         group = b % groups;
@@ -131,17 +139,29 @@ __device__ __forceinline__ bool decode_block(const StepParams& p, int64_t& group
         group = b / p.tiles;
         tile = b % p.tiles;
     }
-    return true;
+    if (p.xcd_chunk_log2 > 0) {
+        // Workgroup b runs on XCD b % 8.  Give each XCD runs of 2^xcd_chunk_log2 consecutive
+        // tiles: the XCD number moves from tile bits [0,3) up to bits [j, j+3).
+        const int j = p.xcd_chunk_log2;
+        const int64_t xcd = tile & (kNumXcd - 1);
+        const int64_t hi = tile >> 3;
+        tile = ((hi >> j) << (j + 3)) | (xcd << j) | (hi & ((int64_t(1) << j) - 1));
+    }
+    constexpr int kWavesPerBlock = BLOCK / 64;
+    const int64_t wave = threadIdx.x >> 6;
+    const int64_t lane = threadIdx.x & 63;
+    const int64_t super = tile >> p.stripe_log2;
+    const int64_t within = tile & ((int64_t(1) << p.stripe_log2) - 1);
+    const int64_t chunk = ((super * kWavesPerBlock + wave) << p.stripe_log2) + within;
+    col = chunk * 64 + lane;
+    return col < p.nvec;
 }
 
 template <int S, bool NT, int BLOCK, int WAVES>
 __global__ void __launch_bounds__(BLOCK, WAVES) step_rows_in_registers(const StepParams p)
 {
-    int64_t group, tile;
-    if (!decode_block(p, group, tile))
-        return;
-    const int64_t col = tile * BLOCK + threadIdx.x;
-    if (col >= p.nvec)
+    int64_t group, col;
+    if (!decode_block<BLOCK>(p, group, col))
         return;
     const int32_t* member = p.table + group * S;
     // Row bases are wave-uniform (scalar registers); the lane adds one 32-bit offset.
@@ -188,11 +208,8 @@ __global__ void __launch_bounds__(BLOCK, WAVES) step_rows_in_registers(const Ste
 template <bool NT, int BLOCK, int WAVES>
 __global__ void __launch_bounds__(BLOCK, WAVES) step_rows_streamed(const StepParams p)
 {
-    int64_t group, tile;
-    if (!decode_block(p, group, tile))
-        return;
-    const int64_t col = tile * BLOCK + threadIdx.x;
-    if (col >= p.nvec)
+    int64_t group, col;
+    if (!decode_block<BLOCK>(p, group, col))
         return;
     const int32_t* member = p.table + group * p.members;
     const uint32_t lane_at = (uint32_t)col * 4u;
@@ -299,6 +316,56 @@ __global__ void build_schedule_table(int32_t* table, int P, int G, int g, int pe
     table[idx] = base | member_bits;
 }
 
+// ---------------------------------------------------------------------------
+// HBM-region placement.  Measured on MI355X: the 288 GB of HBM are split, by the
+// top physical address bits, into a few regions tens of GiB wide (the ranks of
+// the 12-high stacks, by all appearance).  Write streams that all fall into one
+// region sustain about 5.9 TB/s, write streams spread over two regions about
+// 7.2 TB/s; reads do not care.  The step writes W, the momentum and the send
+// buffer of every member row at once, so it runs about 15% faster when these
+// three arrays lie in different regions.  Regions cannot be queried, so the
+// allocator finds them by timing: this kernel writes four streams through `a`
+// and four through `b`; it is fast exactly when a and b lie in different regions.
+// The probe must write well beyond the 256 MB Infinity Cache to see the HBM at all.
+constexpr size_t kProbeSideMax = size_t(1) << 30;            // bytes written through each pointer
+constexpr size_t kPlacementMinBytes = size_t(1) << 30;       // smaller arrays are not placed
+constexpr double kProbeFastRatio = 1.10;                     // "different region" if this much faster
+constexpr int kMaxCandidates = 64;
+
+__global__ void __launch_bounds__(256) placement_probe(float* a, float* b, uint32_t vec_per_stream)
+{
+    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= vec_per_stream)
+        return;
+    const v4f zero = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (uint32_t k = 0; k < 4; ++k) {
+        __builtin_nontemporal_store(zero, reinterpret_cast<v4f*>(a) + (size_t)k * vec_per_stream + i);
+        __builtin_nontemporal_store(zero, reinterpret_cast<v4f*>(b) + (size_t)k * vec_per_stream + i);
+    }
+}
+
+// GB/s of the probe on (a, b); both must have side_bytes behind them.  < 0 on a HIP error.
+double probe_gbs(float* a, float* b, size_t side_bytes, hipEvent_t start, hipEvent_t stop)
+{
+    const uint32_t vec = (uint32_t)(side_bytes / 4 / 16);
+    const unsigned grid = (vec + 255) / 256;
+    float best_ms = 1e30f;
+    for (int rep = 0; rep < 4; ++rep) {
+        if (hipEventRecord(start, nullptr) != hipSuccess)
+            return -1.0;
+        hipLaunchKernelGGL(placement_probe, dim3(grid), dim3(256), 0, (hipStream_t) nullptr, a, b, vec);
+        if (hipEventRecord(stop, nullptr) != hipSuccess || hipEventSynchronize(stop) != hipSuccess)
+            return -1.0;
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, start, stop) != hipSuccess)
+            return -1.0;
+        if (rep > 0 && ms < best_ms)
+            best_ms = ms;
+    }
+    return 2.0 * 4.0 * 16.0 * (double)vec / (best_ms * 1e-3) / 1e9;
+}
+
 int exact_log2(int64_t x)
 {
     if (x < 1 || (x & (x - 1)) != 0)
@@ -377,7 +444,12 @@ struct wagma_ctx {
     int64_t n, ld;
     int32_t* d_table;  // (period + 1) * P, device
     int32_t* h_table;  // host mirror
-    int opt_block, opt_nontemporal, opt_force_stream, opt_swizzle, opt_tile_major, opt_waves;
+    int opt_block, opt_nontemporal, opt_force_stream, opt_swizzle, opt_tile_major, opt_waves, opt_stripe_log2, opt_xcd_chunk_log2;
+    float* placed[4];        // w, g, m, pub handed out by wagma_alloc_buffers (or all NULL)
+    int place_candidates;    // allocations tried by the last wagma_alloc_buffers
+    int place_regions;       // how many of w, m, pub lie in pairwise different regions (1..3)
+    double place_same_gbs;   // probe rate inside one region
+    double place_split_gbs;  // probe rate between the regions of w and m (0 if not separated)
 };
 
 extern "C" {
@@ -404,14 +476,23 @@ int wagma_create(wagma_ctx** out, int P, int S, int64_t n, int tau)
     ctx->period = (g == 0 || G == 0) ? 1 : G / gcd_int(g, G);
     // Rows start on 256-byte boundaries so that every wavefront access is aligned.
     ctx->ld = (n + 63) / 64 * 64;
-    ctx->opt_block = 256;
+    // measured best on MI355X for the P=64, S=8, 25.6M-parameter workload
+    ctx->opt_block = 512;
     ctx->opt_nontemporal = 1;
     ctx->opt_force_stream = 0;
     ctx->opt_swizzle = 0;
     ctx->opt_tile_major = 0;
-    ctx->opt_waves = 3;
+    ctx->opt_waves = 2;
+    ctx->opt_stripe_log2 = 2;
+    ctx->opt_xcd_chunk_log2 = 2;
     ctx->d_table = nullptr;
     ctx->h_table = nullptr;
+    for (int k = 0; k < 4; ++k)
+        ctx->placed[k] = nullptr;
+    ctx->place_candidates = 0;
+    ctx->place_regions = 0;
+    ctx->place_same_gbs = 0.0;
+    ctx->place_split_gbs = 0.0;
 
     const size_t entries = (size_t)(ctx->period + 1) * (size_t)P;
     hipError_t e = hipGetDevice(&ctx->device);
@@ -452,7 +533,7 @@ int wagma_destroy(wagma_ctx* ctx)
 {
     if (!ctx)
         return WAGMA_OK;
-    int rc = WAGMA_OK;
+    int rc = wagma_free_buffers(ctx);
     if (ctx->d_table) {
         const hipError_t e = hipFree(ctx->d_table);
         if (e != hipSuccess)
@@ -548,7 +629,15 @@ int wagma_step(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub,
     const bool streamed = p.members > kChunk || (ctx->opt_force_stream && p.members == kChunk);
     p.log2_chunks = streamed ? exact_log2(p.members / kChunk) : 0;
     const int block = ctx->opt_block;
+    p.stripe_log2 = ctx->opt_stripe_log2;
+    // whole stripes: tiles is a multiple of 2^stripe_log2 (the surplus lanes find col >= nvec)
     p.tiles = (p.nvec + block - 1) / block;
+    p.xcd_chunk_log2 = ctx->opt_xcd_chunk_log2;
+    // tiles is rounded up to whole stripes and whole XCD rounds (the surplus lanes find col >= nvec)
+    int round_log2 = p.stripe_log2;
+    if (p.xcd_chunk_log2 > 0 && p.xcd_chunk_log2 + 3 > round_log2)
+        round_log2 = p.xcd_chunk_log2 + 3;
+    p.tiles = ((p.tiles + (int64_t(1) << round_log2) - 1) >> round_log2) << round_log2;
     p.blocks = (int64_t)(ctx->P / p.members) * p.tiles;
     int64_t grid = p.blocks;
     if (p.swizzle)
@@ -594,6 +683,139 @@ int wagma_stale_mask(const wagma_ctx* ctx, uint64_t seed, int64_t iter, uint32_t
     return WAGMA_OK;
 }
 
+int wagma_alloc_buffers(wagma_ctx* ctx, float** w, float** g, float** m, float** pub)
+{
+    if (!ctx || !w || !g || !m || !pub || ctx->placed[0])
+        return WAGMA_EINVAL;
+    int device = -1;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess)
+        return hip_failed(e);
+    if (device != ctx->device)
+        return WAGMA_EINVAL;
+    const size_t bytes = (size_t)ctx->P * (size_t)ctx->ld * sizeof(float);
+    ctx->place_candidates = 0;
+    ctx->place_regions = 1;
+    ctx->place_same_gbs = 0.0;
+    ctx->place_split_gbs = 0.0;
+
+    float* chosen[3] = {nullptr, nullptr, nullptr};  // w, m, pub
+    int n_chosen = 0;
+    float* spare[kMaxCandidates];
+    int n_spare = 0;
+    int rc = WAGMA_OK;
+
+    if (bytes >= kPlacementMinBytes) {
+        hipEvent_t start = nullptr, stop = nullptr;
+        if (hipEventCreate(&start) == hipSuccess && hipEventCreate(&stop) == hipSuccess) {
+            // each probe writes `side` bytes through either pointer: at most half an array
+            size_t side = bytes / 2 < kProbeSideMax ? bytes / 2 : kProbeSideMax;
+            side = side / 1024 * 1024;
+            const size_t tail = (bytes - side) / sizeof(float) / 4 * 4;
+            while (n_chosen < 3 && ctx->place_candidates < kMaxCandidates) {
+                size_t free_b = 0, total_b = 0;
+                if (hipMemGetInfo(&free_b, &total_b) != hipSuccess || free_b < 3 * bytes)
+                    break;  // keep room for the gradient array and for the caller
+                float* c = nullptr;
+                if (hipMalloc((void**)&c, bytes) != hipSuccess) {
+                    (void)hipGetLastError();
+                    break;
+                }
+                ++ctx->place_candidates;
+                const double self = probe_gbs(c, c + side / sizeof(float), side, start, stop);
+                const double ends = probe_gbs(c, c + tail, side, start, stop);
+                bool take = self > 0.0 && ends > 0.0;
+                if (take && ctx->place_same_gbs == 0.0)
+                    ctx->place_same_gbs = self;
+                // a candidate that straddles two regions is of no use
+                if (take && ends > kProbeFastRatio * ctx->place_same_gbs)
+                    take = false;
+                for (int k = 0; take && k < n_chosen; ++k) {
+                    const double cross = probe_gbs(chosen[k], c, side, start, stop);
+                    if (cross < kProbeFastRatio * ctx->place_same_gbs)
+                        take = false;  // same region as an array already placed
+                    else if (k == 0 && n_chosen == 1)
+                        ctx->place_split_gbs = cross;
+                }
+                if (take)
+                    chosen[n_chosen++] = c;
+                else
+                    spare[n_spare++] = c;  // held for now, so that the next candidate lies further on
+            }
+            ctx->place_regions = n_chosen > 0 ? n_chosen : 1;
+        }
+        if (start)
+            (void)hipEventDestroy(start);
+        if (stop)
+            (void)hipEventDestroy(stop);
+    }
+    // whatever could not be separated takes any spare candidate, then a fresh allocation
+    for (int k = n_chosen; k < 3 && rc == WAGMA_OK; ++k) {
+        if (n_spare > 0) {
+            chosen[k] = spare[--n_spare];
+        } else if ((e = hipMalloc((void**)&chosen[k], bytes)) != hipSuccess) {
+            chosen[k] = nullptr;
+            g_last_hip_error = (int)e;
+            rc = e == hipErrorOutOfMemory ? WAGMA_ENOMEM : WAGMA_EHIP;
+        }
+    }
+    for (int k = 0; k < n_spare; ++k)
+        (void)hipFree(spare[k]);
+    float* grad = nullptr;
+    if (rc == WAGMA_OK && (e = hipMalloc((void**)&grad, bytes)) != hipSuccess) {
+        g_last_hip_error = (int)e;
+        rc = e == hipErrorOutOfMemory ? WAGMA_ENOMEM : WAGMA_EHIP;
+    }
+    if (rc == WAGMA_OK && (e = hipDeviceSynchronize()) != hipSuccess)
+        rc = hip_failed(e);
+    if (rc != WAGMA_OK) {
+        for (int k = 0; k < 3; ++k)
+            if (chosen[k])
+                (void)hipFree(chosen[k]);
+        if (grad)
+            (void)hipFree(grad);
+        (void)hipGetLastError();
+        return rc;
+    }
+    ctx->placed[0] = *w = chosen[0];
+    ctx->placed[1] = *g = grad;
+    ctx->placed[2] = *m = chosen[1];
+    ctx->placed[3] = *pub = chosen[2];
+    return WAGMA_OK;
+}
+
+int wagma_free_buffers(wagma_ctx* ctx)
+{
+    if (!ctx)
+        return WAGMA_EINVAL;
+    int rc = WAGMA_OK;
+    for (int k = 0; k < 4; ++k) {
+        if (ctx->placed[k]) {
+            const hipError_t e = hipFree(ctx->placed[k]);
+            if (e != hipSuccess)
+                rc = hip_failed(e);
+            ctx->placed[k] = nullptr;
+        }
+    }
+    return rc;
+}
+
+int wagma_placement_info(const wagma_ctx* ctx, int* candidates, int* regions, double* same_gbs,
+                         double* split_gbs)
+{
+    if (!ctx)
+        return WAGMA_EINVAL;
+    if (candidates)
+        *candidates = ctx->place_candidates;
+    if (regions)
+        *regions = ctx->place_regions;
+    if (same_gbs)
+        *same_gbs = ctx->place_same_gbs;
+    if (split_gbs)
+        *split_gbs = ctx->place_split_gbs;
+    return WAGMA_OK;
+}
+
 int wagma_set_option(wagma_ctx* ctx, int option, int64_t value)
 {
     if (!ctx)
@@ -615,6 +837,16 @@ int wagma_set_option(wagma_ctx* ctx, int option, int64_t value)
         return WAGMA_OK;
     case WAGMA_OPT_TILE_MAJOR:
         ctx->opt_tile_major = value != 0;
+        return WAGMA_OK;
+    case WAGMA_OPT_STRIPE_LOG2:
+        if (value < 0 || value > 16)
+            return WAGMA_EINVAL;
+        ctx->opt_stripe_log2 = (int)value;
+        return WAGMA_OK;
+    case WAGMA_OPT_XCD_CHUNK_LOG2:
+        if (value < 0 || value > 13)
+            return WAGMA_EINVAL;
+        ctx->opt_xcd_chunk_log2 = (int)value;
         return WAGMA_OK;
     case WAGMA_OPT_WAVES:
         if (value < 2 || value > 4)

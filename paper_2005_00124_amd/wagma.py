@@ -19,7 +19,8 @@ LIB_PATH = os.path.join(_PKG, "libwagma.so")
 WAGMA_OK, WAGMA_EINVAL, WAGMA_EHIP, WAGMA_ENOMEM = 0, -1, -2, -3
 WAGMA_MAX_P = 1024
 WAGMA_OPT_BLOCK, WAGMA_OPT_NONTEMPORAL, WAGMA_OPT_FORCE_STREAM = 1, 2, 3
-WAGMA_OPT_XCD_SWIZZLE, WAGMA_OPT_TILE_MAJOR, WAGMA_OPT_WAVES = 4, 5, 6
+WAGMA_OPT_XCD_SWIZZLE, WAGMA_OPT_TILE_MAJOR, WAGMA_OPT_WAVES, WAGMA_OPT_STRIPE_LOG2 = 4, 5, 6, 7
+WAGMA_OPT_XCD_CHUNK_LOG2 = 8
 
 # name -> (restype, argtypes): every symbol include/wagma.h declares
 _i32pp = ctypes.POINTER(ctypes.POINTER(ctypes.c_int32))
@@ -38,6 +39,11 @@ SYMBOLS = {
                                   ctypes.c_int64, ctypes.c_void_p]),
     "wagma_stale_mask": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int64,
                                         ctypes.c_uint32, _u64p]),
+    "wagma_alloc_buffers": (ctypes.c_int, [ctypes.c_void_p] + [ctypes.POINTER(ctypes.c_void_p)] * 4),
+    "wagma_free_buffers": (ctypes.c_int, [ctypes.c_void_p]),
+    "wagma_placement_info": (ctypes.c_int, [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int),
+                                            ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_double),
+                                            ctypes.POINTER(ctypes.c_double)]),
     "wagma_set_option": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64]),
     "wagma_strerror": (ctypes.c_char_p, [ctypes.c_int]),
     "wagma_last_hip_error": (ctypes.c_int, []),
@@ -155,6 +161,34 @@ def wagma_stale_mask(ctx: int, seed: int, it: int, threshold: int, P: int) -> np
     return words
 
 
+def wagma_alloc_buffers(ctx: int):
+    """Returns the device addresses (w, g, m, pub) of arrays placed by the library."""
+    ptrs = [ctypes.c_void_p() for _ in range(4)]
+    _check(load().wagma_alloc_buffers(ctx, *[ctypes.byref(p) for p in ptrs]), "wagma_alloc_buffers")
+    return tuple(p.value for p in ptrs)
+
+
+def wagma_free_buffers(ctx: int) -> None:
+    _check(load().wagma_free_buffers(ctx), "wagma_free_buffers")
+
+
+def wagma_placement_info(ctx: int) -> dict:
+    cand, regions = ctypes.c_int(), ctypes.c_int()
+    same, split = ctypes.c_double(), ctypes.c_double()
+    _check(load().wagma_placement_info(ctx, ctypes.byref(cand), ctypes.byref(regions),
+                                       ctypes.byref(same), ctypes.byref(split)), "wagma_placement_info")
+    return {"candidates": cand.value, "regions": regions.value,
+            "probe_same_region_gbs": same.value, "probe_two_regions_gbs": split.value}
+
+
+class _DeviceArray:
+    """A (P, ld) fp32 view of library-owned device memory for torch.as_tensor."""
+
+    def __init__(self, ptr: int, shape):
+        self.__cuda_array_interface__ = {"shape": tuple(shape), "typestr": "<f4", "data": (ptr, False),
+                                         "version": 2, "strides": None}
+
+
 def wagma_set_option(ctx: int, option: int, value: int) -> None:
     _check(load().wagma_set_option(ctx, option, value), "wagma_set_option")
 
@@ -196,6 +230,21 @@ class Wagma:
         import torch
         return tuple(torch.empty((self.P, self.ld), dtype=torch.float32, device=device)
                      for _ in range(4))
+
+    def alloc_placed(self):
+        """w, g, m, pub as torch views of arrays that the library allocated with w, m and pub in
+        different HBM regions (see wagma_alloc_buffers).  The library owns the memory: it lives
+        until free_placed() or destroy(), and the tensors must not be used after that."""
+        import torch
+        ptrs = wagma_alloc_buffers(self.ctx)
+        dev = torch.device("cuda", torch.cuda.current_device())
+        return tuple(torch.as_tensor(_DeviceArray(p, (self.P, self.ld)), device=dev) for p in ptrs)
+
+    def free_placed(self) -> None:
+        wagma_free_buffers(self.ctx)
+
+    def placement_info(self) -> dict:
+        return wagma_placement_info(self.ctx)
 
     def _validate(self, *tensors) -> None:
         import torch

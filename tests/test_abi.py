@@ -37,7 +37,8 @@ def test_header_constants_match_binding():
     text = open(os.path.join(ROOT, "include", "wagma.h")).read()
     for name in ("WAGMA_OK", "WAGMA_EINVAL", "WAGMA_EHIP", "WAGMA_ENOMEM", "WAGMA_MAX_P",
                  "WAGMA_OPT_BLOCK", "WAGMA_OPT_NONTEMPORAL", "WAGMA_OPT_FORCE_STREAM",
-                 "WAGMA_OPT_XCD_SWIZZLE", "WAGMA_OPT_TILE_MAJOR", "WAGMA_OPT_WAVES"):
+                 "WAGMA_OPT_XCD_SWIZZLE", "WAGMA_OPT_TILE_MAJOR", "WAGMA_OPT_WAVES",
+                 "WAGMA_OPT_STRIPE_LOG2", "WAGMA_OPT_XCD_CHUNK_LOG2"):
         value = re.search(r"#define\s+%s\s+\(?(-?\d+)\)?" % name, text).group(1)
         assert int(value) == getattr(libwagma, name), name
 

@@ -156,6 +156,12 @@ OPTION_SETS = [
     ((lw.WAGMA_OPT_TILE_MAJOR, 1),),
     ((lw.WAGMA_OPT_WAVES, 2),),
     ((lw.WAGMA_OPT_WAVES, 4),),
+    ((lw.WAGMA_OPT_STRIPE_LOG2, 3),),
+    ((lw.WAGMA_OPT_XCD_CHUNK_LOG2, 1),),
+    ((lw.WAGMA_OPT_XCD_CHUNK_LOG2, 8), (lw.WAGMA_OPT_STRIPE_LOG2, 2), (lw.WAGMA_OPT_BLOCK, 512)),
+    ((lw.WAGMA_OPT_XCD_CHUNK_LOG2, 13), (lw.WAGMA_OPT_FORCE_STREAM, 1)),
+    ((lw.WAGMA_OPT_STRIPE_LOG2, 6), (lw.WAGMA_OPT_BLOCK, 512)),
+    ((lw.WAGMA_OPT_STRIPE_LOG2, 16), (lw.WAGMA_OPT_XCD_SWIZZLE, 1)),
     ((lw.WAGMA_OPT_BLOCK, 512), (lw.WAGMA_OPT_XCD_SWIZZLE, 1), (lw.WAGMA_OPT_TILE_MAJOR, 1),
      (lw.WAGMA_OPT_FORCE_STREAM, 1), (lw.WAGMA_OPT_WAVES, 4), (lw.WAGMA_OPT_NONTEMPORAL, 0)),
 ]
@@ -261,6 +267,35 @@ def test_runs_on_a_side_stream():
         assert_same_bits(w.cpu().numpy()[:, :n], ow[:, :n], "w")
 
 
+def test_library_allocator_small_arrays():
+    """Arrays under 1 GiB get plain allocations; the views behave like any other buffer."""
+    P, S, n = 16, 4, 30001
+    with lw.Wagma(P, S, n, 3) as ctx:
+        w, g, m, pub = ctx.alloc_placed()
+        info = ctx.placement_info()
+        assert info["candidates"] == 0 and info["regions"] == 1
+        assert w.shape == (P, ctx.ld) and w.is_cuda and w.dtype == torch.float32
+        assert len({x.data_ptr() for x in (w, g, m, pub)}) == 4
+        with pytest.raises(lw.WagmaError):
+            ctx.alloc_placed()                       # one set per context
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(3)
+        for x in (w, m, pub):
+            x.normal_(0.0, 0.05, generator=gen)
+        ow, om, opub = (x.cpu().numpy().copy() for x in (w, m, pub))
+        for t in range(4):
+            g.normal_(0.0, 1e-2, generator=gen)
+            mask = ctx.stale_mask(9, t, 1 << 30)
+            ctx.step(w, g, m, pub, mask, LR, MU, t)
+            orc.step_f32(P, S, 3, t, ow, g.cpu().numpy(), om, opub, mask, LR, MU, n=n)
+            torch.cuda.synchronize()
+            assert_same_bits(w.cpu().numpy()[:, :n], ow[:, :n], "w at t=%d" % t)
+        del w, g, m, pub
+        ctx.free_placed()
+        w2 = ctx.alloc_placed()                      # and again after freeing
+        del w2
+
+
 # ------------------------------------------------------------------ the five workloads
 
 def test_workload_1_full_tensors():
@@ -296,7 +331,7 @@ def test_workload_1_full_tensors():
                     assert torch.equal(w[int(grp[0]), :n], w[int(grp[1]), :n])
 
 
-def sampled_parity(index, iters=None, count=40000):
+def sampled_parity(index, iters=None, count=40000, placed=False):
     """Full-size run in bench.py's launch configuration; the oracle follows a column sample
     (columns are independent of one another) through every iteration."""
     wl = wk.workload(index)
@@ -304,7 +339,13 @@ def sampled_parity(index, iters=None, count=40000):
     say("workload %d sampled: %s, %d iterations, %d columns" % (index, wl.name, iters, count))
     P, S, n = wl.P, wl.S, wl.n
     with lw.Wagma(P, S, n, wl.tau) as ctx:
-        w, g, m, pub = ctx.alloc()
+        if placed:
+            w, g, m, pub = ctx.alloc_placed()
+            info = ctx.placement_info()
+            say("placement:", info)
+            assert info["candidates"] >= 1 and 1 <= info["regions"] <= 3
+        else:
+            w, g, m, pub = ctx.alloc()
         wk.fill_initial_state(wl, w, m, pub)
         cols = wk.sample_columns(n, count, wl.seed).cuda()
         ow, om, opub = (np.ascontiguousarray(x[:, cols].cpu().numpy()) for x in (w, m, pub))
@@ -332,7 +373,7 @@ def sampled_parity(index, iters=None, count=40000):
         say("workload %d: bit-exact on %d columns x %d iterations; |f32-f64|/max|w| <= %.2e"
             % (index, cols.numel(), iters, worst))
         assert worst <= 1e-6
-    del w, g, m, pub
+        del w, g, m, pub
     torch.cuda.empty_cache()
 
 
@@ -346,6 +387,11 @@ def test_workload_3_sampled():
 
 def test_workload_4_sampled():
     sampled_parity(4)
+
+
+def test_workload_4_sampled_library_allocator():
+    """The configuration bench.py times: arrays placed by wagma_alloc_buffers."""
+    sampled_parity(4, placed=True)
 
 
 def test_workload_5_sampled():
