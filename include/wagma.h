@@ -140,8 +140,9 @@ int wagma_stale_mask(const wagma_ctx* ctx, uint64_t seed, int64_t iter,
  * sustain about 20% less bandwidth than write streams spread over two or three regions, and
  * the step writes w, m and pub of all member rows at once.  This call therefore allocates
  * candidate arrays one after another, times a small write kernel on pairs of them to learn
- * which ones share a region, keeps three that do not (for w, m, pub; g may lie anywhere) and
- * frees the rest.  Arrays under 1 GiB, or a GPU without enough free memory to look around,
+ * which ones share a region, keeps three that do not (for w, m, pub) and one that shares the
+ * region of w (for g: the read-only array is best next to w and worst next to pub), and frees
+ * the rest.  Arrays under 1 GiB, or a GPU without enough free memory to look around,
  * get plain allocations.  Synchronises the device; writes zeros into parts of the new arrays.
  * One set of buffers per context: a second call before wagma_free_buffers is WAGMA_EINVAL.
  * wagma_destroy frees buffers that are still allocated.
@@ -149,10 +150,10 @@ int wagma_stale_mask(const wagma_ctx* ctx, uint64_t seed, int64_t iter,
 int wagma_alloc_buffers(wagma_ctx* ctx, float** w, float** g, float** m, float** pub);
 int wagma_free_buffers(wagma_ctx* ctx);
 /* What the last wagma_alloc_buffers found (any pointer may be NULL): allocations tried, how
- * many of w, m, pub lie in pairwise different regions (1..3), and the probe's write rate in
- * GB/s inside one region and across two (0 when unknown). */
-int wagma_placement_info(const wagma_ctx* ctx, int* candidates, int* regions, double* same_gbs,
-                         double* split_gbs);
+ * many of w, m, pub lie in pairwise different regions (1..3), whether g lies in the region of
+ * w (1/0), and the probe's write rate in GB/s inside one region and across two (0 = unknown). */
+int wagma_placement_info(const wagma_ctx* ctx, int* candidates, int* regions, int* g_with_w,
+                         double* same_gbs, double* split_gbs);
 
 /* Tuning knobs; the defaults are the measured best on MI355X.  Results do not
  * depend on them (same summation order in every variant). */

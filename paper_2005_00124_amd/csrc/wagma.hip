@@ -25,6 +25,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -329,7 +330,6 @@ __global__ void build_schedule_table(int32_t* table, int P, int G, int g, int pe
 // The probe must write well beyond the 256 MB Infinity Cache to see the HBM at all.
 constexpr size_t kProbeSideMax = size_t(1) << 30;            // bytes written through each pointer
 constexpr size_t kPlacementMinBytes = size_t(1) << 30;       // smaller arrays are not placed
-constexpr double kProbeFastRatio = 1.10;                     // "different region" if this much faster
 constexpr int kMaxCandidates = 64;
 
 __global__ void __launch_bounds__(256) placement_probe(float* a, float* b, uint32_t vec_per_stream)
@@ -365,6 +365,146 @@ double probe_gbs(float* a, float* b, size_t side_bytes, hipEvent_t start, hipEve
     }
     return 2.0 * 4.0 * 16.0 * (double)vec / (best_ms * 1e-3) / 1e9;
 }
+
+// The region search of wagma_alloc_buffers.  Candidates are whole arrays allocated one after
+// another (the driver hands out physical memory in address order, so later candidates lie
+// further on).  Probe rates fall into two clusters about 18% apart: both pointers in one
+// region (slow) or in two regions (fast).  The threshold between them is re-estimated from
+// all rates measured so far (the split of the sorted rates that maximises the between-class
+// variance), and the roles are re-derived from the stored measurements after every new
+// candidate, so that an unlucky first candidate cannot mislead the search.
+struct RegionSearch {
+    static constexpr double kMinSpread = 1.13;  // below this max/min ratio only one cluster was seen
+    float* cand[kMaxCandidates];
+    double self[kMaxCandidates], ends[kMaxCandidates];
+    double cross[kMaxCandidates][kMaxCandidates];  // 0 = not measured yet
+    double vals[kMaxCandidates * 8];
+    int n = 0, n_vals = 0;
+    double threshold = 1e30;  // rates below: same region; at or above: different regions
+    double slow_mean = 0.0, fast_mean = 0.0;
+    size_t side = 0, tail = 0;
+    hipEvent_t start = nullptr, stop = nullptr;
+    int w = -1, m = -1, pub = -1, g = -1;  // indices into cand[]
+    bool failed = false;
+
+    void see(double v)
+    {
+        if (v <= 0.0) {
+            failed = true;
+            return;
+        }
+        if (n_vals < kMaxCandidates * 8)
+            vals[n_vals++] = v;
+        double sorted[kMaxCandidates * 8];
+        for (int i = 0; i < n_vals; ++i)
+            sorted[i] = vals[i];
+        for (int i = 1; i < n_vals; ++i) {  // insertion sort: a few hundred values at most
+            const double x = sorted[i];
+            int j = i - 1;
+            while (j >= 0 && sorted[j] > x) {
+                sorted[j + 1] = sorted[j];
+                --j;
+            }
+            sorted[j + 1] = x;
+        }
+        double total = 0.0;
+        for (int i = 0; i < n_vals; ++i)
+            total += sorted[i];
+        slow_mean = total / n_vals;
+        fast_mean = 0.0;
+        threshold = 1e30;
+        if (sorted[n_vals - 1] < kMinSpread * sorted[0])
+            return;
+        double best = -1.0, low_sum = 0.0;
+        for (int k = 1; k < n_vals; ++k) {  // k values in the slow class
+            low_sum += sorted[k - 1];
+            const double mean_lo = low_sum / k, mean_hi = (total - low_sum) / (n_vals - k);
+            const double score = (double)k * (n_vals - k) * (mean_hi - mean_lo) * (mean_hi - mean_lo);
+            if (score > best) {
+                best = score;
+                threshold = 0.5 * (sorted[k - 1] + sorted[k]);
+                slow_mean = mean_lo;
+                fast_mean = mean_hi;
+            }
+        }
+    }
+    void add(float* c)
+    {
+        cand[n] = c;
+        for (int k = 0; k <= n; ++k)
+            cross[n][k] = cross[k][n] = 0.0;
+        if (n == 0) {
+            // The clocks of an idle GPU take a while to come up: time nothing before that.
+            for (int rep = 0; rep < 40; ++rep)
+                (void)probe_gbs(c, c + side / sizeof(float), side, start, stop);
+        }
+        self[n] = probe_gbs(c, c + side / sizeof(float), side, start, stop);
+        see(self[n]);
+        ends[n] = probe_gbs(c, c + tail, side, start, stop);
+        see(ends[n]);
+        ++n;
+        if (n > 1)
+            (void)between(0, n - 1);  // one rate per candidate that does not depend on the roles
+    }
+    void report() const
+    {
+        std::fprintf(stderr, "wagma placement: %d candidates, threshold %.0f GB/s (slow %.0f, fast %.0f), "
+                             "w=%d g=%d m=%d pub=%d\n", n, threshold, slow_mean, fast_mean, w, g, m, pub);
+        for (int i = 0; i < n; ++i) {
+            std::fprintf(stderr, "  cand %2d %p self %.0f ends %.0f cross:", i, (void*)cand[i], self[i], ends[i]);
+            for (int j = 0; j < n; ++j)
+                if (cross[i][j] != 0.0)
+                    std::fprintf(stderr, " %d:%.0f", j, cross[i][j]);
+            std::fprintf(stderr, "\n");
+        }
+    }
+    double between(int i, int j)
+    {
+        if (cross[i][j] == 0.0) {
+            cross[i][j] = cross[j][i] = probe_gbs(cand[i], cand[j], side, start, stop);
+            see(cross[i][j]);
+        }
+        return cross[i][j];
+    }
+    // a candidate that straddles two regions is of no use
+    bool clean(int i) const { return self[i] < threshold && ends[i] < threshold; }
+    // Greedy roles in allocation order; repeated while new probes keep moving the threshold.
+    void assign()
+    {
+        for (int round = 0; round < 8 && !failed; ++round) {
+            const double threshold_before = threshold;
+            w = m = pub = g = -1;
+            for (int i = 0; i < n && !failed; ++i) {
+                if (!clean(i))
+                    continue;
+                if (w < 0) {
+                    w = i;
+                    continue;
+                }
+                const int placed[3] = {w, m, pub};
+                bool apart = true, with_w = false;
+                for (int k = 0; k < 3 && placed[k] >= 0; ++k) {
+                    if (between(placed[k], i) < threshold) {
+                        apart = false;
+                        if (k == 0)
+                            with_w = true;
+                    }
+                }
+                if (apart && m < 0)
+                    m = i;
+                else if (apart && pub < 0)
+                    pub = i;
+                else if (with_w && g < 0)
+                    g = i;
+            }
+            if (threshold == threshold_before)
+                break;  // the yardstick did not move: the roles stand
+        }
+        if (threshold > 1e29)
+            m = pub = -1;  // only one cluster seen: nothing is known to be apart
+    }
+    bool complete() const { return w >= 0 && m >= 0 && pub >= 0 && g >= 0; }
+};
 
 int exact_log2(int64_t x)
 {
@@ -448,6 +588,7 @@ struct wagma_ctx {
     float* placed[4];        // w, g, m, pub handed out by wagma_alloc_buffers (or all NULL)
     int place_candidates;    // allocations tried by the last wagma_alloc_buffers
     int place_regions;       // how many of w, m, pub lie in pairwise different regions (1..3)
+    int place_g_with_w;      // 1 if g was found a place in the region of w
     double place_same_gbs;   // probe rate inside one region
     double place_split_gbs;  // probe rate between the regions of w and m (0 if not separated)
 };
@@ -474,8 +615,14 @@ int wagma_create(wagma_ctx** out, int P, int S, int64_t n, int tau)
     ctx->tau = tau;
     ctx->n = n;
     ctx->period = (g == 0 || G == 0) ? 1 : G / gcd_int(g, G);
-    // Rows start on 256-byte boundaries so that every wavefront access is aligned.
-    ctx->ld = (n + 63) / 64 * 64;
+    // Row stride.  Measured on MI355X: rows on 16 KiB boundaries run about 1% faster than rows
+    // on 256 B boundaries (and rows off a 128 B boundary up to 10% slower); strides that are a
+    // multiple of 1 MiB put all member rows of a group on the same memory channels (20% slower),
+    // so such a stride is skewed by a few row alignments.  Small models keep the padding small.
+    const int64_t row_align = n >= (int64_t(1) << 20) ? 4096 : 64;  // floats
+    ctx->ld = (n + row_align - 1) / row_align * row_align;
+    if ((ctx->ld * 4) % (int64_t(1) << 20) == 0)
+        ctx->ld += 5 * row_align;
     // measured best on MI355X for the P=64, S=8, 25.6M-parameter workload
     ctx->opt_block = 512;
     ctx->opt_nontemporal = 1;
@@ -491,6 +638,7 @@ int wagma_create(wagma_ctx** out, int P, int S, int64_t n, int tau)
         ctx->placed[k] = nullptr;
     ctx->place_candidates = 0;
     ctx->place_regions = 0;
+    ctx->place_g_with_w = 0;
     ctx->place_same_gbs = 0.0;
     ctx->place_split_gbs = 0.0;
 
@@ -696,76 +844,80 @@ int wagma_alloc_buffers(wagma_ctx* ctx, float** w, float** g, float** m, float**
     const size_t bytes = (size_t)ctx->P * (size_t)ctx->ld * sizeof(float);
     ctx->place_candidates = 0;
     ctx->place_regions = 1;
+    ctx->place_g_with_w = 0;
     ctx->place_same_gbs = 0.0;
     ctx->place_split_gbs = 0.0;
 
-    float* chosen[3] = {nullptr, nullptr, nullptr};  // w, m, pub
-    int n_chosen = 0;
+    float* chosen[3] = {nullptr, nullptr, nullptr};  // w, m, pub: pairwise different regions
+    float* grad = nullptr;  // g: read only; best in the region of w (never in that of pub)
     float* spare[kMaxCandidates];
     int n_spare = 0;
     int rc = WAGMA_OK;
 
     if (bytes >= kPlacementMinBytes) {
-        hipEvent_t start = nullptr, stop = nullptr;
-        if (hipEventCreate(&start) == hipSuccess && hipEventCreate(&stop) == hipSuccess) {
+        RegionSearch* rs = new (std::nothrow) RegionSearch();
+        if (rs && hipEventCreate(&rs->start) == hipSuccess && hipEventCreate(&rs->stop) == hipSuccess) {
             // each probe writes `side` bytes through either pointer: at most half an array
-            size_t side = bytes / 2 < kProbeSideMax ? bytes / 2 : kProbeSideMax;
-            side = side / 1024 * 1024;
-            const size_t tail = (bytes - side) / sizeof(float) / 4 * 4;
-            while (n_chosen < 3 && ctx->place_candidates < kMaxCandidates) {
+            rs->side = bytes / 2 < kProbeSideMax ? bytes / 2 : kProbeSideMax;
+            rs->side = rs->side / 1024 * 1024;
+            rs->tail = (bytes - rs->side) / sizeof(float) / 4 * 4;
+            while (!rs->complete() && !rs->failed && rs->n < kMaxCandidates) {
                 size_t free_b = 0, total_b = 0;
                 if (hipMemGetInfo(&free_b, &total_b) != hipSuccess || free_b < 3 * bytes)
-                    break;  // keep room for the gradient array and for the caller
+                    break;  // keep room for the caller
                 float* c = nullptr;
                 if (hipMalloc((void**)&c, bytes) != hipSuccess) {
                     (void)hipGetLastError();
                     break;
                 }
-                ++ctx->place_candidates;
-                const double self = probe_gbs(c, c + side / sizeof(float), side, start, stop);
-                const double ends = probe_gbs(c, c + tail, side, start, stop);
-                bool take = self > 0.0 && ends > 0.0;
-                if (take && ctx->place_same_gbs == 0.0)
-                    ctx->place_same_gbs = self;
-                // a candidate that straddles two regions is of no use
-                if (take && ends > kProbeFastRatio * ctx->place_same_gbs)
-                    take = false;
-                for (int k = 0; take && k < n_chosen; ++k) {
-                    const double cross = probe_gbs(chosen[k], c, side, start, stop);
-                    if (cross < kProbeFastRatio * ctx->place_same_gbs)
-                        take = false;  // same region as an array already placed
-                    else if (k == 0 && n_chosen == 1)
-                        ctx->place_split_gbs = cross;
-                }
-                if (take)
-                    chosen[n_chosen++] = c;
-                else
-                    spare[n_spare++] = c;  // held for now, so that the next candidate lies further on
+                rs->add(c);
+                rs->assign();
             }
-            ctx->place_regions = n_chosen > 0 ? n_chosen : 1;
+            if (std::getenv("WAGMA_DEBUG_PLACEMENT"))
+                rs->report();
+            ctx->place_candidates = rs->n;
+            ctx->place_same_gbs = rs->slow_mean;
+            ctx->place_split_gbs = rs->fast_mean;
+            ctx->place_regions = (rs->w >= 0) + (rs->m >= 0) + (rs->pub >= 0);
+            if (ctx->place_regions == 0)
+                ctx->place_regions = 1;
+            ctx->place_g_with_w = rs->g >= 0;
+            for (int i = 0; i < rs->n; ++i) {
+                if (i == rs->w)
+                    chosen[0] = rs->cand[i];
+                else if (i == rs->m)
+                    chosen[1] = rs->cand[i];
+                else if (i == rs->pub)
+                    chosen[2] = rs->cand[i];
+                else if (i == rs->g)
+                    grad = rs->cand[i];
+                else
+                    spare[n_spare++] = rs->cand[i];
+            }
         }
-        if (start)
-            (void)hipEventDestroy(start);
-        if (stop)
-            (void)hipEventDestroy(stop);
+        if (rs) {
+            if (rs->start)
+                (void)hipEventDestroy(rs->start);
+            if (rs->stop)
+                (void)hipEventDestroy(rs->stop);
+            delete rs;
+        }
     }
-    // whatever could not be separated takes any spare candidate, then a fresh allocation
-    for (int k = n_chosen; k < 3 && rc == WAGMA_OK; ++k) {
+    // whatever could not be placed takes any spare candidate, then a fresh allocation
+    float** missing[4] = {&chosen[0], &chosen[1], &chosen[2], &grad};
+    for (int k = 0; k < 4 && rc == WAGMA_OK; ++k) {
+        if (*missing[k])
+            continue;
         if (n_spare > 0) {
-            chosen[k] = spare[--n_spare];
-        } else if ((e = hipMalloc((void**)&chosen[k], bytes)) != hipSuccess) {
-            chosen[k] = nullptr;
+            *missing[k] = spare[--n_spare];
+        } else if ((e = hipMalloc((void**)missing[k], bytes)) != hipSuccess) {
+            *missing[k] = nullptr;
             g_last_hip_error = (int)e;
             rc = e == hipErrorOutOfMemory ? WAGMA_ENOMEM : WAGMA_EHIP;
         }
     }
     for (int k = 0; k < n_spare; ++k)
         (void)hipFree(spare[k]);
-    float* grad = nullptr;
-    if (rc == WAGMA_OK && (e = hipMalloc((void**)&grad, bytes)) != hipSuccess) {
-        g_last_hip_error = (int)e;
-        rc = e == hipErrorOutOfMemory ? WAGMA_ENOMEM : WAGMA_EHIP;
-    }
     if (rc == WAGMA_OK && (e = hipDeviceSynchronize()) != hipSuccess)
         rc = hip_failed(e);
     if (rc != WAGMA_OK) {
@@ -800,11 +952,13 @@ int wagma_free_buffers(wagma_ctx* ctx)
     return rc;
 }
 
-int wagma_placement_info(const wagma_ctx* ctx, int* candidates, int* regions, double* same_gbs,
-                         double* split_gbs)
+int wagma_placement_info(const wagma_ctx* ctx, int* candidates, int* regions, int* g_with_w,
+                         double* same_gbs, double* split_gbs)
 {
     if (!ctx)
         return WAGMA_EINVAL;
+    if (g_with_w)
+        *g_with_w = ctx->place_g_with_w;
     if (candidates)
         *candidates = ctx->place_candidates;
     if (regions)

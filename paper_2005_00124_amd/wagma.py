@@ -42,8 +42,8 @@ SYMBOLS = {
     "wagma_alloc_buffers": (ctypes.c_int, [ctypes.c_void_p] + [ctypes.POINTER(ctypes.c_void_p)] * 4),
     "wagma_free_buffers": (ctypes.c_int, [ctypes.c_void_p]),
     "wagma_placement_info": (ctypes.c_int, [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int),
-                                            ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_double),
-                                            ctypes.POINTER(ctypes.c_double)]),
+                                            ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int),
+                                            ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]),
     "wagma_set_option": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64]),
     "wagma_strerror": (ctypes.c_char_p, [ctypes.c_int]),
     "wagma_last_hip_error": (ctypes.c_int, []),
@@ -173,11 +173,11 @@ def wagma_free_buffers(ctx: int) -> None:
 
 
 def wagma_placement_info(ctx: int) -> dict:
-    cand, regions = ctypes.c_int(), ctypes.c_int()
+    cand, regions, g_with_w = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
     same, split = ctypes.c_double(), ctypes.c_double()
-    _check(load().wagma_placement_info(ctx, ctypes.byref(cand), ctypes.byref(regions),
+    _check(load().wagma_placement_info(ctx, ctypes.byref(cand), ctypes.byref(regions), ctypes.byref(g_with_w),
                                        ctypes.byref(same), ctypes.byref(split)), "wagma_placement_info")
-    return {"candidates": cand.value, "regions": regions.value,
+    return {"candidates": cand.value, "regions": regions.value, "g_with_w": bool(g_with_w.value),
             "probe_same_region_gbs": same.value, "probe_two_regions_gbs": split.value}
 
 
