@@ -39,11 +39,8 @@ def build(force: bool = False) -> str:
 _lib = None
 
 
-def _load():
-    global _lib
-    if _lib is not None:
-        return _lib
-    lib = ctypes.CDLL(build())
+def bind(lib: ctypes.CDLL) -> ctypes.CDLL:
+    """Attach the C signatures to a loaded oracle library."""
     i32p = ctypes.POINTER(ctypes.c_int32)
     u64p = ctypes.POINTER(ctypes.c_uint64)
     f32p = ctypes.POINTER(ctypes.c_float)
@@ -63,8 +60,14 @@ def _load():
               lib.oracle_is_global_iteration, lib.oracle_step_f32,
               lib.oracle_step_f64, lib.oracle_stale_mask):
         f.restype = ctypes.c_int
-    _lib = lib
     return lib
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = bind(ctypes.CDLL(build()))
+    return _lib
 
 
 def _check(rc: int, what: str) -> None:

@@ -1,0 +1,66 @@
+"""The pins have teeth: a mistake planted in a copy of the oracle (on the CPU) fails its pin.
+
+Each case edits one expression of ``oracle/wagma_oracle.c`` in a temporary copy, compiles it
+with the oracle's own flags and runs one pin from ``test_oracle_pins`` against it.
+"""
+import ctypes
+import os
+import subprocess
+
+import pytest
+
+from oracle import wagma_oracle as orc
+import test_oracle_pins as pins
+
+SRC = os.path.join(os.path.dirname(os.path.abspath(orc.__file__)), "wagma_oracle.c")
+
+MUTATIONS = [
+    ("late divisor S instead of S+1",
+     "/ (float)(S + 1);", "/ (float)(S);", pins.test_stale_rule_hand_value),
+    ("sign of the learning rate",
+     "fmaf(-lr, m_new, w[at])", "fmaf(lr, m_new, w[at])", pins.test_local_update_hand_value),
+    ("cumulative mask in Algorithm 1",
+     "int mask = 1 << shift;", "static int mask; if (r == 1) mask = 1; mask <<= shift;",
+     pins.test_alg1_printed_example_p8_s4),
+    ("momentum line not fused",
+     "float m_new = fmaf(mu, m[at], g[at]);", "float m_new = mu * m[at] + g[at];",
+     pins.test_update_lines_are_fused),
+    ("global iteration on t mod tau",
+     "((t + 1) % tau) == 0", "(t % tau) == 0", pins.test_global_iteration_predicate),
+    ("left-to-right sum",
+     "float right = tree_sum_f32(c + count / 2, count / 2);",
+     "float right = 0; for (int i = count / 2; i < count; ++i) left += c[i];",
+     pins.test_sum_is_a_pairwise_tree_in_member_order),
+    ("late member contributes W' instead of its send buffer",
+     "? pub[(int64_t)p * ld + j] /* send buffer */", "? w_prime[p]", pins.test_stale_rule_hand_value),
+    ("reciprocal multiply for 1/(S+1)",
+     "w[at] = (w_sum + w_prime[p]) / (float)(S + 1);",
+     "w[at] = (w_sum + w_prime[p]) * (1.0f / (float)(S + 1));",
+     pins.test_stale_divisor_is_a_true_division),
+    ("member digits in reverse phase order",
+     "p |= 1 << bits[r];\n            table", "p |= 1 << bits[group_phases - 1 - r];\n            table",
+     pins.test_alg1_phase_bits_wrap_order),
+    ("send buffer gets W instead of W'",
+     "        /* the send buffer now holds this iteration's locally updated model */\n"
+     "        for (int i = 0; i < P; ++i)\n            pub[(int64_t)i * ld + j] = w_prime[i];",
+     "        for (int i = 0; i < P; ++i)\n            pub[(int64_t)i * ld + j] = w[(int64_t)i * ld + j];",
+     pins.test_stale_rule_hand_value),
+    ("global average ignores half of the replicas",
+     "float sum = tree_sum_f32(w_prime, P);", "float sum = 2.0f * tree_sum_f32(w_prime, P / 2 ? P / 2 : 1);",
+     pins.test_snapshot_script_p4_s2_f32),
+]
+
+
+@pytest.mark.parametrize("name,old,new,pin", MUTATIONS, ids=[m[0] for m in MUTATIONS])
+def test_planted_mistake_is_caught(name, old, new, pin, tmp_path, monkeypatch):
+    text = open(SRC).read()
+    assert text.count(old) >= 1, "the oracle no longer contains the expression this case edits"
+    src = tmp_path / "mutant.c"
+    src.write_text(text.replace(old, new, 1))
+    lib = tmp_path / "mutant.so"
+    subprocess.run(["gcc", *orc.CFLAGS, "-o", str(lib), str(src), "-lm"], check=True)
+    monkeypatch.setattr(orc, "_lib", orc.bind(ctypes.CDLL(str(lib))))
+    with pytest.raises(AssertionError):
+        pin()
+    monkeypatch.undo()
+    pin()     # and the real oracle passes it

@@ -261,6 +261,19 @@ def test_snapshot_script_p4_s2():
     assert np.allclose(w, w[0, 0]) and np.ptp(w) == 0.0
 
 
+def test_snapshot_script_p4_s2_f32():
+    """The same script in fp32, ending in a global iteration: all replicas get the mean of W'."""
+    P, S = 4, 2
+    w, pub = rows(1, 2, 3, 4), rows(1, 20, 3, 4)
+    m, g = rows(0, 0, 0, 0), rows(2, 2, 2, 2)
+    late = np.array([False, True, False, False])
+    orc.step_f32(P, S, 0, 0, w, g, m, pub, late, 0.5, 0.0)
+    assert w.ravel().tolist() == [10.0, float(f32(21.0) / f32(3.0)), 2.5, 2.5]
+    before = w.astype(np.float64).ravel() - 1.0
+    orc.step_f32(P, S, 2, 1, w, g, m, pub, late, 0.5, 0.0)         # (1+1) mod 2 == 0: global
+    assert np.all(w == f32(before.sum() / 4)) and abs(float(w[0, 0]) - before.mean()) < 1e-6
+
+
 def test_sum_is_a_pairwise_tree_in_member_order():
     """(1 + e) + (e + e) = 1 + 2e in fp32 with e = 2^-24, while a left-to-right sum gives 1."""
     e = 2.0 ** -24
