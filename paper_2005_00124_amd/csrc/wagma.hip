@@ -185,6 +185,8 @@ __global__ void __launch_bounds__(BLOCK, WAVES) step_rows_in_registers(const Ste
         if (late[e])
             contrib[e] = load4<NT>(p.pub + row_at[e] + lane_at);  // send buffer of a late process
 
+    // (Issuing the loads and stores one array at a time instead of row by row was measured:
+    // no difference.)
 #pragma unroll
     for (int e = 0; e < S; ++e) {
         const v4f m_new = fma4(p.mu, mv[e], gv[e]);
@@ -374,7 +376,7 @@ double probe_gbs(float* a, float* b, size_t side_bytes, hipEvent_t start, hipEve
 // variance), and the roles are re-derived from the stored measurements after every new
 // candidate, so that an unlucky first candidate cannot mislead the search.
 struct RegionSearch {
-    static constexpr double kMinSpread = 1.13;  // below this max/min ratio only one cluster was seen
+    static constexpr double kMinSpread = 1.10;  // cluster means closer than this: only one cluster was seen
     float* cand[kMaxCandidates];
     double self[kMaxCandidates], ends[kMaxCandidates];
     double cross[kMaxCandidates][kMaxCandidates];  // 0 = not measured yet
@@ -416,16 +418,23 @@ struct RegionSearch {
         if (sorted[n_vals - 1] < kMinSpread * sorted[0])
             return;
         double best = -1.0, low_sum = 0.0;
+        double split_at = 1e30, mean_lo_best = slow_mean, mean_hi_best = 0.0;
         for (int k = 1; k < n_vals; ++k) {  // k values in the slow class
             low_sum += sorted[k - 1];
             const double mean_lo = low_sum / k, mean_hi = (total - low_sum) / (n_vals - k);
             const double score = (double)k * (n_vals - k) * (mean_hi - mean_lo) * (mean_hi - mean_lo);
             if (score > best) {
                 best = score;
-                threshold = 0.5 * (sorted[k - 1] + sorted[k]);
-                slow_mean = mean_lo;
-                fast_mean = mean_hi;
+                split_at = 0.5 * (sorted[k - 1] + sorted[k]);
+                mean_lo_best = mean_lo;
+                mean_hi_best = mean_hi;
             }
+        }
+        // two real clusters are about 18% apart; a split of mere noise is not
+        if (mean_hi_best >= kMinSpread * mean_lo_best) {
+            threshold = split_at;
+            slow_mean = mean_lo_best;
+            fast_mean = mean_hi_best;
         }
     }
     void add(float* c)
