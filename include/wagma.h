@@ -71,6 +71,23 @@ int64_t wagma_row_stride(const wagma_ctx* ctx);
 /* Override the row stride (before the first step): ld >= 4*ceil(n/4), ld % 4 == 0. */
 int wagma_set_row_stride(wagma_ctx* ctx, int64_t ld);
 
+/*
+ * The paper's family of variants (Section 4, the paragraph on the four parameters tau, alpha,
+ * beta, S; Section 6.2, the four ablation experiments) is reached through the arguments:
+ *   wait-avoiding group allreduce (alpha)      a stale_mask with late processes
+ *   plain group allreduce (beta)               stale_mask = NULL
+ *   local SGD with period tau (ablation 1)     S = 1
+ *   global model averaging every step          tau = 1   (or S = P: ablation 3)
+ *   smaller groups (ablation 4)                S
+ *   no periodic synchronisation                tau = 0
+ *   fixed groups (ablation 2)                  wagma_set_grouping(ctx, WAGMA_GROUPING_FIXED):
+ *       every group iteration uses the groups of iteration 0 instead of Algorithm 1's
+ *       rotation; global iterations are unchanged.
+ */
+#define WAGMA_GROUPING_DYNAMIC 0 /* Algorithm 1 (default) */
+#define WAGMA_GROUPING_FIXED 1   /* the groups of iteration 0, always */
+int wagma_set_grouping(wagma_ctx* ctx, int mode);
+
 /* Number of distinct group schedules: the schedule of iteration t equals that
  * of iteration t + period.  period = G / gcd(g, G) with G = log2 P, g = log2 S
  * (the starting phase of Algorithm 1, line 3, is (t*g) mod G). */

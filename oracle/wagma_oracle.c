@@ -202,10 +202,13 @@ static int mask_bit(const uint64_t *stale_mask, int p)
  * w, g, m, pub: P rows of ld floats, n used columns.  w, m, pub are updated
  * in place; g is read only.  stale_mask: bit p set = process p is late in
  * this iteration (NULL = nobody).
+ * fixed_groups != 0 is the paper's second ablation (Section 6.2): group model
+ * averaging without the dynamic grouping strategy, i.e. the groups of
+ * iteration 0 in every group iteration.
  */
 int oracle_step_f32(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
                     float *w, const float *g, float *m, float *pub,
-                    const uint64_t *stale_mask, float lr, float mu)
+                    const uint64_t *stale_mask, float lr, float mu, int fixed_groups)
 {
     if (exact_log2(P) < 0 || exact_log2(S) < 0 || S > P || n < 1 || ld < n ||
         tau < 0 || t < 0 || !w || !g || !m || !pub)
@@ -222,7 +225,7 @@ int oracle_step_f32(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
     }
     int global = oracle_is_global_iteration(tau, t);
     if (!global)
-        oracle_member_table(P, S, t, table);
+        oracle_member_table(P, S, fixed_groups ? 0 : t, table);
 
     for (int64_t j = 0; j < n; ++j) {
         /* lines 6-7: local update of every replica */
@@ -272,7 +275,7 @@ int oracle_step_f32(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
 /* The same iteration carried in fp64 (a shadow used to bound rounding). */
 int oracle_step_f64(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
                     double *w, const double *g, double *m, double *pub,
-                    const uint64_t *stale_mask, double lr, double mu)
+                    const uint64_t *stale_mask, double lr, double mu, int fixed_groups)
 {
     if (exact_log2(P) < 0 || exact_log2(S) < 0 || S > P || n < 1 || ld < n ||
         tau < 0 || t < 0 || !w || !g || !m || !pub)
@@ -289,7 +292,7 @@ int oracle_step_f64(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
     }
     int global = oracle_is_global_iteration(tau, t);
     if (!global)
-        oracle_member_table(P, S, t, table);
+        oracle_member_table(P, S, fixed_groups ? 0 : t, table);
 
     for (int64_t j = 0; j < n; ++j) {
         for (int i = 0; i < P; ++i) {

@@ -50,10 +50,10 @@ def bind(lib: ctypes.CDLL) -> ctypes.CDLL:
     lib.oracle_is_global_iteration.argtypes = [ctypes.c_int, ctypes.c_int64]
     lib.oracle_step_f32.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
                                     ctypes.c_int, ctypes.c_int64, f32p, f32p, f32p, f32p, u64p,
-                                    ctypes.c_float, ctypes.c_float]
+                                    ctypes.c_float, ctypes.c_float, ctypes.c_int]
     lib.oracle_step_f64.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
                                     ctypes.c_int, ctypes.c_int64, f64p, f64p, f64p, f64p, u64p,
-                                    ctypes.c_double, ctypes.c_double]
+                                    ctypes.c_double, ctypes.c_double, ctypes.c_int]
     lib.oracle_stale_mask.argtypes = [ctypes.c_uint64, ctypes.c_int64, ctypes.c_int,
                                       ctypes.c_uint32, u64p]
     for f in (lib.oracle_grouping_unionfind, lib.oracle_member_table,
@@ -113,7 +113,7 @@ def mask_words(stale) -> np.ndarray | None:
     return words
 
 
-def _step(fn, ctype, dtype, P, S, tau, t, w, g, m, pub, stale, lr, mu, n=None):
+def _step(fn, ctype, dtype, P, S, tau, t, w, g, m, pub, stale, lr, mu, n=None, fixed_groups=False):
     for name, a in (("w", w), ("g", g), ("m", m), ("pub", pub)):
         if a.dtype != dtype or a.ndim != 2 or a.shape[0] != P or not a.flags.c_contiguous:
             raise ValueError("%s must be a C-contiguous (P, ld) %s array" % (name, dtype))
@@ -129,19 +129,20 @@ def _step(fn, ctype, dtype, P, S, tau, t, w, g, m, pub, stale, lr, mu, n=None):
               w.ctypes.data_as(ptr), g.ctypes.data_as(ptr), m.ctypes.data_as(ptr),
               pub.ctypes.data_as(ptr),
               None if words is None else words.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64)),
-              lr, mu), "step")
+              lr, mu, 1 if fixed_groups else 0), "step")
 
 
-def step_f32(P, S, tau, t, w, g, m, pub, stale, lr, mu, n=None) -> None:
-    """One iteration of Algorithm 2 (lines 6-17) in fp32, in place."""
+def step_f32(P, S, tau, t, w, g, m, pub, stale, lr, mu, n=None, fixed_groups=False) -> None:
+    """One iteration of Algorithm 2 (lines 6-17) in fp32, in place.
+    fixed_groups: the groups of iteration 0 every time (Section 6.2, second ablation)."""
     _step(_load().oracle_step_f32, ctypes.c_float, np.float32,
-          P, S, tau, t, w, g, m, pub, stale, lr, mu, n)
+          P, S, tau, t, w, g, m, pub, stale, lr, mu, n, fixed_groups)
 
 
-def step_f64(P, S, tau, t, w, g, m, pub, stale, lr, mu, n=None) -> None:
+def step_f64(P, S, tau, t, w, g, m, pub, stale, lr, mu, n=None, fixed_groups=False) -> None:
     """The same iteration carried in fp64 (rounding shadow)."""
     _step(_load().oracle_step_f64, ctypes.c_double, np.float64,
-          P, S, tau, t, w, g, m, pub, stale, lr, mu, n)
+          P, S, tau, t, w, g, m, pub, stale, lr, mu, n, fixed_groups)
 
 
 def stale_mask(seed: int, t: int, P: int, threshold: int) -> np.ndarray:

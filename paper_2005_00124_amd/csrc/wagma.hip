@@ -590,6 +590,7 @@ void launch_block(const StepParams& p, bool streamed, int block, int waves, unsi
 
 struct wagma_ctx {
     int P, S, G, g, tau, period, device;
+    int fixed_groups;  // 1: every group iteration uses the groups of iteration 0
     int64_t n, ld;
     int32_t* d_table;  // (period + 1) * P, device
     int32_t* h_table;  // host mirror
@@ -641,6 +642,7 @@ int wagma_create(wagma_ctx** out, int P, int S, int64_t n, int tau)
     ctx->opt_waves = 2;
     ctx->opt_stripe_log2 = 2;
     ctx->opt_xcd_chunk_log2 = 2;
+    ctx->fixed_groups = 0;
     ctx->d_table = nullptr;
     ctx->h_table = nullptr;
     for (int k = 0; k < 4; ++k)
@@ -714,6 +716,14 @@ int wagma_set_row_stride(wagma_ctx* ctx, int64_t ld)
     return WAGMA_OK;
 }
 
+int wagma_set_grouping(wagma_ctx* ctx, int mode)
+{
+    if (!ctx || (mode != WAGMA_GROUPING_DYNAMIC && mode != WAGMA_GROUPING_FIXED))
+        return WAGMA_EINVAL;
+    ctx->fixed_groups = mode == WAGMA_GROUPING_FIXED;
+    return WAGMA_OK;
+}
+
 int wagma_schedule_period(const wagma_ctx* ctx)
 {
     return ctx ? ctx->period : WAGMA_EINVAL;
@@ -732,7 +742,7 @@ int wagma_group_schedule(const wagma_ctx* ctx, int64_t iter, const int32_t** dev
     const int global = wagma_is_global_iteration(ctx, iter);
     if (global < 0)
         return global;
-    const int64_t row = global ? ctx->period : iter % ctx->period;
+    const int64_t row = global ? ctx->period : (ctx->fixed_groups ? 0 : iter % ctx->period);
     if (dev_table)
         *dev_table = ctx->d_table + row * ctx->P;
     if (host_table)

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_PKG, "libwagma.so")
 
 WAGMA_OK, WAGMA_EINVAL, WAGMA_EHIP, WAGMA_ENOMEM = 0, -1, -2, -3
 WAGMA_MAX_P = 1024
+WAGMA_GROUPING_DYNAMIC, WAGMA_GROUPING_FIXED = 0, 1
 WAGMA_OPT_BLOCK, WAGMA_OPT_NONTEMPORAL, WAGMA_OPT_FORCE_STREAM = 1, 2, 3
 WAGMA_OPT_XCD_SWIZZLE, WAGMA_OPT_TILE_MAJOR, WAGMA_OPT_WAVES, WAGMA_OPT_STRIPE_LOG2 = 4, 5, 6, 7
 WAGMA_OPT_XCD_CHUNK_LOG2 = 8
@@ -31,6 +32,7 @@ SYMBOLS = {
     "wagma_destroy": (ctypes.c_int, [ctypes.c_void_p]),
     "wagma_row_stride": (ctypes.c_int64, [ctypes.c_void_p]),
     "wagma_set_row_stride": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int64]),
+    "wagma_set_grouping": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int]),
     "wagma_schedule_period": (ctypes.c_int, [ctypes.c_void_p]),
     "wagma_group_schedule": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int64, _i32pp, _i32pp]),
     "wagma_is_global_iteration": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int64]),
@@ -114,6 +116,10 @@ def wagma_row_stride(ctx: int) -> int:
 
 def wagma_set_row_stride(ctx: int, ld: int) -> None:
     _check(load().wagma_set_row_stride(ctx, ld), "wagma_set_row_stride")
+
+
+def wagma_set_grouping(ctx: int, mode: int) -> None:
+    _check(load().wagma_set_grouping(ctx, mode), "wagma_set_grouping")
 
 
 def wagma_schedule_period(ctx: int) -> int:
@@ -208,6 +214,9 @@ class Wagma:
 
     def set_row_stride(self, ld: int) -> None:
         wagma_set_row_stride(self.ctx, ld)
+
+    def set_grouping(self, mode: int) -> None:
+        wagma_set_grouping(self.ctx, mode)
 
     def set_option(self, option: int, value: int) -> None:
         wagma_set_option(self.ctx, option, value)

@@ -45,7 +45,7 @@ def random_state(P, ld, n, seed, device="cuda"):
     return w, g, m, pub, gen
 
 
-def run_case(P, S, n, tau, iters, q, seed, options=(), ld=None, t0=0):
+def run_case(P, S, n, tau, iters, q, seed, options=(), ld=None, t0=0, fixed_groups=False):
     say("case P=%d S=%d n=%d tau=%d iters=%d q=%.2f seed=%d options=%s ld=%s"
         % (P, S, n, tau, iters, q, seed, options, ld))
     with lw.Wagma(P, S, n, tau) as ctx:
@@ -53,6 +53,8 @@ def run_case(P, S, n, tau, iters, q, seed, options=(), ld=None, t0=0):
             ctx.set_row_stride(ld)
         for opt, val in options:
             ctx.set_option(opt, val)
+        if fixed_groups:
+            ctx.set_grouping(lw.WAGMA_GROUPING_FIXED)
         ld = ctx.ld
         w, g, m, pub, gen = random_state(P, ld, n, seed)
         ow, om, opub = (x.cpu().numpy().copy() for x in (w, m, pub))
@@ -67,10 +69,13 @@ def run_case(P, S, n, tau, iters, q, seed, options=(), ld=None, t0=0):
             if t % 5 == 3:                       # everybody late, the degenerate extreme
                 mask = orc.mask_words(np.ones(P, dtype=bool))
             ctx.step(w, g, m, pub, mask, LR, MU, t)
-            orc.step_f32(P, S, tau, t, ow, og, om, opub, mask, LR, MU, n=n)
+            orc.step_f32(P, S, tau, t, ow, og, om, opub, mask, LR, MU, n=n, fixed_groups=fixed_groups)
             torch.cuda.synchronize()
             for have, want, what in ((w, ow, "w"), (m, om, "m"), (pub, opub, "pub")):
                 assert_same_bits(have.cpu().numpy()[:, :n], want[:, :n], "%s at t=%d" % (what, t))
+            if fixed_groups and not ctx.is_global(t):
+                _, host = ctx.group_schedule(t)
+                assert np.array_equal(host, orc.member_table(P, S, 0).ravel())
         for x, k in zip((w, m, pub), keep_pad):
             assert torch.equal(x[:, pad0:], k), "padding beyond 4*ceil(n/4) was written"
         assert torch.equal(g.cpu(), torch.from_numpy(og)), "g was written"
@@ -180,6 +185,22 @@ def test_degenerate_parameters():
     run_case(8, 2, 2049, tau=1, iters=5, q=0.5, seed=23)       # always global
     run_case(16, 4, 2049, tau=10, iters=3, q=1.0, seed=24)     # everybody late every iteration
     run_case(16, 4, 2049, tau=10, iters=4, q=0.2, seed=25, t0=10 ** 12)   # huge iteration numbers
+
+
+def test_variant_family():
+    """The paper's family (Section 4: tau, alpha, beta, S; Section 6.2: the ablations)."""
+    run_case(64, 8, 4099, tau=4, iters=6, q=0.3, seed=31, fixed_groups=True)    # ablation 2
+    run_case(32, 8, 4099, tau=0, iters=6, q=0.3, seed=32, fixed_groups=True)    # period 5 schedule frozen
+    run_case(16, 1, 4099, tau=5, iters=6, q=0.0, seed=33)                        # ablation 1: local SGD
+    run_case(64, 64, 4099, tau=0, iters=3, q=0.0, seed=34)                       # ablation 3: S = P
+    run_case(64, 4, 4099, tau=10, iters=3, q=0.25, seed=35)                      # ablation 4: S = 4
+    run_case(16, 4, 4099, tau=1, iters=3, q=0.25, seed=36)                       # averaging every step
+    with lw.Wagma(8, 2, 16, 0) as ctx:
+        with pytest.raises(lw.WagmaError):
+            ctx.set_grouping(7)
+        ctx.set_grouping(lw.WAGMA_GROUPING_FIXED)
+        ctx.set_grouping(lw.WAGMA_GROUPING_DYNAMIC)
+        assert not np.array_equal(ctx.group_schedule(0)[1], ctx.group_schedule(1)[1])
 
 
 def test_subnormals_and_specials():

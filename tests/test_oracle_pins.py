@@ -472,3 +472,68 @@ def test_lateness_rate_and_extremes():
     assert not np.array_equal(a, orc.stale_mask(3, 6, P, 1 << 31))
     assert not np.array_equal(a, orc.stale_mask(4, 5, P, 1 << 31))
     assert np.array_equal(a, orc.stale_mask(3, 5, P, 1 << 31))
+
+
+# ------------------------------------------------- the family of variants (Sections 4 and 6.2)
+
+def test_fixed_groups_ablation():
+    """Second ablation of Section 6.2: without the rotation the groups of iteration 0 are used
+    every time, so with lr = 0 a second averaging changes nothing and the replicas never mix
+    beyond their fixed group (only the global average mixes them)."""
+    P, S = 16, 4
+    rng = np.random.default_rng(11)
+    w0 = rng.integers(-32, 32, size=(P, 7)).astype(np.float32)
+    w = w0.copy()
+    g, m, pub = np.zeros_like(w), np.zeros_like(w), w.copy()
+    orc.step_f32(P, S, 0, 0, w, g, m, pub, None, 0.0, 0.9, fixed_groups=True)
+    first = w.copy()
+    groups = orc.member_table(P, S, 0)
+    for grp in groups:
+        assert np.array_equal(first[grp], np.broadcast_to(w0[grp].mean(axis=0), (S, 7)))
+    for t in range(1, 6):
+        orc.step_f32(P, S, 0, t, w, g, m, pub, None, 0.0, 0.9, fixed_groups=True)
+        assert np.array_equal(w, first)
+    assert len({tuple(r) for r in w.tolist()}) == P // S           # still P/S distinct models
+    orc.step_f32(P, S, 3, 8, w, g, m, pub, None, 0.0, 0.9, fixed_groups=True)   # (8+1) mod 3 == 0
+    assert np.all(w == w[0:1])
+    # with the rotation the same start mixes completely in two group iterations
+    w = w0.copy()
+    pub = w.copy()
+    for t in range(2):
+        orc.step_f32(P, S, 0, t, w, g, m, pub, None, 0.0, 0.9)
+    assert np.all(w == w[0:1])
+
+
+def test_fixed_groups_brute_force():
+    P, S, n = 8, 2, 9
+    rng = np.random.default_rng(12)
+    w = rng.normal(0, 1, (P, n)).astype(np.float32).astype(np.float64)
+    m = rng.normal(0, 0.1, (P, n)).astype(np.float32).astype(np.float64)
+    pub = rng.normal(0, 1, (P, n)).astype(np.float32).astype(np.float64)
+    lr, mu = float(f32(0.1)), float(f32(0.9))
+    for t in range(5):
+        g = rng.normal(0, 0.5, (P, n)).astype(np.float32).astype(np.float64)
+        stale = rng.random(P) < 0.3
+        # the brute force of iteration 0's phase bits, whatever t is
+        want_w, want_m, want_pub = brute_force_step(P, S, 0, 0, w, g, m, pub, stale, lr, mu)
+        orc.step_f64(P, S, 0, t, w, g, m, pub, stale, lr, mu, fixed_groups=True)
+        for have, want in ((w, want_w), (m, want_m), (pub, want_pub)):
+            assert np.allclose(have, want, rtol=0, atol=1e-12)
+
+
+def test_local_sgd_is_group_size_one():
+    """First ablation of Section 6.2: no group collectives = local SGD with period tau."""
+    P, n, tau = 4, 5, 3
+    rng = np.random.default_rng(13)
+    w = rng.normal(0, 1, (P, n))
+    m = np.zeros_like(w)
+    pub = w.copy()
+    ref_w, ref_m = w.copy(), m.copy()
+    for t in range(6):
+        g = rng.normal(0, 1, (P, n))
+        orc.step_f64(P, 1, tau, t, w, g, m, pub, None, 0.1, 0.9)
+        ref_m = 0.9 * ref_m + g
+        ref_w = ref_w - 0.1 * ref_m
+        if (t + 1) % tau == 0:
+            ref_w = np.broadcast_to(ref_w.mean(axis=0), ref_w.shape).copy()
+        assert np.allclose(w, ref_w, rtol=0, atol=1e-12) and np.allclose(m, ref_m, rtol=0, atol=1e-12)
