@@ -141,6 +141,29 @@ int wagma_step(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub,
                void* stream);
 
 /*
+ * Per-tensor layout.  Training frameworks keep a model as a list of tensors (the ResNet-50 of
+ * Section 6.2 has 161, each replica its own set), not as one flat row.  A plan describes
+ * where they are; wagma_step_tensors then does exactly what wagma_step does (same arithmetic,
+ * same order, same results) on that layout.
+ *   T       number of tensors per replica, >= 1.
+ *   sizes   host, T entries: floats in tensor k; their sum must be the n of wagma_create.
+ *   w, g, m, pub   host arrays of P*T DEVICE pointers; entry p*T + k is tensor k of process p.
+ *           Every pointer 16-byte aligned; tensors must not overlap one another.  Sizes need
+ *           not be multiples of 4: nothing beyond a tensor's last element is read or written.
+ * wagma_tensors_create copies the tables to the device (allocation, copy and synchronisation
+ * happen here, none in the step); the plan refers to ctx and to the tensors, which must stay
+ * where they are while the plan is used.  Destroy the plan before its context.
+ */
+typedef struct wagma_tensors wagma_tensors;
+int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64_t* sizes,
+                         float* const* w, const float* const* g, float* const* m, float* const* pub);
+int wagma_tensors_destroy(wagma_tensors* plan);
+/* One iteration of Algorithm 2 (lines 6-17) on the tensors of `plan`; stale_mask, lr, mu, iter
+ * and stream as for wagma_step.  Launch only: no allocation, copy or synchronisation. */
+int wagma_step_tensors(wagma_ctx* ctx, const wagma_tensors* plan, const uint64_t* stale_mask,
+                       float lr, float mu, int64_t iter, void* stream);
+
+/*
  * Seeded lateness model (not from the paper, whose lateness is physical; its
  * simulation delays random ranks, Section 6.2): process p is late in iteration
  * iter iff the upper 32 bits of a 64-bit hash of (seed, iter, p) are below

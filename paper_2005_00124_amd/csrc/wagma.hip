@@ -44,6 +44,12 @@ constexpr int64_t kMaxN = int64_t(1) << 31;
 
 thread_local int g_last_hip_error = 0;
 
+struct TileRef {
+    int32_t tensor;       // which tensor a tile of the per-tensor layout belongs to
+    int32_t reserved;
+    int64_t first_slice;  // first 16-byte slice of the tile inside that tensor
+};
+
 struct StepParams {
     float* w;
     const float* g;
@@ -65,27 +71,42 @@ struct StepParams {
     int tile_major;        // 1: consecutive blocks walk the groups of one column tile
     int stripe_log2;       // log2 of the distance, in KiB, between a workgroup's wavefronts
     int xcd_chunk_log2;    // log2 of the run of consecutive tiles one XCD works on (0: 1 tile)
+    // per-tensor layout only (device tables)
+    float* const* tw;            // [P][T] base pointers, index rank * T + tensor
+    const float* const* tg;
+    float* const* tm;
+    float* const* tpub;
+    const TileRef* tile_ref;     // [tiles]
+    const int64_t* tensor_size;  // [T] floats
+    int num_tensors;
 };
 
-template <bool NT>
-__device__ __forceinline__ v4f load4(const float* p)
+// Element types of the kernel bodies: v4f (one 16-byte column slice) and float
+// (the ragged last elements of a tensor in the per-tensor layout).
+template <bool NT, typename V>
+__device__ __forceinline__ V load_v(const float* p)
 {
     if (NT)
-        return __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
-    return *reinterpret_cast<const v4f*>(p);
+        return __builtin_nontemporal_load(reinterpret_cast<const V*>(p));
+    return *reinterpret_cast<const V*>(p);
 }
 
-template <bool NT>
-__device__ __forceinline__ void store4(float* p, v4f v)
+template <bool NT, typename V>
+__device__ __forceinline__ void store_v(float* p, V v)
 {
     if (NT)
-        __builtin_nontemporal_store(v, reinterpret_cast<v4f*>(p));
+        __builtin_nontemporal_store(v, reinterpret_cast<V*>(p));
     else
-        *reinterpret_cast<v4f*>(p) = v;
+        *reinterpret_cast<V*>(p) = v;
 }
 
-// a*b + c with one rounding per lane (Algorithm 2 lines 6-7 are two of these).
-__device__ __forceinline__ v4f fma4(float a, v4f b, v4f c)
+// a*b + c with one rounding per element (Algorithm 2 lines 6-7 are two of these).
+__device__ __forceinline__ float fma_v(float a, float b, float c)
+{
+    return __builtin_fmaf(a, b, c);
+}
+
+__device__ __forceinline__ v4f fma_v(float a, v4f b, v4f c)
 {
     v4f r;
     r.x = __builtin_fmaf(a, b.x, c.x);
@@ -102,15 +123,149 @@ __device__ __forceinline__ bool is_late(const StepParams& p, int rank)
 
 // Balanced pairwise sum of N = 2^k values: adjacent members first, i.e. the
 // butterfly phases of Section 3.3 in the order Algorithm 1 runs them.
-template <int N>
-__device__ __forceinline__ v4f tree_sum(const v4f* c)
+template <int N, typename V>
+__device__ __forceinline__ V tree_sum(const V* c)
 {
     if constexpr (N == 1) {
         return c[0];
     } else {
-        v4f left = tree_sum<N / 2>(c);
-        v4f right = tree_sum<N / 2>(c + N / 2);
+        V left = tree_sum<N / 2, V>(c);
+        V right = tree_sum<N / 2, V>(c + N / 2);
         return left + right;
+    }
+}
+
+// Where the lane's element of a rank's row lives.  Flat layout: P rows of ld floats;
+// the row base is wave-uniform (scalar registers) and the lane adds one 32-bit offset.
+struct FlatAddr {
+    const StepParams& p;
+    uint32_t lane_at;  // float index inside the row
+    __device__ __forceinline__ float* w(int rank) const { return p.w + (int64_t)rank * p.ld + lane_at; }
+    __device__ __forceinline__ const float* g(int rank) const { return p.g + (int64_t)rank * p.ld + lane_at; }
+    __device__ __forceinline__ float* m(int rank) const { return p.m + (int64_t)rank * p.ld + lane_at; }
+    __device__ __forceinline__ float* pub(int rank) const { return p.pub + (int64_t)rank * p.ld + lane_at; }
+};
+
+// Per-tensor layout: a table of P x T base pointers per array; the lane adds its
+// float index inside the tensor.
+struct TensorAddr {
+    const StepParams& p;
+    int tensor;
+    uint32_t lane_at;
+    __device__ __forceinline__ int64_t slot(int rank) const { return (int64_t)rank * p.num_tensors + tensor; }
+    __device__ __forceinline__ float* w(int rank) const { return p.tw[slot(rank)] + lane_at; }
+    __device__ __forceinline__ const float* g(int rank) const { return p.tg[slot(rank)] + lane_at; }
+    __device__ __forceinline__ float* m(int rank) const { return p.tm[slot(rank)] + lane_at; }
+    __device__ __forceinline__ float* pub(int rank) const { return p.tpub[slot(rank)] + lane_at; }
+};
+
+// One group of S <= 8 members, all member rows held in registers.
+template <int S, bool NT, typename V, typename Addr>
+__device__ __forceinline__ void registers_body(const StepParams& p, const int32_t* member, const Addr& at)
+{
+    bool late[S];
+    int rank[S];
+    V wv[S], gv[S], mv[S], contrib[S];
+#pragma unroll
+    for (int e = 0; e < S; ++e) {
+        rank[e] = member[e];
+        late[e] = is_late(p, rank[e]);
+        wv[e] = load_v<NT, V>(at.w(rank[e]));
+        gv[e] = load_v<NT, V>(at.g(rank[e]));
+        mv[e] = load_v<NT, V>(at.m(rank[e]));
+    }
+#pragma unroll
+    for (int e = 0; e < S; ++e)
+        if (late[e])
+            contrib[e] = load_v<NT, V>(at.pub(rank[e]));  // the send buffer of a late process
+
+    // (Issuing the loads and stores one array at a time instead of row by row was measured:
+    // no difference.)
+#pragma unroll
+    for (int e = 0; e < S; ++e) {
+        const V m_new = fma_v(p.mu, mv[e], gv[e]);
+        wv[e] = fma_v(-p.lr, m_new, wv[e]);  // W'
+        store_v<NT, V>(at.m(rank[e]), m_new);
+        store_v<NT, V>(at.pub(rank[e]), wv[e]);
+        if (!late[e])
+            contrib[e] = wv[e];
+    }
+    const V w_sum = tree_sum<S, V>(contrib);
+#pragma unroll
+    for (int e = 0; e < S; ++e) {
+        V out;
+        if (late[e])
+            out = (w_sum + wv[e]) / p.members_plus_1;
+        else
+            out = w_sum * p.inv_members;
+        store_v<NT, V>(at.w(rank[e]), out);
+    }
+}
+
+// One group of any size >= 8: member rows streamed 8 at a time.
+template <bool NT, typename V, typename Addr>
+__device__ __forceinline__ void streamed_body(const StepParams& p, const int32_t* member, const Addr& at)
+{
+    const int chunks = p.members / kChunk;
+    V stack[kStackDepth];
+    V acc;
+    for (int c = 0; c < chunks; ++c) {
+        int rank[kChunk];
+        bool late[kChunk];
+        V wv[kChunk], gv[kChunk], mv[kChunk], contrib[kChunk];
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i) {
+            rank[i] = member[c * kChunk + i];
+            late[i] = is_late(p, rank[i]);
+            wv[i] = load_v<NT, V>(at.w(rank[i]));
+            gv[i] = load_v<NT, V>(at.g(rank[i]));
+            mv[i] = load_v<NT, V>(at.m(rank[i]));
+        }
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i)
+            if (late[i])
+                contrib[i] = load_v<NT, V>(at.pub(rank[i]));
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i) {
+            const V m_new = fma_v(p.mu, mv[i], gv[i]);
+            wv[i] = fma_v(-p.lr, m_new, wv[i]);
+            store_v<NT, V>(at.m(rank[i]), m_new);
+            store_v<NT, V>(at.pub(rank[i]), wv[i]);
+            if (!late[i])
+                contrib[i] = wv[i];
+        }
+        acc = tree_sum<kChunk, V>(contrib);
+        // Binary-counter carry: after chunk c the stack holds one partial sum per set
+        // bit of c+1, so equal-sized neighbours are always added left + right.
+        bool carry = true;
+#pragma unroll
+        for (int l = 0; l < kStackDepth; ++l) {
+            if (carry) {
+                if ((c >> l) & 1) {
+                    acc = stack[l] + acc;
+                } else {
+                    stack[l] = acc;
+                    carry = false;
+                }
+            }
+        }
+    }
+    V w_sum = acc;
+#pragma unroll
+    for (int l = 0; l < kStackDepth; ++l)
+        if (l == p.log2_chunks)
+            w_sum = stack[l];
+    const V fresh = w_sum * p.inv_members;
+
+    for (int e = 0; e < p.members; ++e) {
+        const int rank = member[e];
+        V out = fresh;
+        if (is_late(p, rank)) {
+            // W' of this member: this thread stored it to the send buffer above.
+            const V w_prime = load_v<false, V>(at.pub(rank));
+            out = (w_sum + w_prime) / p.members_plus_1;
+        }
+        store_v<NT, V>(at.w(rank), out);
     }
 }
 
@@ -164,48 +319,8 @@ __global__ void __launch_bounds__(BLOCK, WAVES) step_rows_in_registers(const Ste
     int64_t group, col;
     if (!decode_block<BLOCK>(p, group, col))
         return;
-    const int32_t* member = p.table + group * S;
-    // Row bases are wave-uniform (scalar registers); the lane adds one 32-bit offset.
-    const uint32_t lane_at = (uint32_t)col * 4u;
-
-    bool late[S];
-    int64_t row_at[S];
-    v4f wv[S], gv[S], mv[S], contrib[S];
-#pragma unroll
-    for (int e = 0; e < S; ++e) {
-        const int rank = member[e];
-        row_at[e] = (int64_t)rank * p.ld;
-        late[e] = is_late(p, rank);
-        wv[e] = load4<NT>(p.w + row_at[e] + lane_at);
-        gv[e] = load4<NT>(p.g + row_at[e] + lane_at);
-        mv[e] = load4<NT>(p.m + row_at[e] + lane_at);
-    }
-#pragma unroll
-    for (int e = 0; e < S; ++e)
-        if (late[e])
-            contrib[e] = load4<NT>(p.pub + row_at[e] + lane_at);  // send buffer of a late process
-
-    // (Issuing the loads and stores one array at a time instead of row by row was measured:
-    // no difference.)
-#pragma unroll
-    for (int e = 0; e < S; ++e) {
-        const v4f m_new = fma4(p.mu, mv[e], gv[e]);
-        wv[e] = fma4(-p.lr, m_new, wv[e]);  // W'
-        store4<NT>(p.m + row_at[e] + lane_at, m_new);
-        store4<NT>(p.pub + row_at[e] + lane_at, wv[e]);
-        if (!late[e])
-            contrib[e] = wv[e];
-    }
-    const v4f w_sum = tree_sum<S>(contrib);
-#pragma unroll
-    for (int e = 0; e < S; ++e) {
-        v4f out;
-        if (late[e])
-            out = (w_sum + wv[e]) / p.members_plus_1;
-        else
-            out = w_sum * p.inv_members;
-        store4<NT>(p.w + row_at[e] + lane_at, out);
-    }
+    const FlatAddr at{p, (uint32_t)col * 4u};
+    registers_body<S, NT, v4f>(p, p.table + group * S, at);
 }
 
 template <bool NT, int BLOCK, int WAVES>
@@ -214,71 +329,53 @@ __global__ void __launch_bounds__(BLOCK, WAVES) step_rows_streamed(const StepPar
     int64_t group, col;
     if (!decode_block<BLOCK>(p, group, col))
         return;
-    const int32_t* member = p.table + group * p.members;
-    const uint32_t lane_at = (uint32_t)col * 4u;
-    const int chunks = p.members / kChunk;
+    const FlatAddr at{p, (uint32_t)col * 4u};
+    streamed_body<NT, v4f>(p, p.table + group * p.members, at);
+}
 
-    v4f stack[kStackDepth];
-    v4f acc;
-    for (int c = 0; c < chunks; ++c) {
-        int64_t row_at[kChunk];
-        bool late[kChunk];
-        v4f wv[kChunk], gv[kChunk], mv[kChunk], contrib[kChunk];
-#pragma unroll
-        for (int i = 0; i < kChunk; ++i) {
-            const int rank = member[c * kChunk + i];
-            row_at[i] = (int64_t)rank * p.ld;
-            late[i] = is_late(p, rank);
-            wv[i] = load4<NT>(p.w + row_at[i] + lane_at);
-            gv[i] = load4<NT>(p.g + row_at[i] + lane_at);
-            mv[i] = load4<NT>(p.m + row_at[i] + lane_at);
-        }
-#pragma unroll
-        for (int i = 0; i < kChunk; ++i)
-            if (late[i])
-                contrib[i] = load4<NT>(p.pub + row_at[i] + lane_at);
-#pragma unroll
-        for (int i = 0; i < kChunk; ++i) {
-            const v4f m_new = fma4(p.mu, mv[i], gv[i]);
-            wv[i] = fma4(-p.lr, m_new, wv[i]);
-            store4<NT>(p.m + row_at[i] + lane_at, m_new);
-            store4<NT>(p.pub + row_at[i] + lane_at, wv[i]);
-            if (!late[i])
-                contrib[i] = wv[i];
-        }
-        acc = tree_sum<kChunk>(contrib);
-        // Binary-counter carry: after chunk c the stack holds one partial sum per set
-        // bit of c+1, so equal-sized neighbours are always added left + right.
-        bool carry = true;
-#pragma unroll
-        for (int l = 0; l < kStackDepth; ++l) {
-            if (carry) {
-                if ((c >> l) & 1) {
-                    acc = stack[l] + acc;
-                } else {
-                    stack[l] = acc;
-                    carry = false;
-                }
-            }
+// Per-tensor layout.  Workgroup b owns tile b % tiles of group b / tiles; the tile table
+// names the tensor and the tile's first 16-byte slice inside it.  A lane whose slice is
+// cut off by the end of the tensor does the remaining 1..3 elements one by one; nothing
+// beyond a tensor's last element is touched.
+template <int S, bool NT, int BLOCK>
+__global__ void __launch_bounds__(BLOCK, 2) step_tensors_in_registers(const StepParams p)
+{
+    const int64_t group = blockIdx.x / p.tiles;
+    const TileRef ref = p.tile_ref[blockIdx.x % p.tiles];
+    const int64_t size = p.tensor_size[ref.tensor];
+    const int64_t first = (ref.first_slice + threadIdx.x) * 4;
+    if (first >= size)
+        return;
+    const int32_t* member = p.table + group * S;
+    TensorAddr at{p, ref.tensor, (uint32_t)first};
+    if (first + 4 <= size) {
+        registers_body<S, NT, v4f>(p, member, at);
+    } else {
+        for (int64_t k = first; k < size; ++k) {
+            at.lane_at = (uint32_t)k;
+            registers_body<S, NT, float>(p, member, at);
         }
     }
-    v4f w_sum = acc;
-#pragma unroll
-    for (int l = 0; l < kStackDepth; ++l)
-        if (l == p.log2_chunks)
-            w_sum = stack[l];
-    const v4f fresh = w_sum * p.inv_members;
+}
 
-    for (int e = 0; e < p.members; ++e) {
-        const int rank = member[e];
-        const int64_t row_at = (int64_t)rank * p.ld;
-        v4f out = fresh;
-        if (is_late(p, rank)) {
-            // W' of this member: this thread stored it to the send buffer above.
-            const v4f w_prime = load4<false>(p.pub + row_at + lane_at);
-            out = (w_sum + w_prime) / p.members_plus_1;
+template <bool NT, int BLOCK>
+__global__ void __launch_bounds__(BLOCK, 2) step_tensors_streamed(const StepParams p)
+{
+    const int64_t group = blockIdx.x / p.tiles;
+    const TileRef ref = p.tile_ref[blockIdx.x % p.tiles];
+    const int64_t size = p.tensor_size[ref.tensor];
+    const int64_t first = (ref.first_slice + threadIdx.x) * 4;
+    if (first >= size)
+        return;
+    const int32_t* member = p.table + group * p.members;
+    TensorAddr at{p, ref.tensor, (uint32_t)first};
+    if (first + 4 <= size) {
+        streamed_body<NT, v4f>(p, member, at);
+    } else {
+        for (int64_t k = first; k < size; ++k) {
+            at.lane_at = (uint32_t)k;
+            streamed_body<NT, float>(p, member, at);
         }
-        store4<NT>(p.w + row_at + lane_at, out);
     }
 }
 
@@ -603,6 +700,62 @@ struct wagma_ctx {
     double place_split_gbs;  // probe rate between the regions of w and m (0 if not separated)
 };
 
+struct wagma_tensors {
+    wagma_ctx* ctx;
+    int T;
+    int64_t tiles;      // workgroups per group
+    void* d_blob;       // one device allocation: four pointer tables, the sizes, the tile table
+    float* const* tw;
+    const float* const* tg;
+    float* const* tm;
+    float* const* tpub;
+    const int64_t* tensor_size;
+    const TileRef* tile_ref;
+};
+
+namespace {
+constexpr int kTensorBlock = 256;  // threads per workgroup of the per-tensor kernels
+
+template <bool NT>
+void launch_tensors(const StepParams& p, unsigned grid, hipStream_t stream)
+{
+    const dim3 g(grid), b(kTensorBlock);
+    switch (p.members) {
+    case 1: hipLaunchKernelGGL((step_tensors_in_registers<1, NT, kTensorBlock>), g, b, 0, stream, p); break;
+    case 2: hipLaunchKernelGGL((step_tensors_in_registers<2, NT, kTensorBlock>), g, b, 0, stream, p); break;
+    case 4: hipLaunchKernelGGL((step_tensors_in_registers<4, NT, kTensorBlock>), g, b, 0, stream, p); break;
+    case 8: hipLaunchKernelGGL((step_tensors_in_registers<8, NT, kTensorBlock>), g, b, 0, stream, p); break;
+    default: hipLaunchKernelGGL((step_tensors_streamed<NT, kTensorBlock>), g, b, 0, stream, p); break;
+    }
+}
+}  // namespace
+
+namespace {
+
+// The part of the kernel arguments that both layouts share.
+void fill_common(const wagma_ctx* ctx, StepParams& p, bool global, const uint64_t* stale_mask,
+                        float lr, float mu, int64_t iter)
+{
+    std::memset(&p, 0, sizeof(p));
+    p.lr = lr;
+    p.mu = mu;
+    p.members = global ? ctx->P : ctx->S;
+    p.inv_members = 1.0f / (float)p.members;
+    p.members_plus_1 = (float)(p.members + 1);
+    const int32_t* table = nullptr;
+    wagma_group_schedule(ctx, iter, &table, nullptr);
+    p.table = table;
+    if (!global && stale_mask) {
+        const int words = (ctx->P + 63) / 64;
+        for (int k = 0; k < words; ++k)
+            p.late[k] = stale_mask[k];
+        if (ctx->P < 64)
+            p.late[0] &= (UINT64_C(1) << ctx->P) - 1;
+    }
+}
+
+}  // namespace
+
 extern "C" {
 
 int wagma_create(wagma_ctx** out, int P, int S, int64_t n, int tau)
@@ -768,30 +921,15 @@ int wagma_step(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub,
         return WAGMA_EINVAL;
 
     StepParams p;
+    fill_common(ctx, p, global != 0, stale_mask, lr, mu, iter);
     p.w = w;
     p.g = g;
     p.m = m;
     p.pub = pub;
     p.ld = ctx->ld;
     p.nvec = (ctx->n + 3) / 4;
-    p.lr = lr;
-    p.mu = mu;
-    p.members = global ? ctx->P : ctx->S;
-    p.inv_members = 1.0f / (float)p.members;
-    p.members_plus_1 = (float)(p.members + 1);
     p.swizzle = ctx->opt_swizzle;
     p.tile_major = ctx->opt_tile_major;
-    const int32_t* table = nullptr;
-    wagma_group_schedule(ctx, iter, &table, nullptr);
-    p.table = table;
-    std::memset(p.late, 0, sizeof(p.late));
-    if (!global && stale_mask) {
-        const int words = (ctx->P + 63) / 64;
-        for (int k = 0; k < words; ++k)
-            p.late[k] = stale_mask[k];
-        if (ctx->P < 64)
-            p.late[0] &= (UINT64_C(1) << ctx->P) - 1;
-    }
 
     const bool streamed = p.members > kChunk || (ctx->opt_force_stream && p.members == kChunk);
     p.log2_chunks = streamed ? exact_log2(p.members / kChunk) : 0;
@@ -816,6 +954,142 @@ int wagma_step(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub,
         launch_block<true>(p, streamed, block, ctx->opt_waves, (unsigned)grid, (hipStream_t)stream);
     else
         launch_block<false>(p, streamed, block, ctx->opt_waves, (unsigned)grid, (hipStream_t)stream);
+    e = hipGetLastError();
+    if (e != hipSuccess)
+        return hip_failed(e);
+    return WAGMA_OK;
+}
+
+// ---- per-tensor layout ------------------------------------------------------------------
+
+int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64_t* sizes,
+                         float* const* w, const float* const* g, float* const* m, float* const* pub)
+{
+    if (!out)
+        return WAGMA_EINVAL;
+    *out = nullptr;
+    if (!ctx || T < 1 || T > (1 << 20) || !sizes || !w || !g || !m || !pub)
+        return WAGMA_EINVAL;
+    int64_t total = 0, tiles = 0;
+    for (int k = 0; k < T; ++k) {
+        if (sizes[k] < 1 || sizes[k] > kMaxN)
+            return WAGMA_EINVAL;
+        total += sizes[k];
+        tiles += ((sizes[k] + 3) / 4 + kTensorBlock - 1) / kTensorBlock;
+    }
+    if (total != ctx->n || tiles * (int64_t)ctx->P > 0x7fffffff)
+        return WAGMA_EINVAL;
+    const size_t slots = (size_t)ctx->P * (size_t)T;
+    for (size_t i = 0; i < slots; ++i) {
+        if (!w[i] || !g[i] || !m[i] || !pub[i])
+            return WAGMA_EINVAL;
+        if ((((uintptr_t)w[i]) | ((uintptr_t)g[i]) | ((uintptr_t)m[i]) | ((uintptr_t)pub[i])) & 15u)
+            return WAGMA_EINVAL;
+    }
+    int device = -1;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess)
+        return hip_failed(e);
+    if (device != ctx->device)
+        return WAGMA_EINVAL;
+
+    // blob layout: [4 pointer tables][T sizes][tiles tile refs]; every part 16-byte aligned
+    const size_t table_bytes = (slots * sizeof(void*) + 15) / 16 * 16;
+    const size_t sizes_bytes = ((size_t)T * sizeof(int64_t) + 15) / 16 * 16;
+    const size_t refs_bytes = (size_t)tiles * sizeof(TileRef);
+    const size_t blob_bytes = 4 * table_bytes + sizes_bytes + refs_bytes;
+    char* host = (char*)std::malloc(blob_bytes);
+    wagma_tensors* plan = new (std::nothrow) wagma_tensors();
+    if (!host || !plan) {
+        std::free(host);
+        delete plan;
+        return WAGMA_ENOMEM;
+    }
+    std::memset(host, 0, blob_bytes);
+    std::memcpy(host + 0 * table_bytes, w, slots * sizeof(void*));
+    std::memcpy(host + 1 * table_bytes, g, slots * sizeof(void*));
+    std::memcpy(host + 2 * table_bytes, m, slots * sizeof(void*));
+    std::memcpy(host + 3 * table_bytes, pub, slots * sizeof(void*));
+    std::memcpy(host + 4 * table_bytes, sizes, (size_t)T * sizeof(int64_t));
+    TileRef* refs = (TileRef*)(host + 4 * table_bytes + sizes_bytes);
+    int64_t at = 0;
+    for (int k = 0; k < T; ++k) {
+        const int64_t slices = (sizes[k] + 3) / 4;
+        for (int64_t first = 0; first < slices; first += kTensorBlock) {
+            refs[at].tensor = k;
+            refs[at].first_slice = first;
+            ++at;
+        }
+    }
+    char* dev = nullptr;
+    e = hipMalloc((void**)&dev, blob_bytes);
+    if (e == hipSuccess)
+        e = hipMemcpy(dev, host, blob_bytes, hipMemcpyHostToDevice);
+    std::free(host);
+    if (e != hipSuccess) {
+        if (dev)
+            (void)hipFree(dev);
+        delete plan;
+        g_last_hip_error = (int)e;
+        return e == hipErrorOutOfMemory ? WAGMA_ENOMEM : WAGMA_EHIP;
+    }
+    plan->ctx = ctx;
+    plan->T = T;
+    plan->tiles = tiles;
+    plan->d_blob = dev;
+    plan->tw = (float* const*)(dev + 0 * table_bytes);
+    plan->tg = (const float* const*)(dev + 1 * table_bytes);
+    plan->tm = (float* const*)(dev + 2 * table_bytes);
+    plan->tpub = (float* const*)(dev + 3 * table_bytes);
+    plan->tensor_size = (const int64_t*)(dev + 4 * table_bytes);
+    plan->tile_ref = (const TileRef*)(dev + 4 * table_bytes + sizes_bytes);
+    *out = plan;
+    return WAGMA_OK;
+}
+
+int wagma_tensors_destroy(wagma_tensors* plan)
+{
+    if (!plan)
+        return WAGMA_OK;
+    int rc = WAGMA_OK;
+    const hipError_t e = hipFree(plan->d_blob);
+    if (e != hipSuccess)
+        rc = hip_failed(e);
+    delete plan;
+    return rc;
+}
+
+int wagma_step_tensors(wagma_ctx* ctx, const wagma_tensors* plan, const uint64_t* stale_mask, float lr,
+                       float mu, int64_t iter, void* stream)
+{
+    const int global = wagma_is_global_iteration(ctx, iter);
+    if (global < 0)
+        return global;
+    if (!plan || plan->ctx != ctx)
+        return WAGMA_EINVAL;
+    int device = -1;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess)
+        return hip_failed(e);
+    if (device != ctx->device)
+        return WAGMA_EINVAL;
+
+    StepParams p;
+    fill_common(ctx, p, global != 0, stale_mask, lr, mu, iter);
+    p.tw = plan->tw;
+    p.tg = plan->tg;
+    p.tm = plan->tm;
+    p.tpub = plan->tpub;
+    p.tensor_size = plan->tensor_size;
+    p.tile_ref = plan->tile_ref;
+    p.num_tensors = plan->T;
+    p.tiles = plan->tiles;
+    p.blocks = (int64_t)(ctx->P / p.members) * p.tiles;
+    p.log2_chunks = p.members > kChunk ? exact_log2(p.members / kChunk) : 0;
+    if (ctx->opt_nontemporal)
+        launch_tensors<true>(p, (unsigned)p.blocks, (hipStream_t)stream);
+    else
+        launch_tensors<false>(p, (unsigned)p.blocks, (hipStream_t)stream);
     e = hipGetLastError();
     if (e != hipSuccess)
         return hip_failed(e);

@@ -39,6 +39,11 @@ SYMBOLS = {
     "wagma_step": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                   ctypes.c_void_p, _u64p, ctypes.c_float, ctypes.c_float,
                                   ctypes.c_int64, ctypes.c_void_p]),
+    "wagma_tensors_create": (ctypes.c_int, [ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p), ctypes.c_int,
+                                            ctypes.POINTER(ctypes.c_int64)] + [ctypes.POINTER(ctypes.c_void_p)] * 4),
+    "wagma_tensors_destroy": (ctypes.c_int, [ctypes.c_void_p]),
+    "wagma_step_tensors": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, _u64p, ctypes.c_float,
+                                          ctypes.c_float, ctypes.c_int64, ctypes.c_void_p]),
     "wagma_stale_mask": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int64,
                                         ctypes.c_uint32, _u64p]),
     "wagma_alloc_buffers": (ctypes.c_int, [ctypes.c_void_p] + [ctypes.POINTER(ctypes.c_void_p)] * 4),
@@ -160,6 +165,31 @@ def wagma_step(ctx: int, w, g, m, pub, stale_mask: Optional[np.ndarray], lr: flo
            "wagma_step")
 
 
+def wagma_tensors_create(ctx: int, sizes, w_ptrs, g_ptrs, m_ptrs, pub_ptrs) -> int:
+    """sizes: T ints; *_ptrs: P*T device addresses each, entry p*T + k = tensor k of process p."""
+    T = len(sizes)
+    c_sizes = (ctypes.c_int64 * T)(*sizes)
+    tables = [(ctypes.c_void_p * len(ptrs))(*ptrs) for ptrs in (w_ptrs, g_ptrs, m_ptrs, pub_ptrs)]
+    out = ctypes.c_void_p()
+    _check(load().wagma_tensors_create(ctx, ctypes.byref(out), T, c_sizes, *tables), "wagma_tensors_create")
+    return out.value
+
+
+def wagma_tensors_destroy(plan: int) -> None:
+    _check(load().wagma_tensors_destroy(plan), "wagma_tensors_destroy")
+
+
+def wagma_step_tensors(ctx: int, plan: int, stale_mask: Optional[np.ndarray], lr: float, mu: float,
+                       it: int, stream: Optional[int] = None) -> None:
+    mask = None
+    if stale_mask is not None:
+        stale_mask = np.ascontiguousarray(stale_mask, dtype=np.uint64)
+        mask = stale_mask.ctypes.data_as(_u64p)
+    if stream is None:
+        stream = _current_stream()
+    _check(load().wagma_step_tensors(ctx, plan, mask, lr, mu, it, stream), "wagma_step_tensors")
+
+
 def wagma_stale_mask(ctx: int, seed: int, it: int, threshold: int, P: int) -> np.ndarray:
     words = np.zeros((P + 63) // 64, dtype=np.uint64)
     _check(load().wagma_stale_mask(ctx, seed, it, threshold, words.ctypes.data_as(_u64p)),
@@ -273,10 +303,56 @@ class Wagma:
             raise ValueError("stale_mask must hold ceil(P/64) words")
         wagma_step(self.ctx, w, g, m, pub, stale_mask, lr, mu, it, stream)
 
+    def tensor_plan(self, w, g, m, pub) -> "TensorPlan":
+        """w, g, m, pub: for every process a list of T one-dimensional fp32 CUDA tensors
+        (the same sizes in every process and every array)."""
+        return TensorPlan(self, w, g, m, pub)
+
     def destroy(self) -> None:
         if self.ctx:
             wagma_destroy(self.ctx)
             self.ctx = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.destroy()
+
+
+class TensorPlan:
+    """Owns one wagma_tensors plan; keeps the tensors alive while the plan exists."""
+
+    def __init__(self, owner: Wagma, w, g, m, pub):
+        import torch
+        self.owner = owner
+        self.keep = (w, g, m, pub)
+        sizes = [int(t.numel()) for t in w[0]]
+        tables = []
+        for arr in (w, g, m, pub):
+            if len(arr) != owner.P:
+                raise ValueError("one tensor list per process expected")
+            flat = []
+            for tensors in arr:
+                if [int(t.numel()) for t in tensors] != sizes:
+                    raise ValueError("every process and array must hold tensors of the same sizes")
+                for t in tensors:
+                    if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous():
+                        raise ValueError("tensors must be contiguous CUDA fp32")
+                    flat.append(t.data_ptr())
+            tables.append(flat)
+        self.plan = wagma_tensors_create(owner.ctx, sizes, *tables)
+
+    def step(self, stale_mask, lr: float, mu: float, it: int, stream: Optional[int] = None) -> None:
+        if stale_mask is not None and len(stale_mask) != (self.owner.P + 63) // 64:
+            raise ValueError("stale_mask must hold ceil(P/64) words")
+        wagma_step_tensors(self.owner.ctx, self.plan, stale_mask, lr, mu, it, stream)
+
+    def destroy(self) -> None:
+        if self.plan:
+            wagma_tensors_destroy(self.plan)
+            self.plan = None
+            self.keep = None
 
     def __enter__(self):
         return self

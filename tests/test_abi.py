@@ -58,6 +58,9 @@ def test_host_side_argument_checks(lib):
     assert lib.wagma_step(None, None, None, None, None, None, 0.1, 0.9, 0, None) == libwagma.WAGMA_EINVAL
     assert lib.wagma_set_option(None, 1, 256) == libwagma.WAGMA_EINVAL
     assert lib.wagma_set_grouping(None, 0) == libwagma.WAGMA_EINVAL
+    assert lib.wagma_tensors_create(None, None, 1, None, None, None, None, None) == libwagma.WAGMA_EINVAL
+    assert lib.wagma_tensors_destroy(None) == libwagma.WAGMA_OK
+    assert lib.wagma_step_tensors(None, None, None, 0.1, 0.9, 0, None) == libwagma.WAGMA_EINVAL
     assert lib.wagma_alloc_buffers(None, None, None, None, None) == libwagma.WAGMA_EINVAL
     assert lib.wagma_free_buffers(None) == libwagma.WAGMA_EINVAL
     assert lib.wagma_placement_info(None, None, None, None, None, None) == libwagma.WAGMA_EINVAL

@@ -1,0 +1,154 @@
+"""GPU parity of the per-tensor entry point (wagma_step_tensors) against the CPU oracle and
+against the flat entry point, through the C-ABI."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import wagma_oracle as orc
+from paper_2005_00124_amd import wagma as lw
+from paper_2005_00124_amd import workloads as wk
+
+pytestmark = pytest.mark.gpu
+LR, MU = 0.1, 0.9
+GUARD = 8        # floats of sentinel before and after every tensor
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def bits(a):
+    return np.ascontiguousarray(a).view(np.uint32)
+
+
+def make_arrays(P, sizes, gen, scale):
+    """For every process a list of tensors, each inside its own guarded allocation."""
+    arrays, guards = [], []
+    for _p in range(P):
+        tensors = []
+        for size in sizes:
+            buf = torch.full((size + 2 * GUARD,), 777.0, device="cuda")
+            t = buf[GUARD:GUARD + size]          # 32-byte offset: still 16-byte aligned
+            t.normal_(0.0, scale, generator=gen)
+            tensors.append(t)
+            guards.append(buf)
+        arrays.append(tensors)
+    return arrays, guards
+
+
+def to_rows(arrays):
+    """(P, n) numpy matrix: the tensors of every process side by side."""
+    return np.stack([torch.cat(t).cpu().numpy() for t in arrays])
+
+
+def run_tensor_case(P, S, sizes, tau, iters, q, seed, fixed_groups=False):
+    say("tensor case P=%d S=%d T=%d n=%d tau=%d iters=%d q=%.2f seed=%d" % (P, S, len(sizes), sum(sizes), tau, iters, q, seed))
+    n = sum(sizes)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    with lw.Wagma(P, S, n, tau) as ctx:
+        if fixed_groups:
+            ctx.set_grouping(lw.WAGMA_GROUPING_FIXED)
+        (w, gw), (g, gg), (m, gm), (pub, gp) = (make_arrays(P, sizes, gen, s) for s in (0.05, 0.01, 0.01, 0.05))
+        ow, om, opub = to_rows(w), to_rows(m), to_rows(pub)
+        thr = min(int(q * 2 ** 32), 2 ** 32 - 1)
+        with ctx.tensor_plan(w, g, m, pub) as plan:
+            for t in range(iters):
+                for tensors in g:
+                    for x in tensors:
+                        x.normal_(0.0, 1e-2, generator=gen)
+                og = to_rows(g)
+                mask = ctx.stale_mask(seed, t, thr)
+                if t % 4 == 2:
+                    mask = orc.mask_words(np.ones(P, dtype=bool))
+                plan.step(mask, LR, MU, t)
+                orc.step_f32(P, S, tau, t, ow, og, om, opub, mask, LR, MU, fixed_groups=fixed_groups)
+                torch.cuda.synchronize()
+                for have, want, what in ((w, ow, "w"), (m, om, "m"), (pub, opub, "pub")):
+                    h = to_rows(have)
+                    assert np.array_equal(bits(h), bits(want)), "%s differs at t=%d" % (what, t)
+        assert np.array_equal(bits(to_rows(g)), bits(og)), "g was written"
+        for buf in gw + gg + gm + gp:
+            assert bool((buf[:GUARD] == 777.0).all()) and bool((buf[-GUARD:] == 777.0).all()), \
+                "an element outside a tensor was written"
+
+
+RAGGED = [1, 2, 3, 4, 5, 7, 64, 255, 257, 1000, 1023, 1025, 4099, 70001]
+
+
+@pytest.mark.parametrize("P,S", [(1, 1), (2, 2), (4, 2), (8, 4), (16, 4), (64, 8), (32, 16), (64, 64), (128, 32)])
+def test_tensors_bit_exact(P, S):
+    sizes = RAGGED if P <= 16 else RAGGED[:-1]
+    run_tensor_case(P, S, sizes, tau=3, iters=5, q=0.3, seed=100 + P + S)
+
+
+def test_tensors_variants():
+    run_tensor_case(16, 4, [33, 1024, 9], tau=0, iters=4, q=1.0, seed=7)            # everybody late
+    run_tensor_case(16, 4, [33, 1024, 9], tau=1, iters=3, q=0.5, seed=8)            # always global
+    run_tensor_case(32, 8, [4097, 130], tau=0, iters=6, q=0.3, seed=9, fixed_groups=True)
+    run_tensor_case(8, 1, [17], tau=2, iters=4, q=0.5, seed=10)                     # one tensor, S = 1
+
+
+def test_plan_validation():
+    P, S = 4, 2
+    sizes = [10, 6]
+    with lw.Wagma(P, S, 16, 0) as ctx:
+        def arrs():
+            return [[torch.zeros(s, device="cuda") for s in sizes] for _ in range(P)]
+        w, g, m, pub = arrs(), arrs(), arrs(), arrs()
+        plan = ctx.tensor_plan(w, g, m, pub)
+        plan.destroy()
+        with pytest.raises(lw.WagmaError):                       # sizes do not add up to n
+            lw.wagma_tensors_create(ctx.ctx, [10, 5], *[[t.data_ptr() for ts in a for t in ts] for a in (w, g, m, pub)])
+        bad = [t.data_ptr() for ts in w for t in ts]
+        bad[3] += 4                                              # misaligned
+        with pytest.raises(lw.WagmaError):
+            lw.wagma_tensors_create(ctx.ctx, sizes, bad, *[[t.data_ptr() for ts in a for t in ts] for a in (g, m, pub)])
+        with pytest.raises(ValueError):
+            ctx.tensor_plan(w[:-1], g, m, pub)
+        with lw.Wagma(P, S, 16, 0) as other:
+            plan = ctx.tensor_plan(w, g, m, pub)
+            assert lw.load().wagma_step_tensors(other.ctx, plan.plan, None, LR, MU, 0, None) == lw.WAGMA_EINVAL
+            plan.destroy()
+
+
+def test_tensor_views_of_workload_2_equal_the_flat_path():
+    """ResNet-50-shaped tensor list (161 tensors) as views into flat rows: the per-tensor entry
+    point and the flat entry point give the same bits on the whole model, and both match the
+    oracle on a column sample."""
+    wl = wk.workload(2)
+    P, S, n = wl.P, wl.S, wl.n
+    tensors = wl.tensors()
+    sizes = [int(np.prod(t[1])) for t in tensors]
+    assert len(sizes) == 161 and sum(sizes) == n
+    say("workload 2 per-tensor vs flat:", wl.name)
+    with lw.Wagma(P, S, n, wl.tau) as ctx:
+        flat = ctx.alloc()
+        wk.fill_initial_state(wl, flat[0], flat[2], flat[3])
+        twin = [x.clone() for x in flat]
+
+        def views(buf):
+            out = []
+            for p in range(P):
+                at, row = 0, []
+                for s in sizes:
+                    row.append(buf[p, at:at + s])
+                    at += s
+                out.append(row)
+            return out
+        cols = wk.sample_columns(n, 20000, wl.seed).cuda()
+        ow, om, opub = (np.ascontiguousarray(x[:, cols].cpu().numpy()) for x in (flat[0], flat[2], flat[3]))
+        with ctx.tensor_plan(*[views(x) for x in twin]) as plan:
+            for t in range(12):
+                wk.fill_gradients(wl, t, flat[1])
+                twin[1].copy_(flat[1])
+                mask = ctx.stale_mask(wl.seed, t, wl.stale_threshold)
+                ctx.step(*flat, mask, wl.lr, wl.mu, t)
+                plan.step(mask, wl.lr, wl.mu, t)
+                orc.step_f32(P, S, wl.tau, t, ow, np.ascontiguousarray(flat[1][:, cols].cpu().numpy()), om, opub,
+                             mask, wl.lr, wl.mu)
+                torch.cuda.synchronize()
+                for a, b, what in zip(flat, twin, "wgmp"):
+                    assert torch.equal(a[:, :n], b[:, :n]), "%s differs between the layouts at t=%d" % (what, t)
+                assert np.array_equal(bits(twin[0][:, cols].cpu().numpy()), bits(ow))
+                assert np.array_equal(bits(twin[3][:, cols].cpu().numpy()), bits(opub))
