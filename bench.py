@@ -73,6 +73,8 @@ def main() -> int:
     ap.add_argument("--ld", type=int, default=None, help="row stride override (floats)")
     ap.add_argument("--plain-alloc", action="store_true",
                     help="ordinary torch allocations instead of the library's HBM-region-aware allocator")
+    ap.add_argument("--tensors", action="store_true",
+                    help="time wagma_step_tensors on the workload's tensor list (views into the same rows)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-columns", type=int, default=131072)
     args = ap.parse_args()
@@ -122,8 +124,31 @@ def main() -> int:
     masks = [ctx.stale_mask(wl.seed, t, wl.stale_threshold) for t in range(max(K, W))]
     stream = torch.cuda.current_stream()
 
+    plan = None
+    if args.tensors:
+        import math
+        sizes = [math.prod(t[1]) for t in wl.tensors()]
+
+        def views(buf):
+            out = []
+            for p in range(P):
+                at, row = 0, []
+                for size in sizes:
+                    row.append(buf[p, at:at + size])
+                    at += size
+                out.append(row)
+            return out
+        plan = ctx.tensor_plan(views(w), views(g), views(m), views(pub))
+        log("per-tensor layout: %d tensors per replica" % len(sizes))
+
+    def step(t):
+        if plan is not None:
+            plan.step(masks[t], wl.lr, wl.mu, t)
+        else:
+            ctx.step(w, g, m, pub, masks[t], wl.lr, wl.mu, t)
+
     for t in range(W):
-        ctx.step(w, g, m, pub, masks[t], wl.lr, wl.mu, t)
+        step(t)
     torch.cuda.synchronize()
 
     starts = [torch.cuda.Event(enable_timing=True) for _ in range(K)]
@@ -132,7 +157,7 @@ def main() -> int:
     t0 = time.perf_counter()
     for t in range(K):
         starts[t].record(stream)
-        ctx.step(w, g, m, pub, masks[t], wl.lr, wl.mu, t)
+        step(t)
         ends[t].record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -150,7 +175,8 @@ def main() -> int:
     assert torch.isfinite(w[:, :n]).all()
 
     if grp:
-        dom, dom_ts = "group step (S=%d member rows in registers)" % S, grp
+        dom, dom_ts = "group step (S=%d member rows %s%s)" % (
+            S, "in registers" if S <= 8 else "streamed", ", per-tensor layout" if plan is not None else ""), grp
     else:
         dom, dom_ts = "global step (rows streamed)", glb
     dom_ms = sum(ms[t] for t in dom_ts)
@@ -159,8 +185,8 @@ def main() -> int:
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                 "avg_launch_ms": dom_ms / len(dom_ts), "launches": len(dom_ts),
                 "algorithmic_bytes_per_launch": sum(bytes_of[t] for t in dom_ts) / len(dom_ts),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(wl.index) if grp and not args.opt and not args.ld
-                else None}
+                "traffic": MEASURED_TRAFFIC_BYTES.get(wl.index)
+                if grp and not args.opt and not args.ld and plan is None else None}
     out = {
         "metric": "replica-params averaged/sec", "value": P * n * K / wall, "unit": "replica-params/s",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": wall * 1e3 / K,
@@ -168,13 +194,16 @@ def main() -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "P": P, "S": S, "n": n, "ld": ld, "tau": wl.tau,
                    "late_probability": wl.q, "global_steps_in_run": len(glb),
-                   "options": args.opt, "allocation": placement},
+                   "options": args.opt, "allocation": placement,
+                   "layout": "per-tensor" if plan is not None else "flat rows"},
         "hbm_gbs_all_steps": sum(bytes_of) / ((grp_ms + glb_ms) * 1e-3) / 1e9,
         "group_step_ms": (grp_ms / len(grp)) if grp else None,
         "global_step_ms": (glb_ms / len(glb)) if glb else None,
         "global_step_gbs": (sum(bytes_of[t] for t in glb) / (glb_ms * 1e-3) / 1e9) if glb else None,
         "roofline": roofline,
     }
+    if plan is not None:
+        plan.destroy()
     del w, g, m, pub
     ctx.destroy()
     torch.cuda.empty_cache()

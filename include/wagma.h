@@ -174,6 +174,25 @@ int wagma_stale_mask(const wagma_ctx* ctx, uint64_t seed, int64_t iter,
                      uint32_t threshold, uint64_t* mask_words);
 
 /*
+ * Two more lateness models, both integer-only and reproducible, in the layout wagma_step takes.
+ *
+ * wagma_straggler_mask: exactly `count` randomly selected processes are late in iteration iter,
+ * as the image-classification experiment injects its delays (Section 6.2 selects two processes
+ * per training step).  0 <= count <= P.
+ *
+ * wagma_clock_mask: every process draws a step time shaped like the reinforcement-learning
+ * workload of Section 6.4 (1.7 s to 43.5 s, median below 2 s: nine steps in sixteen take
+ * 1.7-2 s, the others one of 16 geometrically spaced times from 2 s to 43.5 s).  The process that
+ * finishes first is the activator of Section 3.2 and is never late; any other process is late
+ * iff it finishes more than tolerance_ms after it.  step_ms (host, P entries, may be NULL)
+ * receives the step times in milliseconds.
+ */
+int wagma_straggler_mask(const wagma_ctx* ctx, uint64_t seed, int64_t iter, int count,
+                         uint64_t* mask_words);
+int wagma_clock_mask(const wagma_ctx* ctx, uint64_t seed, int64_t iter, uint32_t tolerance_ms,
+                     uint64_t* mask_words, uint32_t* step_ms);
+
+/*
  * Optional allocator for the four P x ld arrays (device memory, uninitialised).  A caller may
  * always bring its own buffers instead.  On MI355X, write streams that all fall into one
  * HBM region (regions are tens of GiB wide, selected by the top physical address bits)

@@ -370,3 +370,75 @@ int oracle_stale_mask(uint64_t seed, int64_t t, int P, uint32_t threshold,
     }
     return ORACLE_OK;
 }
+
+/*
+ * Lateness as the paper's image-classification experiment injects it
+ * (Section 6.2): in every training step `count` randomly selected processes
+ * are delayed (the paper selects two).  Draw j of iteration t is the top
+ * log2(P) bits of a hash of (seed, t, j); draws that repeat a process already
+ * selected are skipped.  P must be a power of two.
+ */
+int oracle_straggler_mask(uint64_t seed, int64_t t, int P, int count, uint64_t *mask_words)
+{
+    int bits = exact_log2(P);
+    if (bits < 0 || t < 0 || count < 0 || count > P || !mask_words)
+        return ORACLE_EINVAL;
+    for (int k = 0; k < (P + 63) / 64; ++k)
+        mask_words[k] = 0;
+    uint64_t per_iter =
+        splitmix_finish((seed ^ UINT64_C(0x5354524147474C52)) + UINT64_C(0x9E3779B97F4A7C15) * ((uint64_t)t + 1u));
+    int chosen = 0;
+    for (uint64_t j = 0; chosen < count; ++j) {
+        uint64_t h = splitmix_finish(per_iter + UINT64_C(0xD1B54A32D192ED03) * (j + 1u));
+        int p = bits == 0 ? 0 : (int)(h >> (64 - bits));
+        if ((mask_words[p >> 6] >> (p & 63)) & 1u)
+            continue;
+        mask_words[p >> 6] |= UINT64_C(1) << (p & 63);
+        ++chosen;
+    }
+    return ORACLE_OK;
+}
+
+/*
+ * Lateness from simulated step times, shaped like the reinforcement-learning
+ * workload of Section 6.4 (iteration times from 1.7 s to 43.5 s, median below
+ * 2 s): nine steps in sixteen take between 1.7 s and 2 s, the others one of 16
+ * geometrically spaced times from 2 s to 43.5 s.  The process that finishes
+ * first is the activator (Section 3.2) and is never late; any other process is
+ * late iff it finishes more than tolerance_ms after the activator.
+ * step_ms, if not NULL, receives the P step times.
+ */
+static const uint32_t oracle_tail_ms[16] = {2000, 2456, 3016, 3703, 4548, 5585, 6858, 8422,
+                                            10342, 12700, 15595, 19151, 23517, 28879, 35463, 43500};
+
+int oracle_clock_mask(uint64_t seed, int64_t t, int P, uint32_t tolerance_ms,
+                      uint64_t *mask_words, uint32_t *step_ms)
+{
+    if (P < 1 || t < 0 || !mask_words)
+        return ORACLE_EINVAL;
+    uint32_t *ms = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)P);
+    if (!ms)
+        return ORACLE_ENOMEM;
+    uint64_t per_iter =
+        splitmix_finish((seed ^ UINT64_C(0x434C4F434B4D534B)) + UINT64_C(0x9E3779B97F4A7C15) * ((uint64_t)t + 1u));
+    uint32_t fastest = UINT32_MAX;
+    for (int p = 0; p < P; ++p) {
+        uint64_t h = splitmix_finish(per_iter + UINT64_C(0xD1B54A32D192ED03) * ((uint64_t)p + 1u));
+        if ((h >> 60) < 9u)
+            ms[p] = 1700u + (uint32_t)((h >> 32) & 0xFFu) * 300u / 256u; /* 1700 .. 1999 */
+        else
+            ms[p] = oracle_tail_ms[(h >> 56) & 15u];
+        if (ms[p] < fastest)
+            fastest = ms[p];
+    }
+    for (int k = 0; k < (P + 63) / 64; ++k)
+        mask_words[k] = 0;
+    for (int p = 0; p < P; ++p) {
+        if ((uint64_t)ms[p] > (uint64_t)fastest + tolerance_ms)
+            mask_words[p >> 6] |= UINT64_C(1) << (p & 63);
+        if (step_ms)
+            step_ms[p] = ms[p];
+    }
+    free(ms);
+    return ORACLE_OK;
+}

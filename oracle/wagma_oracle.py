@@ -56,6 +56,10 @@ def bind(lib: ctypes.CDLL) -> ctypes.CDLL:
                                     ctypes.c_double, ctypes.c_double, ctypes.c_int]
     lib.oracle_stale_mask.argtypes = [ctypes.c_uint64, ctypes.c_int64, ctypes.c_int,
                                       ctypes.c_uint32, u64p]
+    lib.oracle_straggler_mask.argtypes = [ctypes.c_uint64, ctypes.c_int64, ctypes.c_int, ctypes.c_int, u64p]
+    lib.oracle_clock_mask.argtypes = [ctypes.c_uint64, ctypes.c_int64, ctypes.c_int, ctypes.c_uint32, u64p,
+                                      ctypes.POINTER(ctypes.c_uint32)]
+    lib.oracle_straggler_mask.restype = lib.oracle_clock_mask.restype = ctypes.c_int
     for f in (lib.oracle_grouping_unionfind, lib.oracle_member_table,
               lib.oracle_is_global_iteration, lib.oracle_step_f32,
               lib.oracle_step_f64, lib.oracle_stale_mask):
@@ -152,3 +156,21 @@ def stale_mask(seed: int, t: int, P: int, threshold: int) -> np.ndarray:
         seed, t, P, threshold, words.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64))),
         "stale_mask")
     return words
+
+
+def straggler_mask(seed: int, t: int, P: int, count: int) -> np.ndarray:
+    """Exactly ``count`` randomly selected late processes (Section 6.2 selects two per step)."""
+    words = np.zeros((P + 63) // 64, dtype=np.uint64)
+    _check(_load().oracle_straggler_mask(
+        seed, t, P, count, words.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64))), "straggler_mask")
+    return words
+
+
+def clock_mask(seed: int, t: int, P: int, tolerance_ms: int):
+    """(mask words, step times in ms): late = more than tolerance_ms behind the fastest process."""
+    words = np.zeros((P + 63) // 64, dtype=np.uint64)
+    ms = np.zeros(P, dtype=np.uint32)
+    _check(_load().oracle_clock_mask(
+        seed, t, P, tolerance_ms, words.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64)),
+        ms.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32))), "clock_mask")
+    return words, ms

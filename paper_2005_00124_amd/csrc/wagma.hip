@@ -1124,6 +1124,61 @@ int wagma_stale_mask(const wagma_ctx* ctx, uint64_t seed, int64_t iter, uint32_t
     return WAGMA_OK;
 }
 
+int wagma_straggler_mask(const wagma_ctx* ctx, uint64_t seed, int64_t iter, int count,
+                         uint64_t* mask_words)
+{
+    if (!ctx || iter < 0 || count < 0 || count > ctx->P || !mask_words)
+        return WAGMA_EINVAL;
+    const int words = (ctx->P + 63) / 64;
+    for (int k = 0; k < words; ++k)
+        mask_words[k] = 0;
+    // the key differs from that of wagma_stale_mask by a tag, so the two models are independent
+    const uint64_t iter_key =
+        mix64((seed ^ UINT64_C(0x5354524147474C52)) + ((uint64_t)iter + 1) * UINT64_C(0x9E3779B97F4A7C15));
+    int picked = 0;
+    for (uint64_t draw = 1; picked < count; ++draw) {
+        const uint64_t h = mix64(iter_key + draw * UINT64_C(0xD1B54A32D192ED03));
+        const int rank = ctx->G == 0 ? 0 : (int)(h >> (64 - ctx->G));
+        const uint64_t bit = UINT64_C(1) << (rank & 63);
+        if (mask_words[rank >> 6] & bit)
+            continue;  // already selected: draw again
+        mask_words[rank >> 6] |= bit;
+        ++picked;
+    }
+    return WAGMA_OK;
+}
+
+int wagma_clock_mask(const wagma_ctx* ctx, uint64_t seed, int64_t iter, uint32_t tolerance_ms,
+                     uint64_t* mask_words, uint32_t* step_ms)
+{
+    // 16 geometric steps from 2 s to 43.5 s: the tail of the step-time distribution
+    static const uint32_t kTailMs[16] = {2000, 2456, 3016, 3703, 4548, 5585, 6858, 8422,
+                                         10342, 12700, 15595, 19151, 23517, 28879, 35463, 43500};
+    if (!ctx || iter < 0 || !mask_words)
+        return WAGMA_EINVAL;
+    uint32_t ms[WAGMA_MAX_P];
+    const uint64_t iter_key =
+        mix64((seed ^ UINT64_C(0x434C4F434B4D534B)) + ((uint64_t)iter + 1) * UINT64_C(0x9E3779B97F4A7C15));
+    uint32_t first_done = UINT32_MAX;
+    for (int rank = 0; rank < ctx->P; ++rank) {
+        const uint64_t h = mix64(iter_key + ((uint64_t)rank + 1) * UINT64_C(0xD1B54A32D192ED03));
+        const bool in_tail = (h >> 60) >= 9;  // seven steps in sixteen
+        ms[rank] = in_tail ? kTailMs[(h >> 56) & 15] : 1700u + (uint32_t)((h >> 32) & 0xFF) * 300u / 256u;
+        if (ms[rank] < first_done)
+            first_done = ms[rank];
+    }
+    const int words = (ctx->P + 63) / 64;
+    for (int k = 0; k < words; ++k)
+        mask_words[k] = 0;
+    for (int rank = 0; rank < ctx->P; ++rank) {
+        if ((uint64_t)ms[rank] > (uint64_t)first_done + tolerance_ms)
+            mask_words[rank >> 6] |= UINT64_C(1) << (rank & 63);
+        if (step_ms)
+            step_ms[rank] = ms[rank];
+    }
+    return WAGMA_OK;
+}
+
 int wagma_alloc_buffers(wagma_ctx* ctx, float** w, float** g, float** m, float** pub)
 {
     if (!ctx || !w || !g || !m || !pub || ctx->placed[0])

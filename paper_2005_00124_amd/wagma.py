@@ -46,6 +46,9 @@ SYMBOLS = {
                                           ctypes.c_float, ctypes.c_int64, ctypes.c_void_p]),
     "wagma_stale_mask": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int64,
                                         ctypes.c_uint32, _u64p]),
+    "wagma_straggler_mask": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int64, ctypes.c_int, _u64p]),
+    "wagma_clock_mask": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int64, ctypes.c_uint32, _u64p,
+                                        ctypes.POINTER(ctypes.c_uint32)]),
     "wagma_alloc_buffers": (ctypes.c_int, [ctypes.c_void_p] + [ctypes.POINTER(ctypes.c_void_p)] * 4),
     "wagma_free_buffers": (ctypes.c_int, [ctypes.c_void_p]),
     "wagma_placement_info": (ctypes.c_int, [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int),
@@ -197,6 +200,22 @@ def wagma_stale_mask(ctx: int, seed: int, it: int, threshold: int, P: int) -> np
     return words
 
 
+def wagma_straggler_mask(ctx: int, seed: int, it: int, count: int, P: int) -> np.ndarray:
+    words = np.zeros((P + 63) // 64, dtype=np.uint64)
+    _check(load().wagma_straggler_mask(ctx, seed, it, count, words.ctypes.data_as(_u64p)),
+           "wagma_straggler_mask")
+    return words
+
+
+def wagma_clock_mask(ctx: int, seed: int, it: int, tolerance_ms: int, P: int):
+    """Returns (mask words, step times in ms)."""
+    words = np.zeros((P + 63) // 64, dtype=np.uint64)
+    ms = np.zeros(P, dtype=np.uint32)
+    _check(load().wagma_clock_mask(ctx, seed, it, tolerance_ms, words.ctypes.data_as(_u64p),
+                                   ms.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32))), "wagma_clock_mask")
+    return words, ms
+
+
 def wagma_alloc_buffers(ctx: int):
     """Returns the device addresses (w, g, m, pub) of arrays placed by the library."""
     ptrs = [ctypes.c_void_p() for _ in range(4)]
@@ -263,6 +282,12 @@ class Wagma:
 
     def stale_mask(self, seed: int, it: int, threshold: int) -> np.ndarray:
         return wagma_stale_mask(self.ctx, seed, it, threshold, self.P)
+
+    def straggler_mask(self, seed: int, it: int, count: int) -> np.ndarray:
+        return wagma_straggler_mask(self.ctx, seed, it, count, self.P)
+
+    def clock_mask(self, seed: int, it: int, tolerance_ms: int):
+        return wagma_clock_mask(self.ctx, seed, it, tolerance_ms, self.P)
 
     def alloc(self, device="cuda"):
         """Four (P, ld) fp32 device buffers w, g, m, pub (uninitialised)."""

@@ -131,6 +131,21 @@ def test_stale_masks_bit_exact():
                                               orc.stale_mask(seed, t, P, thr))
 
 
+def test_experiment_lateness_models_bit_exact():
+    for P in (1, 8, 64, 1024):
+        with lw.Wagma(P, 1, 16, 0) as ctx:
+            for seed in (0, 200500128, 2 ** 64 - 1):
+                for t in (0, 1, 49, 10 ** 9):
+                    for k in sorted({0, 1, min(2, P), P}):
+                        assert np.array_equal(ctx.straggler_mask(seed, t, k), orc.straggler_mask(seed, t, P, k))
+                    for tol in (0, 250, 5000, 2 ** 32 - 1):
+                        words, ms = ctx.clock_mask(seed, t, tol)
+                        owords, oms = orc.clock_mask(seed, t, P, tol)
+                        assert np.array_equal(words, owords) and np.array_equal(ms, oms)
+            with pytest.raises(lw.WagmaError):
+                ctx.straggler_mask(0, 0, P + 1)
+
+
 # ------------------------------------------------------------------ step parity, small sizes
 
 @pytest.mark.parametrize("P,S", [(1, 1), (2, 1), (2, 2), (4, 2), (4, 4), (8, 4), (8, 8), (16, 4),

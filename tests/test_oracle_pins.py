@@ -537,3 +537,60 @@ def test_local_sgd_is_group_size_one():
         if (t + 1) % tau == 0:
             ref_w = np.broadcast_to(ref_w.mean(axis=0), ref_w.shape).copy()
         assert np.allclose(w, ref_w, rtol=0, atol=1e-12) and np.allclose(m, ref_m, rtol=0, atol=1e-12)
+
+
+# ------------------------------------------------- lateness models of the experiments
+
+def test_straggler_mask_selects_exactly_k():
+    """Section 6.2 delays two randomly selected processes per step."""
+    P = 64
+    counts = np.zeros(P)
+    for t in range(2000):
+        words = orc.straggler_mask(200500128, t, P, 2)
+        late = [p for p in range(P) if (int(words[p >> 6]) >> (p & 63)) & 1]
+        assert len(late) == 2
+        counts[late] += 1
+    # every process is selected about 2/64 of the time (binomial bounds, 5 sigma)
+    expect = 2000 * 2 / P
+    assert np.all(np.abs(counts - expect) < 5 * math.sqrt(expect))
+    assert not orc.straggler_mask(1, 0, 8, 0).any()
+    assert int(orc.straggler_mask(1, 0, 8, 8)[0]) == 0xFF
+    assert int(orc.straggler_mask(1, 5, 1, 1)[0]) == 1
+    assert int(orc.straggler_mask(9, 3, 1024, 1024).view(np.uint8).astype(np.int64).sum()) == 128 * 255
+    assert np.array_equal(orc.straggler_mask(5, 7, 64, 2), orc.straggler_mask(5, 7, 64, 2))
+    assert not np.array_equal(orc.straggler_mask(5, 7, 64, 2), orc.straggler_mask(5, 8, 64, 2))
+    with pytest.raises(ValueError):
+        orc.straggler_mask(1, 0, 8, 9)
+    # Python restatement, bit for bit
+    for seed, t, P, k in [(0, 0, 16, 3), (2 ** 64 - 1, 99, 64, 2), (77, 5, 1024, 17)]:
+        bits_per_rank = int(math.log2(P))
+        per_iter = splitmix_finish(((seed ^ 0x5354524147474C52) + 0x9E3779B97F4A7C15 * (t + 1)) & MASK64)
+        chosen, j = set(), 0
+        while len(chosen) < k:
+            h = splitmix_finish((per_iter + 0xD1B54A32D192ED03 * (j + 1)) & MASK64)
+            chosen.add(h >> (64 - bits_per_rank))
+            j += 1
+        words = orc.straggler_mask(seed, t, P, k)
+        have = {p for p in range(P) if (int(words[p >> 6]) >> (p & 63)) & 1}
+        assert have == chosen
+
+
+def test_clock_mask_distribution_and_activator():
+    """Section 6.4: step times from 1.7 s to 43.5 s with a median below 2 s; Section 3.2: the
+    process that arrives first (the activator) is never late."""
+    P = 64
+    all_ms = []
+    for t in range(300):
+        words, ms = orc.clock_mask(200500128, t, P, 500)
+        all_ms.append(ms)
+        late = np.array([(int(words[p >> 6]) >> (p & 63)) & 1 for p in range(P)], dtype=bool)
+        assert not late[np.argmin(ms)]
+        assert np.array_equal(late, ms.astype(np.int64) > int(ms.min()) + 500)
+    all_ms = np.concatenate(all_ms)
+    assert all_ms.min() >= 1700 and all_ms.max() == 43500
+    assert np.median(all_ms) < 2000
+    assert 0.40 < np.mean(all_ms >= 2000) < 0.475          # seven steps in sixteen are in the tail
+    # an infinite tolerance makes nobody late; zero tolerance leaves only the ties with the fastest
+    assert not orc.clock_mask(3, 0, P, 2 ** 32 - 1)[0].any()
+    words, ms = orc.clock_mask(3, 0, P, 0)
+    assert bin(int(words[0])).count("1") == int(np.sum(ms > ms.min()))
