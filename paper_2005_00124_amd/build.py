@@ -7,7 +7,7 @@ import sys
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
-SRC = os.path.join(PKG, "csrc", "wagma.hip")
+SRC = os.path.join(PKG, "csrc", "wagma.hip")   # includes wagma_kernels.h and wagma_placement.h
 LIB = os.path.join(PKG, "libwagma.so")
 
 # IEEE fp32 throughout: no contraction (the two fused multiply-adds are explicit), no

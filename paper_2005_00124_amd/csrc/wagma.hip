@@ -31,406 +31,17 @@
 #include <new>
 
 #include "wagma.h"
+#include "wagma_kernels.h"
+#include "wagma_placement.h"
 
 namespace {
 
-typedef float v4f __attribute__((ext_vector_type(4)));
-
-constexpr int kMaskWords = WAGMA_MAX_P / 64;
-constexpr int kChunk = 8;       // rows per chunk of the streaming kernel
-constexpr int kStackDepth = 7;  // log2(WAGMA_MAX_P / kChunk)
-constexpr int kNumXcd = 8;      // accelerator complex dies of an MI355X
-constexpr int64_t kMaxN = int64_t(1) << 31;
-
 thread_local int g_last_hip_error = 0;
 
-struct TileRef {
-    int32_t tensor;       // which tensor a tile of the per-tensor layout belongs to
-    int32_t reserved;
-    int64_t first_slice;  // first 16-byte slice of the tile inside that tensor
-};
+// ---- the HIP side of the region search (wagma_placement.h) ---------------------------------
 
-struct StepParams {
-    float* w;
-    const float* g;
-    float* m;
-    float* pub;
-    const int32_t* table;  // P ranks, group-major, butterfly member order
-    int64_t ld;            // row stride in floats
-    int64_t nvec;          // 16-byte column slices per row = ceil(n/4)
-    int64_t tiles;         // workgroups per group = ceil(nvec / block)
-    int64_t blocks;        // groups * tiles (grid may be padded beyond this)
-    uint64_t late[kMaskWords];
-    float lr;
-    float mu;
-    float inv_members;     // 1/S (or 1/P): exact, a power of two
-    float members_plus_1;  // S + 1
-    int members;           // S, or P in a global iteration
-    int log2_chunks;       // log2(members / kChunk) for the streaming kernel
-    int swizzle;           // 1: contiguous block range per XCD
-    int tile_major;        // 1: consecutive blocks walk the groups of one column tile
-    int stripe_log2;       // log2 of the distance, in KiB, between a workgroup's wavefronts
-    int xcd_chunk_log2;    // log2 of the run of consecutive tiles one XCD works on (0: 1 tile)
-    // per-tensor layout only (device tables)
-    float* const* tw;            // [P][T] base pointers, index rank * T + tensor
-    const float* const* tg;
-    float* const* tm;
-    float* const* tpub;
-    const TileRef* tile_ref;     // [tiles]
-    const int64_t* tensor_size;  // [T] floats
-    int num_tensors;
-};
-
-// Element types of the kernel bodies: v4f (one 16-byte column slice) and float
-// (the ragged last elements of a tensor in the per-tensor layout).
-template <bool NT, typename V>
-__device__ __forceinline__ V load_v(const float* p)
-{
-    if (NT)
-        return __builtin_nontemporal_load(reinterpret_cast<const V*>(p));
-    return *reinterpret_cast<const V*>(p);
-}
-
-template <bool NT, typename V>
-__device__ __forceinline__ void store_v(float* p, V v)
-{
-    if (NT)
-        __builtin_nontemporal_store(v, reinterpret_cast<V*>(p));
-    else
-        *reinterpret_cast<V*>(p) = v;
-}
-
-// a*b + c with one rounding per element (Algorithm 2 lines 6-7 are two of these).
-__device__ __forceinline__ float fma_v(float a, float b, float c)
-{
-    return __builtin_fmaf(a, b, c);
-}
-
-__device__ __forceinline__ v4f fma_v(float a, v4f b, v4f c)
-{
-    v4f r;
-    r.x = __builtin_fmaf(a, b.x, c.x);
-    r.y = __builtin_fmaf(a, b.y, c.y);
-    r.z = __builtin_fmaf(a, b.z, c.z);
-    r.w = __builtin_fmaf(a, b.w, c.w);
-    return r;
-}
-
-__device__ __forceinline__ bool is_late(const StepParams& p, int rank)
-{
-    return (p.late[rank >> 6] >> (rank & 63)) & 1u;
-}
-
-// Balanced pairwise sum of N = 2^k values: adjacent members first, i.e. the
-// butterfly phases of Section 3.3 in the order Algorithm 1 runs them.
-template <int N, typename V>
-__device__ __forceinline__ V tree_sum(const V* c)
-{
-    if constexpr (N == 1) {
-        return c[0];
-    } else {
-        V left = tree_sum<N / 2, V>(c);
-        V right = tree_sum<N / 2, V>(c + N / 2);
-        return left + right;
-    }
-}
-
-// Where the lane's element of a rank's row lives.  Flat layout: P rows of ld floats;
-// the row base is wave-uniform (scalar registers) and the lane adds one 32-bit offset.
-struct FlatAddr {
-    const StepParams& p;
-    uint32_t lane_at;  // float index inside the row
-    __device__ __forceinline__ float* w(int rank) const { return p.w + (int64_t)rank * p.ld + lane_at; }
-    __device__ __forceinline__ const float* g(int rank) const { return p.g + (int64_t)rank * p.ld + lane_at; }
-    __device__ __forceinline__ float* m(int rank) const { return p.m + (int64_t)rank * p.ld + lane_at; }
-    __device__ __forceinline__ float* pub(int rank) const { return p.pub + (int64_t)rank * p.ld + lane_at; }
-};
-
-// Per-tensor layout: a table of P x T base pointers per array; the lane adds its
-// float index inside the tensor.
-struct TensorAddr {
-    const StepParams& p;
-    int tensor;
-    uint32_t lane_at;
-    __device__ __forceinline__ int64_t slot(int rank) const { return (int64_t)rank * p.num_tensors + tensor; }
-    __device__ __forceinline__ float* w(int rank) const { return p.tw[slot(rank)] + lane_at; }
-    __device__ __forceinline__ const float* g(int rank) const { return p.tg[slot(rank)] + lane_at; }
-    __device__ __forceinline__ float* m(int rank) const { return p.tm[slot(rank)] + lane_at; }
-    __device__ __forceinline__ float* pub(int rank) const { return p.tpub[slot(rank)] + lane_at; }
-};
-
-// One group of S <= 8 members, all member rows held in registers.
-template <int S, bool NT, typename V, typename Addr>
-__device__ __forceinline__ void registers_body(const StepParams& p, const int32_t* member, const Addr& at)
-{
-    bool late[S];
-    int rank[S];
-    V wv[S], gv[S], mv[S], contrib[S];
-#pragma unroll
-    for (int e = 0; e < S; ++e) {
-        rank[e] = member[e];
-        late[e] = is_late(p, rank[e]);
-        wv[e] = load_v<NT, V>(at.w(rank[e]));
-        gv[e] = load_v<NT, V>(at.g(rank[e]));
-        mv[e] = load_v<NT, V>(at.m(rank[e]));
-    }
-#pragma unroll
-    for (int e = 0; e < S; ++e)
-        if (late[e])
-            contrib[e] = load_v<NT, V>(at.pub(rank[e]));  // the send buffer of a late process
-
-    // (Issuing the loads and stores one array at a time instead of row by row was measured:
-    // no difference.)
-#pragma unroll
-    for (int e = 0; e < S; ++e) {
-        const V m_new = fma_v(p.mu, mv[e], gv[e]);
-        wv[e] = fma_v(-p.lr, m_new, wv[e]);  // W'
-        store_v<NT, V>(at.m(rank[e]), m_new);
-        store_v<NT, V>(at.pub(rank[e]), wv[e]);
-        if (!late[e])
-            contrib[e] = wv[e];
-    }
-    const V w_sum = tree_sum<S, V>(contrib);
-#pragma unroll
-    for (int e = 0; e < S; ++e) {
-        V out;
-        if (late[e])
-            out = (w_sum + wv[e]) / p.members_plus_1;
-        else
-            out = w_sum * p.inv_members;
-        store_v<NT, V>(at.w(rank[e]), out);
-    }
-}
-
-// One group of any size >= 8: member rows streamed 8 at a time.
-template <bool NT, typename V, typename Addr>
-__device__ __forceinline__ void streamed_body(const StepParams& p, const int32_t* member, const Addr& at)
-{
-    const int chunks = p.members / kChunk;
-    V stack[kStackDepth];
-    V acc;
-    for (int c = 0; c < chunks; ++c) {
-        int rank[kChunk];
-        bool late[kChunk];
-        V wv[kChunk], gv[kChunk], mv[kChunk], contrib[kChunk];
-#pragma unroll
-        for (int i = 0; i < kChunk; ++i) {
-            rank[i] = member[c * kChunk + i];
-            late[i] = is_late(p, rank[i]);
-            wv[i] = load_v<NT, V>(at.w(rank[i]));
-            gv[i] = load_v<NT, V>(at.g(rank[i]));
-            mv[i] = load_v<NT, V>(at.m(rank[i]));
-        }
-#pragma unroll
-        for (int i = 0; i < kChunk; ++i)
-            if (late[i])
-                contrib[i] = load_v<NT, V>(at.pub(rank[i]));
-#pragma unroll
-        for (int i = 0; i < kChunk; ++i) {
-            const V m_new = fma_v(p.mu, mv[i], gv[i]);
-            wv[i] = fma_v(-p.lr, m_new, wv[i]);
-            store_v<NT, V>(at.m(rank[i]), m_new);
-            store_v<NT, V>(at.pub(rank[i]), wv[i]);
-            if (!late[i])
-                contrib[i] = wv[i];
-        }
-        acc = tree_sum<kChunk, V>(contrib);
-        // Binary-counter carry: after chunk c the stack holds one partial sum per set
-        // bit of c+1, so equal-sized neighbours are always added left + right.
-        bool carry = true;
-#pragma unroll
-        for (int l = 0; l < kStackDepth; ++l) {
-            if (carry) {
-                if ((c >> l) & 1) {
-                    acc = stack[l] + acc;
-                } else {
-                    stack[l] = acc;
-                    carry = false;
-                }
-            }
-        }
-    }
-    V w_sum = acc;
-#pragma unroll
-    for (int l = 0; l < kStackDepth; ++l)
-        if (l == p.log2_chunks)
-            w_sum = stack[l];
-    const V fresh = w_sum * p.inv_members;
-
-    for (int e = 0; e < p.members; ++e) {
-        const int rank = member[e];
-        V out = fresh;
-        if (is_late(p, rank)) {
-            // W' of this member: this thread stored it to the send buffer above.
-            const V w_prime = load_v<false, V>(at.pub(rank));
-            out = (w_sum + w_prime) / p.members_plus_1;
-        }
-        store_v<NT, V>(at.w(rank), out);
-    }
-}
-
-// Which group and which 16-byte column slice does this lane own?  Workgroups are
-// handed to the 8 XCDs round-robin; with `swizzle` each XCD instead walks one
-// contiguous eighth of the work.  A wavefront always owns 64 consecutive slices
-// (1 KiB per row).  The wavefronts of workgroup `tile` sit 2^stripe_log2 KiB apart
-// and consecutive workgroups fill the gaps, so that a workgroup's simultaneous
-// requests to one row hit addresses one stripe apart (stripe_log2 = 0: the plain
-// contiguous tile).  Returns false for lanes and workgroups beyond the end.
-template <int BLOCK>
-__device__ __forceinline__ bool decode_block(const StepParams& p, int64_t& group, int64_t& col)
-{
-    int64_t b = blockIdx.x;
-    if (p.swizzle) {
-        const int64_t per_xcd = (p.blocks + kNumXcd - 1) / kNumXcd;
-        b = (b % kNumXcd) * per_xcd + b / kNumXcd;
-    }
-    if (b >= p.blocks)
-        return false;
-    int64_t tile;
-    if (p.tile_major) {
-        const int64_t groups = p.blocks / p.tiles;
-        group = b % groups;
-        tile = b / groups;
-    } else {
-        group = b / p.tiles;
-        tile = b % p.tiles;
-    }
-    if (p.xcd_chunk_log2 > 0) {
-        // Workgroup b runs on XCD b % 8.  Give each XCD runs of 2^xcd_chunk_log2 consecutive
-        // tiles: the XCD number moves from tile bits [0,3) up to bits [j, j+3).
-        const int j = p.xcd_chunk_log2;
-        const int64_t xcd = tile & (kNumXcd - 1);
-        const int64_t hi = tile >> 3;
-        tile = ((hi >> j) << (j + 3)) | (xcd << j) | (hi & ((int64_t(1) << j) - 1));
-    }
-    constexpr int kWavesPerBlock = BLOCK / 64;
-    const int64_t wave = threadIdx.x >> 6;
-    const int64_t lane = threadIdx.x & 63;
-    const int64_t super = tile >> p.stripe_log2;
-    const int64_t within = tile & ((int64_t(1) << p.stripe_log2) - 1);
-    const int64_t chunk = ((super * kWavesPerBlock + wave) << p.stripe_log2) + within;
-    col = chunk * 64 + lane;
-    return col < p.nvec;
-}
-
-template <int S, bool NT, int BLOCK, int WAVES>
-__global__ void __launch_bounds__(BLOCK, WAVES) step_rows_in_registers(const StepParams p)
-{
-    int64_t group, col;
-    if (!decode_block<BLOCK>(p, group, col))
-        return;
-    const FlatAddr at{p, (uint32_t)col * 4u};
-    registers_body<S, NT, v4f>(p, p.table + group * S, at);
-}
-
-template <bool NT, int BLOCK, int WAVES>
-__global__ void __launch_bounds__(BLOCK, WAVES) step_rows_streamed(const StepParams p)
-{
-    int64_t group, col;
-    if (!decode_block<BLOCK>(p, group, col))
-        return;
-    const FlatAddr at{p, (uint32_t)col * 4u};
-    streamed_body<NT, v4f>(p, p.table + group * p.members, at);
-}
-
-// Per-tensor layout.  Workgroup b owns tile b % tiles of group b / tiles; the tile table
-// names the tensor and the tile's first 16-byte slice inside it.  A lane whose slice is
-// cut off by the end of the tensor does the remaining 1..3 elements one by one; nothing
-// beyond a tensor's last element is touched.
-template <int S, bool NT, int BLOCK>
-__global__ void __launch_bounds__(BLOCK, 2) step_tensors_in_registers(const StepParams p)
-{
-    const int64_t group = blockIdx.x / p.tiles;
-    const TileRef ref = p.tile_ref[blockIdx.x % p.tiles];
-    const int64_t size = p.tensor_size[ref.tensor];
-    const int64_t first = (ref.first_slice + threadIdx.x) * 4;
-    if (first >= size)
-        return;
-    const int32_t* member = p.table + group * S;
-    TensorAddr at{p, ref.tensor, (uint32_t)first};
-    if (first + 4 <= size) {
-        registers_body<S, NT, v4f>(p, member, at);
-    } else {
-        for (int64_t k = first; k < size; ++k) {
-            at.lane_at = (uint32_t)k;
-            registers_body<S, NT, float>(p, member, at);
-        }
-    }
-}
-
-template <bool NT, int BLOCK>
-__global__ void __launch_bounds__(BLOCK, 2) step_tensors_streamed(const StepParams p)
-{
-    const int64_t group = blockIdx.x / p.tiles;
-    const TileRef ref = p.tile_ref[blockIdx.x % p.tiles];
-    const int64_t size = p.tensor_size[ref.tensor];
-    const int64_t first = (ref.first_slice + threadIdx.x) * 4;
-    if (first >= size)
-        return;
-    const int32_t* member = p.table + group * p.members;
-    TensorAddr at{p, ref.tensor, (uint32_t)first};
-    if (first + 4 <= size) {
-        streamed_body<NT, v4f>(p, member, at);
-    } else {
-        for (int64_t k = first; k < size; ++k) {
-            at.lane_at = (uint32_t)k;
-            streamed_body<NT, float>(p, member, at);
-        }
-    }
-}
-
-// Schedule table: rows 0..period-1 hold the groups of iterations t = residue
-// (mod period) after Algorithm 1; row `period` is the single group 0..P-1 of a
-// global iteration.  Slot k*S + e of a row is member e of the group with the
-// k-th smallest base.  The phase bits are b_r = (t*g + r) mod G, r = 0..g-1
-// (Algorithm 1 lines 3, 6, 14); the base has those bits clear and the bits of k
-// spread over the remaining positions; member e sets phase bit b_r iff digit r
-// of e is set.
-__global__ void build_schedule_table(int32_t* table, int P, int G, int g, int period)
-{
-    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= (period + 1) * P)
-        return;
-    const int residue = idx / P;
-    const int slot = idx % P;
-    if (residue == period) {
-        table[idx] = slot;
-        return;
-    }
-    const int k = slot >> g;
-    const int e = slot & ((1 << g) - 1);
-    int phase_mask = 0, member_bits = 0;
-    for (int r = 0; r < g; ++r) {
-        const int b = (residue * g + r) % G;
-        phase_mask |= 1 << b;
-        if ((e >> r) & 1)
-            member_bits |= 1 << b;
-    }
-    int base = 0, rest = k;
-    for (int bit = 0; bit < G; ++bit) {
-        if (!((phase_mask >> bit) & 1)) {
-            base |= (rest & 1) << bit;
-            rest >>= 1;
-        }
-    }
-    table[idx] = base | member_bits;
-}
-
-// ---------------------------------------------------------------------------
-// HBM-region placement.  Measured on MI355X: the 288 GB of HBM are split, by the
-// top physical address bits, into a few regions tens of GiB wide (the ranks of
-// the 12-high stacks, by all appearance).  Write streams that all fall into one
-// region sustain about 5.9 TB/s, write streams spread over two regions about
-// 7.2 TB/s; reads do not care.  The step writes W, the momentum and the send
-// buffer of every member row at once, so it runs about 15% faster when these
-// three arrays lie in different regions.  Regions cannot be queried, so the
-// allocator finds them by timing: this kernel writes four streams through `a`
-// and four through `b`; it is fast exactly when a and b lie in different regions.
-// The probe must write well beyond the 256 MB Infinity Cache to see the HBM at all.
-constexpr size_t kProbeSideMax = size_t(1) << 30;            // bytes written through each pointer
-constexpr size_t kPlacementMinBytes = size_t(1) << 30;       // smaller arrays are not placed
-constexpr int kMaxCandidates = 64;
-
+// Writes four streams through `a` and four through `b`; fast exactly when a and b lie in
+// different HBM regions.
 __global__ void __launch_bounds__(256) placement_probe(float* a, float* b, uint32_t vec_per_stream)
 {
     const uint32_t i = blockIdx.x * 256u + threadIdx.x;
@@ -444,173 +55,69 @@ __global__ void __launch_bounds__(256) placement_probe(float* a, float* b, uint3
     }
 }
 
-// GB/s of the probe on (a, b); both must have side_bytes behind them.  < 0 on a HIP error.
-double probe_gbs(float* a, float* b, size_t side_bytes, hipEvent_t start, hipEvent_t stop)
-{
-    const uint32_t vec = (uint32_t)(side_bytes / 4 / 16);
-    const unsigned grid = (vec + 255) / 256;
-    float best_ms = 1e30f;
-    for (int rep = 0; rep < 4; ++rep) {
-        if (hipEventRecord(start, nullptr) != hipSuccess)
-            return -1.0;
-        hipLaunchKernelGGL(placement_probe, dim3(grid), dim3(256), 0, (hipStream_t) nullptr, a, b, vec);
-        if (hipEventRecord(stop, nullptr) != hipSuccess || hipEventSynchronize(stop) != hipSuccess)
-            return -1.0;
-        float ms = 0.0f;
-        if (hipEventElapsedTime(&ms, start, stop) != hipSuccess)
-            return -1.0;
-        if (rep > 0 && ms < best_ms)
-            best_ms = ms;
-    }
-    return 2.0 * 4.0 * 16.0 * (double)vec / (best_ms * 1e-3) / 1e9;
-}
-
-// The region search of wagma_alloc_buffers.  Candidates are whole arrays allocated one after
-// another (the driver hands out physical memory in address order, so later candidates lie
-// further on).  Probe rates fall into two clusters about 18% apart: both pointers in one
-// region (slow) or in two regions (fast).  The threshold between them is re-estimated from
-// all rates measured so far (the split of the sorted rates that maximises the between-class
-// variance), and the roles are re-derived from the stored measurements after every new
-// candidate, so that an unlucky first candidate cannot mislead the search.
-struct RegionSearch {
-    static constexpr double kMinSpread = 1.10;  // cluster means closer than this: only one cluster was seen
-    float* cand[kMaxCandidates];
-    double self[kMaxCandidates], ends[kMaxCandidates];
-    double cross[kMaxCandidates][kMaxCandidates];  // 0 = not measured yet
-    double vals[kMaxCandidates * 8];
-    int n = 0, n_vals = 0;
-    double threshold = 1e30;  // rates below: same region; at or above: different regions
-    double slow_mean = 0.0, fast_mean = 0.0;
-    size_t side = 0, tail = 0;
+struct HipMemory {
     hipEvent_t start = nullptr, stop = nullptr;
-    int w = -1, m = -1, pub = -1, g = -1;  // indices into cand[]
-    bool failed = false;
+    size_t reserve = 0;  // free memory to leave untouched
 
-    void see(double v)
+    bool init()
     {
-        if (v <= 0.0) {
-            failed = true;
-            return;
-        }
-        if (n_vals < kMaxCandidates * 8)
-            vals[n_vals++] = v;
-        double sorted[kMaxCandidates * 8];
-        for (int i = 0; i < n_vals; ++i)
-            sorted[i] = vals[i];
-        for (int i = 1; i < n_vals; ++i) {  // insertion sort: a few hundred values at most
-            const double x = sorted[i];
-            int j = i - 1;
-            while (j >= 0 && sorted[j] > x) {
-                sorted[j + 1] = sorted[j];
-                --j;
-            }
-            sorted[j + 1] = x;
-        }
-        double total = 0.0;
-        for (int i = 0; i < n_vals; ++i)
-            total += sorted[i];
-        slow_mean = total / n_vals;
-        fast_mean = 0.0;
-        threshold = 1e30;
-        if (sorted[n_vals - 1] < kMinSpread * sorted[0])
-            return;
-        double best = -1.0, low_sum = 0.0;
-        double split_at = 1e30, mean_lo_best = slow_mean, mean_hi_best = 0.0;
-        for (int k = 1; k < n_vals; ++k) {  // k values in the slow class
-            low_sum += sorted[k - 1];
-            const double mean_lo = low_sum / k, mean_hi = (total - low_sum) / (n_vals - k);
-            const double score = (double)k * (n_vals - k) * (mean_hi - mean_lo) * (mean_hi - mean_lo);
-            if (score > best) {
-                best = score;
-                split_at = 0.5 * (sorted[k - 1] + sorted[k]);
-                mean_lo_best = mean_lo;
-                mean_hi_best = mean_hi;
-            }
-        }
-        // two real clusters are about 18% apart; a split of mere noise is not
-        if (mean_hi_best >= kMinSpread * mean_lo_best) {
-            threshold = split_at;
-            slow_mean = mean_lo_best;
-            fast_mean = mean_hi_best;
-        }
+        return hipEventCreate(&start) == hipSuccess && hipEventCreate(&stop) == hipSuccess;
     }
-    void add(float* c)
+    ~HipMemory()
     {
-        cand[n] = c;
-        for (int k = 0; k <= n; ++k)
-            cross[n][k] = cross[k][n] = 0.0;
-        if (n == 0) {
-            // The clocks of an idle GPU take a while to come up: time nothing before that.
-            for (int rep = 0; rep < 40; ++rep)
-                (void)probe_gbs(c, c + side / sizeof(float), side, start, stop);
-        }
-        self[n] = probe_gbs(c, c + side / sizeof(float), side, start, stop);
-        see(self[n]);
-        ends[n] = probe_gbs(c, c + tail, side, start, stop);
-        see(ends[n]);
-        ++n;
-        if (n > 1)
-            (void)between(0, n - 1);  // one rate per candidate that does not depend on the roles
+        if (start)
+            (void)hipEventDestroy(start);
+        if (stop)
+            (void)hipEventDestroy(stop);
     }
-    void report() const
+    char* allocate(size_t bytes)
     {
-        std::fprintf(stderr, "wagma placement: %d candidates, threshold %.0f GB/s (slow %.0f, fast %.0f), "
-                             "w=%d g=%d m=%d pub=%d\n", n, threshold, slow_mean, fast_mean, w, g, m, pub);
-        for (int i = 0; i < n; ++i) {
-            std::fprintf(stderr, "  cand %2d %p self %.0f ends %.0f cross:", i, (void*)cand[i], self[i], ends[i]);
-            for (int j = 0; j < n; ++j)
-                if (cross[i][j] != 0.0)
-                    std::fprintf(stderr, " %d:%.0f", j, cross[i][j]);
-            std::fprintf(stderr, "\n");
+        size_t free_b = 0, total_b = 0;
+        if (hipMemGetInfo(&free_b, &total_b) != hipSuccess || free_b < bytes + reserve)
+            return nullptr;
+        char* c = nullptr;
+        if (hipMalloc((void**)&c, bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
         }
+        return c;
     }
-    double between(int i, int j)
+    void release(char* c) { (void)hipFree(c); }
+    // GB/s of the probe writing side_bytes through a and through b; best of three timed runs.
+    double rate(char* a, char* b, size_t side_bytes)
     {
-        if (cross[i][j] == 0.0) {
-            cross[i][j] = cross[j][i] = probe_gbs(cand[i], cand[j], side, start, stop);
-            see(cross[i][j]);
+        const uint32_t vec = (uint32_t)(side_bytes / 4 / 16);
+        const unsigned grid = (vec + 255) / 256;
+        float best_ms = 1e30f;
+        for (int rep = 0; rep < 4; ++rep) {
+            if (hipEventRecord(start, nullptr) != hipSuccess)
+                return -1.0;
+            hipLaunchKernelGGL(placement_probe, dim3(grid), dim3(256), 0, (hipStream_t) nullptr, (float*)a,
+                               (float*)b, vec);
+            if (hipEventRecord(stop, nullptr) != hipSuccess || hipEventSynchronize(stop) != hipSuccess)
+                return -1.0;
+            float ms = 0.0f;
+            if (hipEventElapsedTime(&ms, start, stop) != hipSuccess)
+                return -1.0;
+            if (rep > 0 && ms < best_ms)
+                best_ms = ms;
         }
-        return cross[i][j];
+        return 2.0 * 4.0 * 16.0 * (double)vec / (best_ms * 1e-3) / 1e9;
     }
-    // a candidate that straddles two regions is of no use
-    bool clean(int i) const { return self[i] < threshold && ends[i] < threshold; }
-    // Greedy roles in allocation order; repeated while new probes keep moving the threshold.
-    void assign()
-    {
-        for (int round = 0; round < 8 && !failed; ++round) {
-            const double threshold_before = threshold;
-            w = m = pub = g = -1;
-            for (int i = 0; i < n && !failed; ++i) {
-                if (!clean(i))
-                    continue;
-                if (w < 0) {
-                    w = i;
-                    continue;
-                }
-                const int placed[3] = {w, m, pub};
-                bool apart = true, with_w = false;
-                for (int k = 0; k < 3 && placed[k] >= 0; ++k) {
-                    if (between(placed[k], i) < threshold) {
-                        apart = false;
-                        if (k == 0)
-                            with_w = true;
-                    }
-                }
-                if (apart && m < 0)
-                    m = i;
-                else if (apart && pub < 0)
-                    pub = i;
-                else if (with_w && g < 0)
-                    g = i;
-            }
-            if (threshold == threshold_before)
-                break;  // the yardstick did not move: the roles stand
-        }
-        if (threshold > 1e29)
-            m = pub = -1;  // only one cluster seen: nothing is known to be apart
-    }
-    bool complete() const { return w >= 0 && m >= 0 && pub >= 0 && g >= 0; }
 };
+
+void report_search(const wagma_placement::RegionSearch<HipMemory>& rs)
+{
+    std::fprintf(stderr, "wagma placement: %d candidates, threshold %.0f GB/s, w=%d g=%d m=%d pub=%d\n",
+                 rs.count(), rs.threshold(), rs.role_w(), rs.role_g(), rs.role_m(), rs.role_pub());
+    for (int i = 0; i < rs.count(); ++i) {
+        std::fprintf(stderr, "  cand %2d %p inner %.0f cross:", i, (void*)rs.candidate(i), rs.inner_rate(i));
+        for (int j = 0; j < rs.count(); ++j)
+            if (rs.cross_rate(i, j) != 0.0)
+                std::fprintf(stderr, " %d:%.0f", j, rs.cross_rate(i, j));
+        std::fprintf(stderr, "\n");
+    }
+}
 
 int exact_log2(int64_t x)
 {
@@ -1196,91 +703,46 @@ int wagma_alloc_buffers(wagma_ctx* ctx, float** w, float** g, float** m, float**
     ctx->place_same_gbs = 0.0;
     ctx->place_split_gbs = 0.0;
 
-    float* chosen[3] = {nullptr, nullptr, nullptr};  // w, m, pub: pairwise different regions
-    float* grad = nullptr;  // g: read only; best in the region of w (never in that of pub)
-    float* spare[kMaxCandidates];
-    int n_spare = 0;
-    int rc = WAGMA_OK;
-
-    if (bytes >= kPlacementMinBytes) {
-        RegionSearch* rs = new (std::nothrow) RegionSearch();
-        if (rs && hipEventCreate(&rs->start) == hipSuccess && hipEventCreate(&rs->stop) == hipSuccess) {
-            // each probe writes `side` bytes through either pointer: at most half an array
-            rs->side = bytes / 2 < kProbeSideMax ? bytes / 2 : kProbeSideMax;
-            rs->side = rs->side / 1024 * 1024;
-            rs->tail = (bytes - rs->side) / sizeof(float) / 4 * 4;
-            while (!rs->complete() && !rs->failed && rs->n < kMaxCandidates) {
-                size_t free_b = 0, total_b = 0;
-                if (hipMemGetInfo(&free_b, &total_b) != hipSuccess || free_b < 3 * bytes)
-                    break;  // keep room for the caller
-                float* c = nullptr;
-                if (hipMalloc((void**)&c, bytes) != hipSuccess) {
-                    (void)hipGetLastError();
-                    break;
-                }
-                rs->add(c);
-                rs->assign();
-            }
+    wagma_placement::Result found;
+    if (bytes >= wagma_placement::kPlacementMinBytes) {
+        HipMemory memory;
+        memory.reserve = 2 * bytes;  // keep room for the caller while candidates are held
+        auto* search = new (std::nothrow) wagma_placement::RegionSearch<HipMemory>(memory, bytes);
+        if (search && memory.init()) {
+            found = search->run();
             if (std::getenv("WAGMA_DEBUG_PLACEMENT"))
-                rs->report();
-            ctx->place_candidates = rs->n;
-            ctx->place_same_gbs = rs->slow_mean;
-            ctx->place_split_gbs = rs->fast_mean;
-            ctx->place_regions = (rs->w >= 0) + (rs->m >= 0) + (rs->pub >= 0);
-            if (ctx->place_regions == 0)
-                ctx->place_regions = 1;
-            ctx->place_g_with_w = rs->g >= 0;
-            for (int i = 0; i < rs->n; ++i) {
-                if (i == rs->w)
-                    chosen[0] = rs->cand[i];
-                else if (i == rs->m)
-                    chosen[1] = rs->cand[i];
-                else if (i == rs->pub)
-                    chosen[2] = rs->cand[i];
-                else if (i == rs->g)
-                    grad = rs->cand[i];
-                else
-                    spare[n_spare++] = rs->cand[i];
-            }
+                report_search(*search);
+            ctx->place_candidates = found.candidates;
+            ctx->place_regions = found.regions;
+            ctx->place_g_with_w = found.g_with_w;
+            ctx->place_same_gbs = found.slow_gbs;
+            ctx->place_split_gbs = found.fast_gbs;
         }
-        if (rs) {
-            if (rs->start)
-                (void)hipEventDestroy(rs->start);
-            if (rs->stop)
-                (void)hipEventDestroy(rs->stop);
-            delete rs;
-        }
+        delete search;
     }
-    // whatever could not be placed takes any spare candidate, then a fresh allocation
-    float** missing[4] = {&chosen[0], &chosen[1], &chosen[2], &grad};
-    for (int k = 0; k < 4 && rc == WAGMA_OK; ++k) {
-        if (*missing[k])
-            continue;
-        if (n_spare > 0) {
-            *missing[k] = spare[--n_spare];
-        } else if ((e = hipMalloc((void**)missing[k], bytes)) != hipSuccess) {
-            *missing[k] = nullptr;
+    // whatever the search did not provide is an ordinary allocation
+    char** arrays[4] = {&found.w, &found.g, &found.m, &found.pub};
+    int rc = WAGMA_OK;
+    for (char** a : arrays) {
+        if (!*a && rc == WAGMA_OK && (e = hipMalloc((void**)a, bytes)) != hipSuccess) {
+            *a = nullptr;
             g_last_hip_error = (int)e;
             rc = e == hipErrorOutOfMemory ? WAGMA_ENOMEM : WAGMA_EHIP;
         }
     }
-    for (int k = 0; k < n_spare; ++k)
-        (void)hipFree(spare[k]);
     if (rc == WAGMA_OK && (e = hipDeviceSynchronize()) != hipSuccess)
         rc = hip_failed(e);
     if (rc != WAGMA_OK) {
-        for (int k = 0; k < 3; ++k)
-            if (chosen[k])
-                (void)hipFree(chosen[k]);
-        if (grad)
-            (void)hipFree(grad);
+        for (char** a : arrays)
+            if (*a)
+                (void)hipFree(*a);
         (void)hipGetLastError();
         return rc;
     }
-    ctx->placed[0] = *w = chosen[0];
-    ctx->placed[1] = *g = grad;
-    ctx->placed[2] = *m = chosen[1];
-    ctx->placed[3] = *pub = chosen[2];
+    ctx->placed[0] = *w = (float*)found.w;
+    ctx->placed[1] = *g = (float*)found.g;
+    ctx->placed[2] = *m = (float*)found.m;
+    ctx->placed[3] = *pub = (float*)found.pub;
     return WAGMA_OK;
 }
 

@@ -1,0 +1,396 @@
+// Device code of libwagma: the fused WAGMA-SGD step (Algorithm 2 lines 6-17 of
+// arXiv 2005.00124 with the groups of Algorithm 1) for gfx950.  Included by wagma.hip only.
+#ifndef WAGMA_KERNELS_H
+#define WAGMA_KERNELS_H
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "wagma.h"
+
+namespace {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr int kMaskWords = WAGMA_MAX_P / 64;
+constexpr int kChunk = 8;       // rows per chunk of the streaming kernel
+constexpr int kStackDepth = 7;  // log2(WAGMA_MAX_P / kChunk)
+constexpr int kNumXcd = 8;      // accelerator complex dies of an MI355X
+constexpr int64_t kMaxN = int64_t(1) << 31;
+
+struct TileRef {
+    int32_t tensor;       // which tensor a tile of the per-tensor layout belongs to
+    int32_t reserved;
+    int64_t first_slice;  // first 16-byte slice of the tile inside that tensor
+};
+
+struct StepParams {
+    float* w;
+    const float* g;
+    float* m;
+    float* pub;
+    const int32_t* table;  // P ranks, group-major, butterfly member order
+    int64_t ld;            // row stride in floats
+    int64_t nvec;          // 16-byte column slices per row = ceil(n/4)
+    int64_t tiles;         // workgroups per group = ceil(nvec / block)
+    int64_t blocks;        // groups * tiles (grid may be padded beyond this)
+    uint64_t late[kMaskWords];
+    float lr;
+    float mu;
+    float inv_members;     // 1/S (or 1/P): exact, a power of two
+    float members_plus_1;  // S + 1
+    int members;           // S, or P in a global iteration
+    int log2_chunks;       // log2(members / kChunk) for the streaming kernel
+    int swizzle;           // 1: contiguous block range per XCD
+    int tile_major;        // 1: consecutive blocks walk the groups of one column tile
+    int stripe_log2;       // log2 of the distance, in KiB, between a workgroup's wavefronts
+    int xcd_chunk_log2;    // log2 of the run of consecutive tiles one XCD works on (0: 1 tile)
+    // per-tensor layout only (device tables)
+    float* const* tw;            // [P][T] base pointers, index rank * T + tensor
+    const float* const* tg;
+    float* const* tm;
+    float* const* tpub;
+    const TileRef* tile_ref;     // [tiles]
+    const int64_t* tensor_size;  // [T] floats
+    int num_tensors;
+};
+
+// Element types of the kernel bodies: v4f (one 16-byte column slice) and float
+// (the ragged last elements of a tensor in the per-tensor layout).
+template <bool NT, typename V>
+__device__ __forceinline__ V load_v(const float* p)
+{
+    if (NT)
+        return __builtin_nontemporal_load(reinterpret_cast<const V*>(p));
+    return *reinterpret_cast<const V*>(p);
+}
+
+template <bool NT, typename V>
+__device__ __forceinline__ void store_v(float* p, V v)
+{
+    if (NT)
+        __builtin_nontemporal_store(v, reinterpret_cast<V*>(p));
+    else
+        *reinterpret_cast<V*>(p) = v;
+}
+
+// a*b + c with one rounding per element (Algorithm 2 lines 6-7 are two of these).
+__device__ __forceinline__ float fma_v(float a, float b, float c)
+{
+    return __builtin_fmaf(a, b, c);
+}
+
+__device__ __forceinline__ v4f fma_v(float a, v4f b, v4f c)
+{
+    v4f r;
+    r.x = __builtin_fmaf(a, b.x, c.x);
+    r.y = __builtin_fmaf(a, b.y, c.y);
+    r.z = __builtin_fmaf(a, b.z, c.z);
+    r.w = __builtin_fmaf(a, b.w, c.w);
+    return r;
+}
+
+__device__ __forceinline__ bool is_late(const StepParams& p, int rank)
+{
+    return (p.late[rank >> 6] >> (rank & 63)) & 1u;
+}
+
+// Balanced pairwise sum of N = 2^k values: adjacent members first, i.e. the
+// butterfly phases of Section 3.3 in the order Algorithm 1 runs them.
+template <int N, typename V>
+__device__ __forceinline__ V tree_sum(const V* c)
+{
+    if constexpr (N == 1) {
+        return c[0];
+    } else {
+        V left = tree_sum<N / 2, V>(c);
+        V right = tree_sum<N / 2, V>(c + N / 2);
+        return left + right;
+    }
+}
+
+// Where the lane's element of a rank's row lives.  Flat layout: P rows of ld floats;
+// the row base is wave-uniform (scalar registers) and the lane adds one 32-bit offset.
+struct FlatAddr {
+    const StepParams& p;
+    uint32_t lane_at;  // float index inside the row
+    __device__ __forceinline__ float* w(int rank) const { return p.w + (int64_t)rank * p.ld + lane_at; }
+    __device__ __forceinline__ const float* g(int rank) const { return p.g + (int64_t)rank * p.ld + lane_at; }
+    __device__ __forceinline__ float* m(int rank) const { return p.m + (int64_t)rank * p.ld + lane_at; }
+    __device__ __forceinline__ float* pub(int rank) const { return p.pub + (int64_t)rank * p.ld + lane_at; }
+};
+
+// Per-tensor layout: a table of P x T base pointers per array; the lane adds its
+// float index inside the tensor.
+struct TensorAddr {
+    const StepParams& p;
+    int tensor;
+    uint32_t lane_at;
+    __device__ __forceinline__ int64_t slot(int rank) const { return (int64_t)rank * p.num_tensors + tensor; }
+    __device__ __forceinline__ float* w(int rank) const { return p.tw[slot(rank)] + lane_at; }
+    __device__ __forceinline__ const float* g(int rank) const { return p.tg[slot(rank)] + lane_at; }
+    __device__ __forceinline__ float* m(int rank) const { return p.tm[slot(rank)] + lane_at; }
+    __device__ __forceinline__ float* pub(int rank) const { return p.tpub[slot(rank)] + lane_at; }
+};
+
+// One group of S <= 8 members, all member rows held in registers.
+template <int S, bool NT, typename V, typename Addr>
+__device__ __forceinline__ void registers_body(const StepParams& p, const int32_t* member, const Addr& at)
+{
+    bool late[S];
+    int rank[S];
+    V wv[S], gv[S], mv[S], contrib[S];
+#pragma unroll
+    for (int e = 0; e < S; ++e) {
+        rank[e] = member[e];
+        late[e] = is_late(p, rank[e]);
+        wv[e] = load_v<NT, V>(at.w(rank[e]));
+        gv[e] = load_v<NT, V>(at.g(rank[e]));
+        mv[e] = load_v<NT, V>(at.m(rank[e]));
+    }
+#pragma unroll
+    for (int e = 0; e < S; ++e)
+        if (late[e])
+            contrib[e] = load_v<NT, V>(at.pub(rank[e]));  // the send buffer of a late process
+
+    // (Issuing the loads and stores one array at a time instead of row by row was measured:
+    // no difference.)
+#pragma unroll
+    for (int e = 0; e < S; ++e) {
+        const V m_new = fma_v(p.mu, mv[e], gv[e]);
+        wv[e] = fma_v(-p.lr, m_new, wv[e]);  // W'
+        store_v<NT, V>(at.m(rank[e]), m_new);
+        store_v<NT, V>(at.pub(rank[e]), wv[e]);
+        if (!late[e])
+            contrib[e] = wv[e];
+    }
+    const V w_sum = tree_sum<S, V>(contrib);
+#pragma unroll
+    for (int e = 0; e < S; ++e) {
+        V out;
+        if (late[e])
+            out = (w_sum + wv[e]) / p.members_plus_1;
+        else
+            out = w_sum * p.inv_members;
+        store_v<NT, V>(at.w(rank[e]), out);
+    }
+}
+
+// One group of any size >= 8: member rows streamed 8 at a time.
+template <bool NT, typename V, typename Addr>
+__device__ __forceinline__ void streamed_body(const StepParams& p, const int32_t* member, const Addr& at)
+{
+    const int chunks = p.members / kChunk;
+    V stack[kStackDepth];
+    V acc;
+    for (int c = 0; c < chunks; ++c) {
+        int rank[kChunk];
+        bool late[kChunk];
+        V wv[kChunk], gv[kChunk], mv[kChunk], contrib[kChunk];
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i) {
+            rank[i] = member[c * kChunk + i];
+            late[i] = is_late(p, rank[i]);
+            wv[i] = load_v<NT, V>(at.w(rank[i]));
+            gv[i] = load_v<NT, V>(at.g(rank[i]));
+            mv[i] = load_v<NT, V>(at.m(rank[i]));
+        }
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i)
+            if (late[i])
+                contrib[i] = load_v<NT, V>(at.pub(rank[i]));
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i) {
+            const V m_new = fma_v(p.mu, mv[i], gv[i]);
+            wv[i] = fma_v(-p.lr, m_new, wv[i]);
+            store_v<NT, V>(at.m(rank[i]), m_new);
+            store_v<NT, V>(at.pub(rank[i]), wv[i]);
+            if (!late[i])
+                contrib[i] = wv[i];
+        }
+        acc = tree_sum<kChunk, V>(contrib);
+        // Binary-counter carry: after chunk c the stack holds one partial sum per set
+        // bit of c+1, so equal-sized neighbours are always added left + right.
+        bool carry = true;
+#pragma unroll
+        for (int l = 0; l < kStackDepth; ++l) {
+            if (carry) {
+                if ((c >> l) & 1) {
+                    acc = stack[l] + acc;
+                } else {
+                    stack[l] = acc;
+                    carry = false;
+                }
+            }
+        }
+    }
+    V w_sum = acc;
+#pragma unroll
+    for (int l = 0; l < kStackDepth; ++l)
+        if (l == p.log2_chunks)
+            w_sum = stack[l];
+    const V fresh = w_sum * p.inv_members;
+
+    for (int e = 0; e < p.members; ++e) {
+        const int rank = member[e];
+        V out = fresh;
+        if (is_late(p, rank)) {
+            // W' of this member: this thread stored it to the send buffer above.
+            const V w_prime = load_v<false, V>(at.pub(rank));
+            out = (w_sum + w_prime) / p.members_plus_1;
+        }
+        store_v<NT, V>(at.w(rank), out);
+    }
+}
+
+// Which group and which 16-byte column slice does this lane own?  Workgroups are
+// handed to the 8 XCDs round-robin; with `swizzle` each XCD instead walks one
+// contiguous eighth of the work.  A wavefront always owns 64 consecutive slices
+// (1 KiB per row).  The wavefronts of workgroup `tile` sit 2^stripe_log2 KiB apart
+// and consecutive workgroups fill the gaps, so that a workgroup's simultaneous
+// requests to one row hit addresses one stripe apart (stripe_log2 = 0: the plain
+// contiguous tile).  Returns false for lanes and workgroups beyond the end.
+template <int BLOCK>
+__device__ __forceinline__ bool decode_block(const StepParams& p, int64_t& group, int64_t& col)
+{
+    int64_t b = blockIdx.x;
+    if (p.swizzle) {
+        const int64_t per_xcd = (p.blocks + kNumXcd - 1) / kNumXcd;
+        b = (b % kNumXcd) * per_xcd + b / kNumXcd;
+    }
+    if (b >= p.blocks)
+        return false;
+    int64_t tile;
+    if (p.tile_major) {
+        const int64_t groups = p.blocks / p.tiles;
+        group = b % groups;
+        tile = b / groups;
+    } else {
+        group = b / p.tiles;
+        tile = b % p.tiles;
+    }
+    if (p.xcd_chunk_log2 > 0) {
+        // Workgroup b runs on XCD b % 8.  Give each XCD runs of 2^xcd_chunk_log2 consecutive
+        // tiles: the XCD number moves from tile bits [0,3) up to bits [j, j+3).
+        const int j = p.xcd_chunk_log2;
+        const int64_t xcd = tile & (kNumXcd - 1);
+        const int64_t hi = tile >> 3;
+        tile = ((hi >> j) << (j + 3)) | (xcd << j) | (hi & ((int64_t(1) << j) - 1));
+    }
+    constexpr int kWavesPerBlock = BLOCK / 64;
+    const int64_t wave = threadIdx.x >> 6;
+    const int64_t lane = threadIdx.x & 63;
+    const int64_t super = tile >> p.stripe_log2;
+    const int64_t within = tile & ((int64_t(1) << p.stripe_log2) - 1);
+    const int64_t chunk = ((super * kWavesPerBlock + wave) << p.stripe_log2) + within;
+    col = chunk * 64 + lane;
+    return col < p.nvec;
+}
+
+template <int S, bool NT, int BLOCK, int WAVES>
+__global__ void __launch_bounds__(BLOCK, WAVES) step_rows_in_registers(const StepParams p)
+{
+    int64_t group, col;
+    if (!decode_block<BLOCK>(p, group, col))
+        return;
+    const FlatAddr at{p, (uint32_t)col * 4u};
+    registers_body<S, NT, v4f>(p, p.table + group * S, at);
+}
+
+template <bool NT, int BLOCK, int WAVES>
+__global__ void __launch_bounds__(BLOCK, WAVES) step_rows_streamed(const StepParams p)
+{
+    int64_t group, col;
+    if (!decode_block<BLOCK>(p, group, col))
+        return;
+    const FlatAddr at{p, (uint32_t)col * 4u};
+    streamed_body<NT, v4f>(p, p.table + group * p.members, at);
+}
+
+// Per-tensor layout.  Workgroup b owns tile b % tiles of group b / tiles; the tile table
+// names the tensor and the tile's first 16-byte slice inside it.  A lane whose slice is
+// cut off by the end of the tensor does the remaining 1..3 elements one by one; nothing
+// beyond a tensor's last element is touched.
+template <int S, bool NT, int BLOCK>
+__global__ void __launch_bounds__(BLOCK, 2) step_tensors_in_registers(const StepParams p)
+{
+    const int64_t group = blockIdx.x / p.tiles;
+    const TileRef ref = p.tile_ref[blockIdx.x % p.tiles];
+    const int64_t size = p.tensor_size[ref.tensor];
+    const int64_t first = (ref.first_slice + threadIdx.x) * 4;
+    if (first >= size)
+        return;
+    const int32_t* member = p.table + group * S;
+    TensorAddr at{p, ref.tensor, (uint32_t)first};
+    if (first + 4 <= size) {
+        registers_body<S, NT, v4f>(p, member, at);
+    } else {
+        for (int64_t k = first; k < size; ++k) {
+            at.lane_at = (uint32_t)k;
+            registers_body<S, NT, float>(p, member, at);
+        }
+    }
+}
+
+template <bool NT, int BLOCK>
+__global__ void __launch_bounds__(BLOCK, 2) step_tensors_streamed(const StepParams p)
+{
+    const int64_t group = blockIdx.x / p.tiles;
+    const TileRef ref = p.tile_ref[blockIdx.x % p.tiles];
+    const int64_t size = p.tensor_size[ref.tensor];
+    const int64_t first = (ref.first_slice + threadIdx.x) * 4;
+    if (first >= size)
+        return;
+    const int32_t* member = p.table + group * p.members;
+    TensorAddr at{p, ref.tensor, (uint32_t)first};
+    if (first + 4 <= size) {
+        streamed_body<NT, v4f>(p, member, at);
+    } else {
+        for (int64_t k = first; k < size; ++k) {
+            at.lane_at = (uint32_t)k;
+            streamed_body<NT, float>(p, member, at);
+        }
+    }
+}
+
+// Schedule table: rows 0..period-1 hold the groups of iterations t = residue
+// (mod period) after Algorithm 1; row `period` is the single group 0..P-1 of a
+// global iteration.  Slot k*S + e of a row is member e of the group with the
+// k-th smallest base.  The phase bits are b_r = (t*g + r) mod G, r = 0..g-1
+// (Algorithm 1 lines 3, 6, 14); the base has those bits clear and the bits of k
+// spread over the remaining positions; member e sets phase bit b_r iff digit r
+// of e is set.
+__global__ void build_schedule_table(int32_t* table, int P, int G, int g, int period)
+{
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (period + 1) * P)
+        return;
+    const int residue = idx / P;
+    const int slot = idx % P;
+    if (residue == period) {
+        table[idx] = slot;
+        return;
+    }
+    const int k = slot >> g;
+    const int e = slot & ((1 << g) - 1);
+    int phase_mask = 0, member_bits = 0;
+    for (int r = 0; r < g; ++r) {
+        const int b = (residue * g + r) % G;
+        phase_mask |= 1 << b;
+        if ((e >> r) & 1)
+            member_bits |= 1 << b;
+    }
+    int base = 0, rest = k;
+    for (int bit = 0; bit < G; ++bit) {
+        if (!((phase_mask >> bit) & 1)) {
+            base |= (rest & 1) << bit;
+            rest >>= 1;
+        }
+    }
+    table[idx] = base | member_bits;
+}
+
+}  // namespace
+
+#endif  // WAGMA_KERNELS_H
