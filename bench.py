@@ -24,7 +24,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 MEASURED_TRAFFIC_BYTES = {4: 40.88e9}
 
 OPTS = {"block": 1, "nontemporal": 2, "force_stream": 3, "xcd_swizzle": 4, "tile_major": 5, "waves": 6,
-        "stripe_log2": 7, "xcd_chunk_log2": 8}
+        "stripe_log2": 7, "xcd_chunk_log2": 8, "placement": 9}
 
 
 def log(*a):
@@ -117,7 +117,7 @@ def main() -> int:
     else:
         w, g, m, pub = ctx.alloc_placed()     # w, m, pub in different HBM regions
         info = ctx.placement_info()
-        placement = "wagma_alloc_buffers: %(regions)d regions after %(candidates)d candidates" % info
+        placement = "wagma_alloc_buffers: %(mode)s placement, %(candidates)d memory blocks examined" % info
         log("placement:", info)
     wk.fill_initial_state(wl, w, m, pub)
     wk.fill_gradients(wl, 0, g)       # one gradient slab, reused: generating it is not part of the path

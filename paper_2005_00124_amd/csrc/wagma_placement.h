@@ -152,6 +152,7 @@ private:
         fast_mean_ = 0.0;
         threshold_ = kNoThreshold;
         double best = -1.0, low_sum = 0.0, split_at = kNoThreshold, lo_best = slow_mean_, hi_best = 0.0;
+        int k_best = 0;
         for (int k = 1; k < n_vals_; ++k) {  // k values in the slow class
             low_sum += sorted[k - 1];
             const double lo = low_sum / k, hi = (total - low_sum) / (n_vals_ - k);
@@ -161,10 +162,13 @@ private:
                 split_at = 0.5 * (sorted[k - 1] + sorted[k]);
                 lo_best = lo;
                 hi_best = hi;
+                k_best = k;
             }
         }
-        // two real clusters are about 18% apart; a split of mere noise is not
-        if (hi_best >= kMinSpread * lo_best) {
+        // Two real clusters are about 18% apart and the slow one holds a good part of the
+        // readings (every candidate is probed against itself); a slow straggler or two do not
+        // make a cluster, and a split of mere noise is none.
+        if (hi_best >= kMinSpread * lo_best && k_best >= 2 && 4 * k_best >= n_vals_) {
             threshold_ = split_at;
             slow_mean_ = lo_best;
             fast_mean_ = hi_best;

@@ -21,7 +21,8 @@ WAGMA_MAX_P = 1024
 WAGMA_GROUPING_DYNAMIC, WAGMA_GROUPING_FIXED = 0, 1
 WAGMA_OPT_BLOCK, WAGMA_OPT_NONTEMPORAL, WAGMA_OPT_FORCE_STREAM = 1, 2, 3
 WAGMA_OPT_XCD_SWIZZLE, WAGMA_OPT_TILE_MAJOR, WAGMA_OPT_WAVES, WAGMA_OPT_STRIPE_LOG2 = 4, 5, 6, 7
-WAGMA_OPT_XCD_CHUNK_LOG2 = 8
+WAGMA_OPT_XCD_CHUNK_LOG2, WAGMA_OPT_PLACEMENT = 8, 9
+WAGMA_PLACE_PLAIN, WAGMA_PLACE_ARRAYS, WAGMA_PLACE_CHUNKS, WAGMA_PLACE_AUTO, WAGMA_PLACE_SEARCH = 0, 1, 2, 3, 4
 
 # name -> (restype, argtypes): every symbol include/wagma.h declares
 _i32pp = ctypes.POINTER(ctypes.POINTER(ctypes.c_int32))
@@ -51,7 +52,7 @@ SYMBOLS = {
                                         ctypes.POINTER(ctypes.c_uint32)]),
     "wagma_alloc_buffers": (ctypes.c_int, [ctypes.c_void_p] + [ctypes.POINTER(ctypes.c_void_p)] * 4),
     "wagma_free_buffers": (ctypes.c_int, [ctypes.c_void_p]),
-    "wagma_placement_info": (ctypes.c_int, [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int),
+    "wagma_placement_info": (ctypes.c_int, [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int),
                                             ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int),
                                             ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]),
     "wagma_set_option": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64]),
@@ -228,11 +229,12 @@ def wagma_free_buffers(ctx: int) -> None:
 
 
 def wagma_placement_info(ctx: int) -> dict:
-    cand, regions, g_with_w = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    mode, cand, regions, g_with_w = ctypes.c_int(), ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
     same, split = ctypes.c_double(), ctypes.c_double()
-    _check(load().wagma_placement_info(ctx, ctypes.byref(cand), ctypes.byref(regions), ctypes.byref(g_with_w),
-                                       ctypes.byref(same), ctypes.byref(split)), "wagma_placement_info")
-    return {"candidates": cand.value, "regions": regions.value, "g_with_w": bool(g_with_w.value),
+    _check(load().wagma_placement_info(ctx, ctypes.byref(mode), ctypes.byref(cand), ctypes.byref(regions),
+                                       ctypes.byref(g_with_w), ctypes.byref(same), ctypes.byref(split)),
+           "wagma_placement_info")
+    return {"mode": {0: "plain", 1: "arrays", 2: "chunks", 4: "search"}.get(mode.value, "?"), "candidates": cand.value, "regions": regions.value, "g_with_w": bool(g_with_w.value),
             "probe_same_region_gbs": same.value, "probe_two_regions_gbs": split.value}
 
 

@@ -38,7 +38,8 @@ def test_header_constants_match_binding():
     for name in ("WAGMA_OK", "WAGMA_EINVAL", "WAGMA_EHIP", "WAGMA_ENOMEM", "WAGMA_MAX_P",
                  "WAGMA_GROUPING_DYNAMIC", "WAGMA_GROUPING_FIXED", "WAGMA_OPT_BLOCK", "WAGMA_OPT_NONTEMPORAL", "WAGMA_OPT_FORCE_STREAM",
                  "WAGMA_OPT_XCD_SWIZZLE", "WAGMA_OPT_TILE_MAJOR", "WAGMA_OPT_WAVES",
-                 "WAGMA_OPT_STRIPE_LOG2", "WAGMA_OPT_XCD_CHUNK_LOG2"):
+                 "WAGMA_OPT_STRIPE_LOG2", "WAGMA_OPT_XCD_CHUNK_LOG2", "WAGMA_OPT_PLACEMENT",
+                 "WAGMA_PLACE_PLAIN", "WAGMA_PLACE_ARRAYS", "WAGMA_PLACE_CHUNKS", "WAGMA_PLACE_AUTO", "WAGMA_PLACE_SEARCH"):
         value = re.search(r"#define\s+%s\s+\(?(-?\d+)\)?" % name, text).group(1)
         assert int(value) == getattr(libwagma, name), name
 
@@ -63,7 +64,7 @@ def test_host_side_argument_checks(lib):
     assert lib.wagma_step_tensors(None, None, None, 0.1, 0.9, 0, None) == libwagma.WAGMA_EINVAL
     assert lib.wagma_alloc_buffers(None, None, None, None, None) == libwagma.WAGMA_EINVAL
     assert lib.wagma_free_buffers(None) == libwagma.WAGMA_EINVAL
-    assert lib.wagma_placement_info(None, None, None, None, None, None) == libwagma.WAGMA_EINVAL
+    assert lib.wagma_placement_info(None, None, None, None, None, None, None) == libwagma.WAGMA_EINVAL
     assert lib.wagma_strerror(0) == b"success"
     assert b"invalid" in lib.wagma_strerror(libwagma.WAGMA_EINVAL)
     assert b"unknown" in lib.wagma_strerror(-99)

@@ -379,7 +379,7 @@ def sampled_parity(index, iters=None, count=40000, placed=False):
             w, g, m, pub = ctx.alloc_placed()
             info = ctx.placement_info()
             say("placement:", info)
-            assert info["candidates"] >= 1 and 1 <= info["regions"] <= 3
+            assert info["mode"] in ("plain", "arrays", "chunks", "search") and 0 <= info["regions"] <= 3
         else:
             w, g, m, pub = ctx.alloc()
         wk.fill_initial_state(wl, w, m, pub)
@@ -428,6 +428,35 @@ def test_workload_4_sampled():
 def test_workload_4_sampled_library_allocator():
     """The configuration bench.py times: arrays placed by wagma_alloc_buffers."""
     sampled_parity(4, placed=True)
+
+
+@pytest.mark.parametrize("mode", [lw.WAGMA_PLACE_CHUNKS, lw.WAGMA_PLACE_ARRAYS, lw.WAGMA_PLACE_SEARCH,
+                                  lw.WAGMA_PLACE_PLAIN])
+def test_every_placement_mode_gives_the_same_bits(mode):
+    """Arrays built from 1 GiB chunks, whole arrays in different regions, plain allocations:
+    the step does not care where its arrays lie (workload 2, 12 iterations, column sample)."""
+    wl = wk.workload(2)
+    P, S, n = wl.P, wl.S, wl.n
+    with lw.Wagma(P, S, n, wl.tau) as ctx:
+        ctx.set_option(lw.WAGMA_OPT_PLACEMENT, mode)
+        w, g, m, pub = ctx.alloc_placed()
+        say("placement:", ctx.placement_info())
+        wk.fill_initial_state(wl, w, m, pub)
+        cols = wk.sample_columns(n, 20000, wl.seed).cuda()
+        ow, om, opub = (np.ascontiguousarray(x[:, cols].cpu().numpy()) for x in (w, m, pub))
+        for t in range(12):
+            wk.fill_gradients(wl, t, g)
+            og = np.ascontiguousarray(g[:, cols].cpu().numpy())
+            mask = ctx.stale_mask(wl.seed, t, wl.stale_threshold)
+            ctx.step(w, g, m, pub, mask, wl.lr, wl.mu, t)
+            orc.step_f32(P, S, wl.tau, t, ow, og, om, opub, mask, wl.lr, wl.mu)
+            torch.cuda.synchronize()
+            for have, want, what in ((w, ow, "w"), (m, om, "m"), (pub, opub, "pub")):
+                assert_same_bits(have[:, cols].cpu().numpy(), want, "%s at t=%d" % (what, t))
+        del w, g, m, pub
+        ctx.free_placed()
+        w2 = ctx.alloc_placed()          # the same context can allocate again
+        del w2
 
 
 def test_workload_5_sampled():
