@@ -21,7 +21,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 # HBM bytes per launch of the dominant kernel from two `rocprofv3 --pmc` runs (FETCH_SIZE scaled by
 # 2.000, WRITE_SIZE by 1.000, the factors a plain copy of known size gave in the same runs); valid
 # for the default launch options only.  Source: profiles/group_step_S8__resnet50-25.6M_P64_S8.md
-MEASURED_TRAFFIC_BYTES = {4: 40.88e9}
+MEASURED_TRAFFIC_BYTES = {4: 40.94e9}
 
 OPTS = {"block": 1, "nontemporal": 2, "force_stream": 3, "xcd_swizzle": 4, "tile_major": 5, "waves": 6,
         "stripe_log2": 7, "xcd_chunk_log2": 8, "placement": 9}
