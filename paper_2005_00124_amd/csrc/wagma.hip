@@ -467,6 +467,69 @@ void fill_common(const wagma_ctx* ctx, StepParams& p, bool global, const uint64_
 
 namespace {
 
+// wagma_step; with group_only the iteration is treated as a group iteration whatever tau says
+// (the allocator times group steps with it).
+int step_flat(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub, const uint64_t* stale_mask,
+              float lr, float mu, int64_t iter, void* stream, bool group_only)
+{
+    int global = wagma_is_global_iteration(ctx, iter);
+    if (global < 0)
+        return global;
+    if (group_only)
+        global = 0;
+    if (!w || !g || !m || !pub)
+        return WAGMA_EINVAL;
+    if ((((uintptr_t)w) | ((uintptr_t)g) | ((uintptr_t)m) | ((uintptr_t)pub)) & 15u)
+        return WAGMA_EINVAL;
+    int device = -1;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess)
+        return hip_failed(e);
+    if (device != ctx->device)
+        return WAGMA_EINVAL;
+
+    StepParams p;
+    fill_common(ctx, p, global != 0, stale_mask, lr, mu, iter);
+    if (group_only)
+        p.table = ctx->d_table + (ctx->fixed_groups ? 0 : iter % ctx->period) * ctx->P;
+    p.w = w;
+    p.g = g;
+    p.m = m;
+    p.pub = pub;
+    p.ld = ctx->ld;
+    p.nvec = (ctx->n + 3) / 4;
+    p.swizzle = ctx->opt_swizzle;
+    p.tile_major = ctx->opt_tile_major;
+
+    const bool streamed = p.members > kChunk || (ctx->opt_force_stream && p.members == kChunk);
+    p.log2_chunks = streamed ? exact_log2(p.members / kChunk) : 0;
+    const int block = ctx->opt_block;
+    p.stripe_log2 = ctx->opt_stripe_log2;
+    // whole stripes: tiles is a multiple of 2^stripe_log2 (the surplus lanes find col >= nvec)
+    p.tiles = (p.nvec + block - 1) / block;
+    p.xcd_chunk_log2 = ctx->opt_xcd_chunk_log2;
+    // tiles is rounded up to whole stripes and whole XCD rounds (the surplus lanes find col >= nvec)
+    int round_log2 = p.stripe_log2;
+    if (p.xcd_chunk_log2 > 0 && p.xcd_chunk_log2 + 3 > round_log2)
+        round_log2 = p.xcd_chunk_log2 + 3;
+    p.tiles = ((p.tiles + (int64_t(1) << round_log2) - 1) >> round_log2) << round_log2;
+    p.blocks = (int64_t)(ctx->P / p.members) * p.tiles;
+    int64_t grid = p.blocks;
+    if (p.swizzle)
+        grid = (grid + kNumXcd - 1) / kNumXcd * kNumXcd;
+    if (grid > 0x7fffffff)
+        return WAGMA_EINVAL;
+
+    if (ctx->opt_nontemporal)
+        launch_block<true>(p, streamed, block, ctx->opt_waves, (unsigned)grid, (hipStream_t)stream);
+    else
+        launch_block<false>(p, streamed, block, ctx->opt_waves, (unsigned)grid, (hipStream_t)stream);
+    e = hipGetLastError();
+    if (e != hipSuccess)
+        return hip_failed(e);
+    return WAGMA_OK;
+}
+
 // ---- candidate placements of the four arrays -----------------------------------------------
 
 struct ArraySet {
@@ -600,8 +663,6 @@ double time_steps(wagma_ctx* ctx, const ArraySet& set)
             (void)hipEventDestroy(start);
         return 0.0;
     }
-    const int saved_tau = ctx->tau;
-    ctx->tau = 0;  // group iterations only
     // every fourth process late, so that the send-buffer reads of late members are part of
     // what is timed
     uint64_t late[kMaskWords];
@@ -613,14 +674,13 @@ double time_steps(wagma_ctx* ctx, const ArraySet& set)
         const int steps = ctx->period;
         ok = hipEventRecord(start, nullptr) == hipSuccess;
         for (int t = 0; t < steps && ok; ++t)
-            ok = wagma_step(ctx, set.ptr[0], set.ptr[1], set.ptr[2], set.ptr[3], late, 0.0f, 0.0f, t,
-                            nullptr) == WAGMA_OK;
+            ok = step_flat(ctx, set.ptr[0], set.ptr[1], set.ptr[2], set.ptr[3], late, 0.0f, 0.0f, t, nullptr,
+                           true) == WAGMA_OK;
         ok = ok && hipEventRecord(stop, nullptr) == hipSuccess && hipEventSynchronize(stop) == hipSuccess;
         float ms = 0.0f;
         if (ok && pass == 1 && hipEventElapsedTime(&ms, start, stop) == hipSuccess)
             ms_per_step = ms / steps;
     }
-    ctx->tau = saved_tau;
     (void)hipEventDestroy(start);
     (void)hipEventDestroy(stop);
     return ok ? ms_per_step : 0.0;
@@ -867,58 +927,7 @@ int wagma_group_schedule(const wagma_ctx* ctx, int64_t iter, const int32_t** dev
 int wagma_step(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub,
                const uint64_t* stale_mask, float lr, float mu, int64_t iter, void* stream)
 {
-    const int global = wagma_is_global_iteration(ctx, iter);
-    if (global < 0)
-        return global;
-    if (!w || !g || !m || !pub)
-        return WAGMA_EINVAL;
-    if ((((uintptr_t)w) | ((uintptr_t)g) | ((uintptr_t)m) | ((uintptr_t)pub)) & 15u)
-        return WAGMA_EINVAL;
-    int device = -1;
-    hipError_t e = hipGetDevice(&device);
-    if (e != hipSuccess)
-        return hip_failed(e);
-    if (device != ctx->device)
-        return WAGMA_EINVAL;
-
-    StepParams p;
-    fill_common(ctx, p, global != 0, stale_mask, lr, mu, iter);
-    p.w = w;
-    p.g = g;
-    p.m = m;
-    p.pub = pub;
-    p.ld = ctx->ld;
-    p.nvec = (ctx->n + 3) / 4;
-    p.swizzle = ctx->opt_swizzle;
-    p.tile_major = ctx->opt_tile_major;
-
-    const bool streamed = p.members > kChunk || (ctx->opt_force_stream && p.members == kChunk);
-    p.log2_chunks = streamed ? exact_log2(p.members / kChunk) : 0;
-    const int block = ctx->opt_block;
-    p.stripe_log2 = ctx->opt_stripe_log2;
-    // whole stripes: tiles is a multiple of 2^stripe_log2 (the surplus lanes find col >= nvec)
-    p.tiles = (p.nvec + block - 1) / block;
-    p.xcd_chunk_log2 = ctx->opt_xcd_chunk_log2;
-    // tiles is rounded up to whole stripes and whole XCD rounds (the surplus lanes find col >= nvec)
-    int round_log2 = p.stripe_log2;
-    if (p.xcd_chunk_log2 > 0 && p.xcd_chunk_log2 + 3 > round_log2)
-        round_log2 = p.xcd_chunk_log2 + 3;
-    p.tiles = ((p.tiles + (int64_t(1) << round_log2) - 1) >> round_log2) << round_log2;
-    p.blocks = (int64_t)(ctx->P / p.members) * p.tiles;
-    int64_t grid = p.blocks;
-    if (p.swizzle)
-        grid = (grid + kNumXcd - 1) / kNumXcd * kNumXcd;
-    if (grid > 0x7fffffff)
-        return WAGMA_EINVAL;
-
-    if (ctx->opt_nontemporal)
-        launch_block<true>(p, streamed, block, ctx->opt_waves, (unsigned)grid, (hipStream_t)stream);
-    else
-        launch_block<false>(p, streamed, block, ctx->opt_waves, (unsigned)grid, (hipStream_t)stream);
-    e = hipGetLastError();
-    if (e != hipSuccess)
-        return hip_failed(e);
-    return WAGMA_OK;
+    return step_flat(ctx, w, g, m, pub, stale_mask, lr, mu, iter, stream, false);
 }
 
 // ---- per-tensor layout ------------------------------------------------------------------

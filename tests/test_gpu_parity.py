@@ -461,3 +461,49 @@ def test_every_placement_mode_gives_the_same_bits(mode):
 
 def test_workload_5_sampled():
     sampled_parity(5, count=20000)
+
+
+def test_steps_captured_in_a_hip_graph():
+    """wagma_step allocates nothing and never synchronises, so a run of steps can be captured in a
+    HIP graph (mask and iteration number are baked in at capture time).  Every replay, with eager
+    work and synchronisations in between, must reproduce the eager result."""
+    wl = wk.workload(1)
+    P, S, n = wl.P, wl.S, wl.n
+    with lw.Wagma(P, S, n, wl.tau) as ctx:
+        w, g, m, pub = ctx.alloc()
+        wk.fill_initial_state(wl, w, m, pub)
+        wk.fill_gradients(wl, 0, g)
+        start = [x.clone() for x in (w, m, pub)]
+        masks = [ctx.stale_mask(wl.seed, t, 1 << 30) for t in range(wl.iters)]
+        for t in range(wl.iters):                         # eager reference: 10 iterations
+            ctx.step(w, g, m, pub, masks[t], wl.lr, wl.mu, t)
+        torch.cuda.synchronize()
+        want = [x.clone() for x in (w, m, pub)]
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for x, s in zip((w, m, pub), start):
+                x.copy_(s)
+            ctx.step(w, g, m, pub, masks[0], wl.lr, wl.mu, 0)      # warm the launch path
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                for t in range(wl.iters):
+                    ctx.step(w, g, m, pub, masks[t], wl.lr, wl.mu, t)
+        torch.cuda.current_stream().wait_stream(side)
+        for replay in range(4):
+            for x, s in zip((w, m, pub), start):
+                x.copy_(s)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for have, ref, what in zip((w, m, pub), want, "wmp"):
+                assert torch.equal(have, ref), "%s differs on replay %d" % (what, replay)
+            g.add_(0.0)                                   # eager work between the replays
+            torch.cuda.synchronize()
+        # the oracle agrees with both
+        ow, om, opub = (s.cpu().numpy().copy() for s in start)
+        og = g.cpu().numpy()
+        for t in range(wl.iters):
+            orc.step_f32(P, S, wl.tau, t, ow, og, om, opub, masks[t], wl.lr, wl.mu, n=n)
+        assert_same_bits(w.cpu().numpy()[:, :n], ow[:, :n], "w after the graph")
