@@ -75,6 +75,8 @@ def main() -> int:
                     help="ordinary torch allocations instead of the library's HBM-region-aware allocator")
     ap.add_argument("--tensors", action="store_true",
                     help="time wagma_step_tensors on the workload's tensor list (views into the same rows)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the K steps in one HIP graph and time its replay (for launch-bound sizes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-columns", type=int, default=131072)
     args = ap.parse_args()
@@ -153,16 +155,36 @@ def main() -> int:
 
     starts = [torch.cuda.Event(enable_timing=True) for _ in range(K)]
     ends = [torch.cuda.Event(enable_timing=True) for _ in range(K)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for t in range(K):
-        starts[t].record(stream)
-        step(t)
-        ends[t].record(stream)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-
-    ms = [starts[t].elapsed_time(ends[t]) for t in range(K)]
+    if args.graph:
+        # masks and iteration numbers are baked into the captured launches
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                for t in range(K):
+                    step(t)
+        stream.wait_stream(side)
+        graph.replay()                      # untimed first replay
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        starts[0].record(stream)
+        graph.replay()
+        ends[0].record(stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        per_step = starts[0].elapsed_time(ends[0]) / K      # no events inside a graph: the mean
+        ms = [per_step] * K
+    else:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for t in range(K):
+            starts[t].record(stream)
+            step(t)
+            ends[t].record(stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        ms = [starts[t].elapsed_time(ends[t]) for t in range(K)]
     is_global = [ctx.is_global(t) for t in range(K)]
     grp = [t for t in range(K) if not is_global[t]]
     glb = [t for t in range(K) if is_global[t]]
@@ -195,7 +217,8 @@ def main() -> int:
         "config": {"workload": wl.name, "P": P, "S": S, "n": n, "ld": ld, "tau": wl.tau,
                    "late_probability": wl.q, "global_steps_in_run": len(glb),
                    "options": args.opt, "allocation": placement,
-                   "layout": "per-tensor" if plan is not None else "flat rows"},
+                   "layout": "per-tensor" if plan is not None else "flat rows",
+                   "launch": "one HIP graph of K steps" if args.graph else "one launch per step"},
         "hbm_gbs_all_steps": sum(bytes_of) / ((grp_ms + glb_ms) * 1e-3) / 1e9,
         "group_step_ms": (grp_ms / len(grp)) if grp else None,
         "global_step_ms": (glb_ms / len(glb)) if glb else None,
