@@ -205,9 +205,13 @@ __device__ __forceinline__ void streamed_body(const StepParams& p, const int32_t
             const V m_new = fma_v(p.mu, mv[i], gv[i]);
             wv[i] = fma_v(-p.lr, m_new, wv[i]);
             store_v<NT, V>(at.m(rank[i]), m_new);
-            store_v<NT, V>(at.pub(rank[i]), wv[i]);
-            if (!late[i])
+            if (late[i]) {
+                // read again below: an ordinary store, so that the line may stay in the L2
+                store_v<false, V>(at.pub(rank[i]), wv[i]);
+            } else {
+                store_v<NT, V>(at.pub(rank[i]), wv[i]);
                 contrib[i] = wv[i];
+            }
         }
         acc = tree_sum<kChunk, V>(contrib);
         // Binary-counter carry: after chunk c the stack holds one partial sum per set
