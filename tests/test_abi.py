@@ -75,3 +75,12 @@ def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(libwagma, "LIB_PATH", str(tmp_path / "missing.so"))
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         libwagma.load()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """Every box has one GPU and the P workers live in its memory: --gpus N > 1 says so and stops."""
+    import subprocess
+    import sys
+    out = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                         capture_output=True, text=True, cwd=ROOT, timeout=120)
+    assert out.returncode != 0 and "ONE GPU" in out.stderr and not out.stdout.strip()
