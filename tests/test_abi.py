@@ -84,3 +84,17 @@ def test_bench_refuses_more_than_one_gpu():
     out = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
                          capture_output=True, text=True, cwd=ROOT, timeout=120)
     assert out.returncode != 0 and "ONE GPU" in out.stderr and not out.stdout.strip()
+
+
+def test_device_code_has_no_packed_fp32_instructions(tmp_path):
+    """The kernels are built with packed-fp32 instruction selection switched off; the device
+    assembly of our own source must hold none of v_pk_add/mul/fma_f32."""
+    import subprocess
+    from paper_2005_00124_amd import build
+    asm = tmp_path / "wagma_device.s"
+    flags = [f for f in build.HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
+    subprocess.run([build.hipcc(), *flags, "--cuda-device-only", "-S", "-o", str(asm), build.SRC],
+                   check=True, capture_output=True)
+    text = asm.read_text()
+    assert "step_rows_in_registers" in text and "global_load_dwordx4" in text
+    assert not re.search(r"\bv_pk_(add|mul|fma)_f32\b", text)
