@@ -15,9 +15,18 @@
  *                                 ordered member list per group.
  *   - oracle_step_f32 / _f64    : Algorithm 2 lines 6-17 for one iteration t
  *                                 on P model replicas held as P rows.
+ *   - oracle_step_lag_f32/_f64  : the same iteration when some processes are
+ *                                 still computing an earlier step and take
+ *                                 part only through their send buffer
+ *                                 (Section 4, the execution snapshot;
+ *                                 Assumption 1, item 3).
  *   - oracle_stale_mask         : the seeded stand-in for "which processes
  *                                 are late in iteration t" (not in the paper;
  *                                 a counter-based integer hash).
+ *   - oracle_lag_states/_masks  : who is on time, late or still computing when
+ *                                 every process runs its steps back to back
+ *                                 and the first to finish activates the
+ *                                 group allreduce (Section 3.2).
  *
  * Readings of the paper taken here (each is also pinned by a CPU test):
  *   - Algorithm 1 line 6: the mask of a phase is 1 << shift, built afresh in
@@ -34,6 +43,12 @@
  *     IEEE division applied after the addition W_sum + W'.
  *   - The send buffer ("pub") of every process holds W' of the last
  *     iteration: pub <- W' at the end of every iteration, global ones too.
+ *   - A process that is still computing when a group allreduce runs (lateness
+ *     deeper than one iteration) contributes its send buffer once more and is
+ *     otherwise left alone in that iteration: no local update, no gradient
+ *     read, send buffer not refreshed; the sum that lands in its receive
+ *     buffer is overwritten by a later one before it looks.  A global
+ *     iteration waits for everybody, so nobody is late or absent in it.
  *
  * Build: gcc -O2 -ffp-contract=off -fno-fast-math -shared -fPIC ... -lm
  * (no contraction, no fast-math, no flush-to-zero: IEEE fp32 throughout).
@@ -201,14 +216,22 @@ static int mask_bit(const uint64_t *stale_mask, int p)
  * One iteration t of Algorithm 2 (lines 6-17) for all P replicas, fp32.
  * w, g, m, pub: P rows of ld floats, n used columns.  w, m, pub are updated
  * in place; g is read only.  stale_mask: bit p set = process p is late in
- * this iteration (NULL = nobody).
+ * this iteration (NULL = nobody): it contributes its send buffer, finishes its
+ * local step afterwards and averages the group's sum with its own W' (lines
+ * 12-13).  busy_mask: bit p set = process p is still computing an earlier step
+ * when this iteration's group allreduce runs (the execution snapshot of
+ * Section 4, carried beyond one iteration; NULL = nobody): it contributes its
+ * send buffer again and nothing of it changes.  busy wins over late.  Both
+ * masks are ignored in a global iteration, which every process enters after
+ * the same number of steps.
  * fixed_groups != 0 is the paper's second ablation (Section 6.2): group model
  * averaging without the dynamic grouping strategy, i.e. the groups of
  * iteration 0 in every group iteration.
  */
-int oracle_step_f32(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
-                    float *w, const float *g, float *m, float *pub,
-                    const uint64_t *stale_mask, float lr, float mu, int fixed_groups)
+int oracle_step_lag_f32(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
+                        float *w, const float *g, float *m, float *pub,
+                        const uint64_t *stale_mask, const uint64_t *busy_mask,
+                        float lr, float mu, int fixed_groups)
 {
     if (exact_log2(P) < 0 || exact_log2(S) < 0 || S > P || n < 1 || ld < n ||
         tau < 0 || t < 0 || !w || !g || !m || !pub)
@@ -228,8 +251,10 @@ int oracle_step_f32(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
         oracle_member_table(P, S, fixed_groups ? 0 : t, table);
 
     for (int64_t j = 0; j < n; ++j) {
-        /* lines 6-7: local update of every replica */
+        /* lines 6-7: local update of every replica that finishes a step in this iteration */
         for (int i = 0; i < P; ++i) {
+            if (!global && mask_bit(busy_mask, i))
+                continue; /* still computing: nothing of this process changes */
             int64_t at = (int64_t)i * ld + j;
             float m_new = fmaf(mu, m[at], g[at]);
             w_prime[i] = fmaf(-lr, m_new, w[at]);
@@ -247,7 +272,7 @@ int oracle_step_f32(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
                 const int32_t *member = table + (int64_t)k * S;
                 for (int e = 0; e < S; ++e) {
                     int p = member[e];
-                    contrib[e] = mask_bit(stale_mask, p)
+                    contrib[e] = (mask_bit(stale_mask, p) || mask_bit(busy_mask, p))
                                      ? pub[(int64_t)p * ld + j] /* send buffer */
                                      : w_prime[p];
                 }
@@ -255,6 +280,8 @@ int oracle_step_f32(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
                 for (int e = 0; e < S; ++e) {
                     int p = member[e];
                     int64_t at = (int64_t)p * ld + j;
+                    if (mask_bit(busy_mask, p))
+                        continue; /* the sum waits in its receive buffer, unread */
                     if (!mask_bit(stale_mask, p))
                         w[at] = w_sum * (1.0f / (float)S);
                     else
@@ -264,7 +291,8 @@ int oracle_step_f32(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
         }
         /* the send buffer now holds this iteration's locally updated model */
         for (int i = 0; i < P; ++i)
-            pub[(int64_t)i * ld + j] = w_prime[i];
+            if (global || !mask_bit(busy_mask, i))
+                pub[(int64_t)i * ld + j] = w_prime[i];
     }
     free(table);
     free(w_prime);
@@ -273,9 +301,10 @@ int oracle_step_f32(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
 }
 
 /* The same iteration carried in fp64 (a shadow used to bound rounding). */
-int oracle_step_f64(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
-                    double *w, const double *g, double *m, double *pub,
-                    const uint64_t *stale_mask, double lr, double mu, int fixed_groups)
+int oracle_step_lag_f64(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
+                        double *w, const double *g, double *m, double *pub,
+                        const uint64_t *stale_mask, const uint64_t *busy_mask,
+                        double lr, double mu, int fixed_groups)
 {
     if (exact_log2(P) < 0 || exact_log2(S) < 0 || S > P || n < 1 || ld < n ||
         tau < 0 || t < 0 || !w || !g || !m || !pub)
@@ -296,6 +325,8 @@ int oracle_step_f64(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
 
     for (int64_t j = 0; j < n; ++j) {
         for (int i = 0; i < P; ++i) {
+            if (!global && mask_bit(busy_mask, i))
+                continue;
             int64_t at = (int64_t)i * ld + j;
             double m_new = mu * m[at] + g[at];
             w_prime[i] = w[at] - lr * m_new;
@@ -310,7 +341,7 @@ int oracle_step_f64(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
                 const int32_t *member = table + (int64_t)k * S;
                 for (int e = 0; e < S; ++e) {
                     int p = member[e];
-                    contrib[e] = mask_bit(stale_mask, p)
+                    contrib[e] = (mask_bit(stale_mask, p) || mask_bit(busy_mask, p))
                                      ? pub[(int64_t)p * ld + j]
                                      : w_prime[p];
                 }
@@ -318,6 +349,8 @@ int oracle_step_f64(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
                 for (int e = 0; e < S; ++e) {
                     int p = member[e];
                     int64_t at = (int64_t)p * ld + j;
+                    if (mask_bit(busy_mask, p))
+                        continue;
                     if (!mask_bit(stale_mask, p))
                         w[at] = w_sum / (double)S;
                     else
@@ -326,12 +359,30 @@ int oracle_step_f64(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
             }
         }
         for (int i = 0; i < P; ++i)
-            pub[(int64_t)i * ld + j] = w_prime[i];
+            if (global || !mask_bit(busy_mask, i))
+                pub[(int64_t)i * ld + j] = w_prime[i];
     }
     free(table);
     free(w_prime);
     free(contrib);
     return ORACLE_OK;
+}
+
+/* Algorithm 2 as printed: every process finishes its local step inside the iteration. */
+int oracle_step_f32(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
+                    float *w, const float *g, float *m, float *pub,
+                    const uint64_t *stale_mask, float lr, float mu, int fixed_groups)
+{
+    return oracle_step_lag_f32(P, S, n, ld, tau, t, w, g, m, pub, stale_mask, NULL, lr, mu,
+                               fixed_groups);
+}
+
+int oracle_step_f64(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
+                    double *w, const double *g, double *m, double *pub,
+                    const uint64_t *stale_mask, double lr, double mu, int fixed_groups)
+{
+    return oracle_step_lag_f64(P, S, n, ld, tau, t, w, g, m, pub, stale_mask, NULL, lr, mu,
+                               fixed_groups);
 }
 
 /*
@@ -441,4 +492,146 @@ int oracle_clock_mask(uint64_t seed, int64_t t, int P, uint32_t tolerance_ms,
     }
     free(ms);
     return ORACLE_OK;
+}
+
+/*
+ * Lateness deeper than one iteration.  Between two global iterations nobody
+ * waits for anybody (Section 3.2): every process runs its local steps back to
+ * back, and group allreduce number k is activated by the first process that
+ * finishes a step begun for it.  The allreduce takes the models as they stand
+ * tolerance_ms after the activation and hands the sum back at that moment.
+ * In iteration k a process is
+ *   ORACLE_FRESH  it finished the step it had begun for allreduce k in time:
+ *                 it contributes W', receives the average and begins its next
+ *                 step when the allreduce is done;
+ *   ORACLE_LATE   it finishes a step after allreduce k has taken its send
+ *                 buffer and before allreduce k+1 takes it again: it averages
+ *                 the sum of allreduce k with its W' (Algorithm 2 lines 12-13)
+ *                 and begins its next step, for allreduce k+1, straight away;
+ *   ORACLE_BUSY   it is still computing when allreduce k+1 runs.
+ * A step begun for allreduce k by process p lasts step_ms[k][p] (a process that
+ * is busy in iteration k never uses its entry of row k).
+ *
+ * step_ms: K+1 rows of P times, row 0 = the first iteration of the window (the
+ * iteration after a global one), every time above tolerance_ms.
+ * states: K rows of P.
+ */
+enum { ORACLE_FRESH = 0, ORACLE_LATE = 1, ORACLE_BUSY = 2 };
+
+int oracle_lag_states(int P, int K, const uint32_t *step_ms, uint32_t tolerance_ms, uint8_t *states)
+{
+    if (P < 1 || K < 0 || !step_ms || !states)
+        return ORACLE_EINVAL;
+    for (int64_t i = 0; i < (int64_t)(K + 1) * P; ++i)
+        if (step_ms[i] <= tolerance_ms)
+            return ORACLE_EINVAL;
+    int64_t *finish = (int64_t *)malloc(sizeof(int64_t) * (size_t)P); /* end of the current step */
+    int *begun_for = (int *)malloc(sizeof(int) * (size_t)P);          /* allreduce it was begun for */
+    if (!finish || !begun_for) {
+        free(finish);
+        free(begun_for);
+        return ORACLE_ENOMEM;
+    }
+    for (int p = 0; p < P; ++p) {
+        finish[p] = step_ms[p];
+        begun_for[p] = 0;
+    }
+    for (int k = 0; k < K; ++k) {
+        uint8_t *state = states + (int64_t)k * P;
+        const uint32_t *next_ms = step_ms + (int64_t)(k + 1) * P;
+        /* the activator: first to finish a step begun for allreduce k */
+        int64_t activated = INT64_MAX;
+        for (int p = 0; p < P; ++p)
+            if (begun_for[p] == k && finish[p] < activated)
+                activated = finish[p];
+        int64_t taken = activated + tolerance_ms; /* when allreduce k reads the models */
+        /* earliest moment allreduce k+1 can be activated, as far as known */
+        int64_t next_activated = INT64_MAX;
+        for (int p = 0; p < P; ++p) {
+            state[p] = ORACLE_BUSY; /* until shown otherwise below */
+            if (begun_for[p] == k && finish[p] <= taken) {
+                state[p] = ORACLE_FRESH;
+                begun_for[p] = k + 1;
+                finish[p] = taken + next_ms[p];
+                if (finish[p] < next_activated)
+                    next_activated = finish[p];
+            }
+        }
+        /* the others in the order in which they finish: one that ends its step before
+           allreduce k+1 reads the models is late in k, and its next step may itself
+           activate allreduce k+1 */
+        for (;;) {
+            int first = -1;
+            for (int p = 0; p < P; ++p)
+                if (state[p] == ORACLE_BUSY && begun_for[p] <= k &&
+                    (first < 0 || finish[p] < finish[first]))
+                    first = p;
+            if (first < 0 || finish[first] > next_activated + tolerance_ms)
+                break;
+            state[first] = ORACLE_LATE;
+            begun_for[first] = k + 1;
+            finish[first] += next_ms[first];
+            if (finish[first] < next_activated)
+                next_activated = finish[first];
+        }
+    }
+    free(finish);
+    free(begun_for);
+    return ORACLE_OK;
+}
+
+/* the step time of process p for a step begun in iteration t (as in oracle_clock_mask) */
+static uint32_t clock_step_ms(uint64_t seed, int64_t t, int p)
+{
+    uint64_t per_iter =
+        splitmix_finish((seed ^ UINT64_C(0x434C4F434B4D534B)) + UINT64_C(0x9E3779B97F4A7C15) * ((uint64_t)t + 1u));
+    uint64_t h = splitmix_finish(per_iter + UINT64_C(0xD1B54A32D192ED03) * ((uint64_t)p + 1u));
+    if ((h >> 60) < 9u)
+        return 1700u + (uint32_t)((h >> 32) & 0xFFu) * 300u / 256u;
+    return oracle_tail_ms[(h >> 56) & 15u];
+}
+
+/*
+ * The two masks of iteration t under the step times of oracle_clock_mask.  The
+ * clocks restart after every global iteration (Algorithm 2 lines 15-16: there
+ * everybody waits); with tau == 0 they restart every `window` iterations
+ * instead, which bounds the staleness as Assumption 1 item 3 asks.  In a global
+ * iteration both masks are empty.
+ */
+int oracle_lag_masks(uint64_t seed, int64_t t, int P, int tau, int window, uint32_t tolerance_ms,
+                     uint64_t *late_words, uint64_t *busy_words)
+{
+    if (P < 1 || t < 0 || tau < 0 || (tau == 0 && window < 1) || tolerance_ms >= 1700u ||
+        !late_words || !busy_words)
+        return ORACLE_EINVAL;
+    for (int k = 0; k < (P + 63) / 64; ++k)
+        late_words[k] = busy_words[k] = 0;
+    if (oracle_is_global_iteration(tau, t))
+        return ORACLE_OK;
+    int64_t length = tau > 0 ? tau : window;
+    int64_t first = t / length * length;
+    int K = (int)(t - first) + 1;
+    uint32_t *ms = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)(K + 1) * (size_t)P);
+    uint8_t *states = (uint8_t *)malloc((size_t)K * (size_t)P);
+    if (!ms || !states) {
+        free(ms);
+        free(states);
+        return ORACLE_ENOMEM;
+    }
+    for (int k = 0; k <= K; ++k)
+        for (int p = 0; p < P; ++p)
+            ms[(int64_t)k * P + p] = clock_step_ms(seed, first + k, p);
+    int rc = oracle_lag_states(P, K, ms, tolerance_ms, states);
+    if (rc == ORACLE_OK) {
+        for (int p = 0; p < P; ++p) {
+            uint8_t s = states[(int64_t)(K - 1) * P + p];
+            if (s == ORACLE_LATE)
+                late_words[p >> 6] |= UINT64_C(1) << (p & 63);
+            else if (s == ORACLE_BUSY)
+                busy_words[p >> 6] |= UINT64_C(1) << (p & 63);
+        }
+    }
+    free(ms);
+    free(states);
+    return rc;
 }

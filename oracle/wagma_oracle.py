@@ -54,6 +54,19 @@ def bind(lib: ctypes.CDLL) -> ctypes.CDLL:
     lib.oracle_step_f64.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
                                     ctypes.c_int, ctypes.c_int64, f64p, f64p, f64p, f64p, u64p,
                                     ctypes.c_double, ctypes.c_double, ctypes.c_int]
+    lib.oracle_step_lag_f32.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
+                                        ctypes.c_int, ctypes.c_int64, f32p, f32p, f32p, f32p, u64p, u64p,
+                                        ctypes.c_float, ctypes.c_float, ctypes.c_int]
+    lib.oracle_step_lag_f64.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
+                                        ctypes.c_int, ctypes.c_int64, f64p, f64p, f64p, f64p, u64p, u64p,
+                                        ctypes.c_double, ctypes.c_double, ctypes.c_int]
+    lib.oracle_lag_states.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_uint32),
+                                      ctypes.c_uint32, ctypes.POINTER(ctypes.c_uint8)]
+    lib.oracle_lag_masks.argtypes = [ctypes.c_uint64, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+                                     ctypes.c_int, ctypes.c_uint32, u64p, u64p]
+    for f in (lib.oracle_step_lag_f32, lib.oracle_step_lag_f64, lib.oracle_lag_states,
+              lib.oracle_lag_masks):
+        f.restype = ctypes.c_int
     lib.oracle_stale_mask.argtypes = [ctypes.c_uint64, ctypes.c_int64, ctypes.c_int,
                                       ctypes.c_uint32, u64p]
     lib.oracle_straggler_mask.argtypes = [ctypes.c_uint64, ctypes.c_int64, ctypes.c_int, ctypes.c_int, u64p]
@@ -117,7 +130,8 @@ def mask_words(stale) -> np.ndarray | None:
     return words
 
 
-def _step(fn, ctype, dtype, P, S, tau, t, w, g, m, pub, stale, lr, mu, n=None, fixed_groups=False):
+def _step(fn, ctype, dtype, P, S, tau, t, w, g, m, pub, stale, lr, mu, n=None, fixed_groups=False,
+          busy=None):
     for name, a in (("w", w), ("g", g), ("m", m), ("pub", pub)):
         if a.dtype != dtype or a.ndim != 2 or a.shape[0] != P or not a.flags.c_contiguous:
             raise ValueError("%s must be a C-contiguous (P, ld) %s array" % (name, dtype))
@@ -126,27 +140,51 @@ def _step(fn, ctype, dtype, P, S, tau, t, w, g, m, pub, stale, lr, mu, n=None, f
     ld = w.shape[1]
     n = ld if n is None else n
     words = mask_words(stale)
-    if words is not None and words.size != (P + 63) // 64:
-        raise ValueError("stale mask must hold ceil(P/64) words")
+    busy_words = mask_words(busy)
+    for a in (words, busy_words):
+        if a is not None and a.size != (P + 63) // 64:
+            raise ValueError("a mask must hold ceil(P/64) words")
     ptr = ctypes.POINTER(ctype)
+    u64p = ctypes.POINTER(ctypes.c_uint64)
     _check(fn(P, S, n, ld, tau, t,
               w.ctypes.data_as(ptr), g.ctypes.data_as(ptr), m.ctypes.data_as(ptr),
               pub.ctypes.data_as(ptr),
-              None if words is None else words.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64)),
+              None if words is None else words.ctypes.data_as(u64p),
+              None if busy_words is None else busy_words.ctypes.data_as(u64p),
               lr, mu, 1 if fixed_groups else 0), "step")
+
+
+def _plain(fn):
+    """Adapts oracle_step_f32/_f64 (no busy mask) to the argument list _step passes."""
+    def call(P, S, n, ld, tau, t, w, g, m, pub, words, busy_words, lr, mu, fixed):
+        assert busy_words is None
+        return fn(P, S, n, ld, tau, t, w, g, m, pub, words, lr, mu, fixed)
+    return call
 
 
 def step_f32(P, S, tau, t, w, g, m, pub, stale, lr, mu, n=None, fixed_groups=False) -> None:
     """One iteration of Algorithm 2 (lines 6-17) in fp32, in place.
     fixed_groups: the groups of iteration 0 every time (Section 6.2, second ablation)."""
-    _step(_load().oracle_step_f32, ctypes.c_float, np.float32,
+    _step(_plain(_load().oracle_step_f32), ctypes.c_float, np.float32,
           P, S, tau, t, w, g, m, pub, stale, lr, mu, n, fixed_groups)
 
 
 def step_f64(P, S, tau, t, w, g, m, pub, stale, lr, mu, n=None, fixed_groups=False) -> None:
     """The same iteration carried in fp64 (rounding shadow)."""
-    _step(_load().oracle_step_f64, ctypes.c_double, np.float64,
+    _step(_plain(_load().oracle_step_f64), ctypes.c_double, np.float64,
           P, S, tau, t, w, g, m, pub, stale, lr, mu, n, fixed_groups)
+
+
+def step_lag_f32(P, S, tau, t, w, g, m, pub, stale, busy, lr, mu, n=None, fixed_groups=False) -> None:
+    """The iteration when the processes of ``busy`` are still computing an earlier step:
+    they contribute their send buffer again and nothing of them changes."""
+    _step(_load().oracle_step_lag_f32, ctypes.c_float, np.float32,
+          P, S, tau, t, w, g, m, pub, stale, lr, mu, n, fixed_groups, busy)
+
+
+def step_lag_f64(P, S, tau, t, w, g, m, pub, stale, busy, lr, mu, n=None, fixed_groups=False) -> None:
+    _step(_load().oracle_step_lag_f64, ctypes.c_double, np.float64,
+          P, S, tau, t, w, g, m, pub, stale, lr, mu, n, fixed_groups, busy)
 
 
 def stale_mask(seed: int, t: int, P: int, threshold: int) -> np.ndarray:
@@ -174,3 +212,29 @@ def clock_mask(seed: int, t: int, P: int, tolerance_ms: int):
         seed, t, P, tolerance_ms, words.ctypes.data_as(ctypes.POINTER(ctypes.c_uint64)),
         ms.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32))), "clock_mask")
     return words, ms
+
+
+FRESH, LATE, BUSY = 0, 1, 2
+
+
+def lag_states(step_ms: np.ndarray, tolerance_ms: int) -> np.ndarray:
+    """(K, P) states of K iterations after a global one, from (K+1, P) step times in ms:
+    FRESH, LATE (finishes before the next group allreduce reads its send buffer) or BUSY."""
+    step_ms = np.ascontiguousarray(step_ms, dtype=np.uint32)
+    K, P = step_ms.shape[0] - 1, step_ms.shape[1]
+    states = np.zeros((K, P), dtype=np.uint8)
+    _check(_load().oracle_lag_states(
+        P, K, step_ms.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)), tolerance_ms,
+        states.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))), "lag_states")
+    return states
+
+
+def lag_masks(seed: int, t: int, P: int, tau: int, window: int, tolerance_ms: int):
+    """(late words, busy words) of iteration t when steps run back to back between global
+    iterations (every ``window`` iterations when tau == 0) with clock_mask's step times."""
+    late = np.zeros((P + 63) // 64, dtype=np.uint64)
+    busy = np.zeros((P + 63) // 64, dtype=np.uint64)
+    u64p = ctypes.POINTER(ctypes.c_uint64)
+    _check(_load().oracle_lag_masks(seed, t, P, tau, window, tolerance_ms,
+                                    late.ctypes.data_as(u64p), busy.ctypes.data_as(u64p)), "lag_masks")
+    return late, busy

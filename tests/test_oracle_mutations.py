@@ -11,6 +11,7 @@ import pytest
 
 from oracle import wagma_oracle as orc
 import test_oracle_pins as pins
+import test_oracle_lag_pins as lag_pins
 
 SRC = os.path.join(os.path.dirname(os.path.abspath(orc.__file__)), "wagma_oracle.c")
 
@@ -41,13 +42,38 @@ MUTATIONS = [
      "p |= 1 << bits[r];\n            table", "p |= 1 << bits[group_phases - 1 - r];\n            table",
      pins.test_alg1_phase_bits_wrap_order),
     ("send buffer gets W instead of W'",
-     "        /* the send buffer now holds this iteration's locally updated model */\n"
-     "        for (int i = 0; i < P; ++i)\n            pub[(int64_t)i * ld + j] = w_prime[i];",
-     "        for (int i = 0; i < P; ++i)\n            pub[(int64_t)i * ld + j] = w[(int64_t)i * ld + j];",
+     "            if (global || !mask_bit(busy_mask, i))\n                pub[(int64_t)i * ld + j] = w_prime[i];",
+     "            if (global || !mask_bit(busy_mask, i))\n                pub[(int64_t)i * ld + j] = w[(int64_t)i * ld + j];",
      pins.test_stale_rule_hand_value),
     ("global average ignores half of the replicas",
      "float sum = tree_sum_f32(w_prime, P);", "float sum = 2.0f * tree_sum_f32(w_prime, P / 2 ? P / 2 : 1);",
      pins.test_snapshot_script_p4_s2_f32),
+    ("a process that is still computing contributes W' instead of its send buffer",
+     "contrib[e] = (mask_bit(stale_mask, p) || mask_bit(busy_mask, p))\n"
+     "                                     ? pub[(int64_t)p * ld + j] /* send buffer */",
+     "contrib[e] = mask_bit(stale_mask, p)\n"
+     "                                     ? pub[(int64_t)p * ld + j] /* send buffer */",
+     lag_pins.test_busy_member_hand_value),
+    ("a process that is still computing receives the average",
+     "continue; /* the sum waits in its receive buffer, unread */", ";",
+     lag_pins.test_busy_member_hand_value),
+    ("a process that is still computing takes its local step",
+     "continue; /* still computing: nothing of this process changes */", ";",
+     lag_pins.test_snapshot_with_a_step_spanning_two_iterations),
+    ("a global iteration leaves out the processes of the busy mask",
+     "if (!global && mask_bit(busy_mask, i))\n                continue; /* still",
+     "if (mask_bit(busy_mask, i))\n                continue; /* still",
+     lag_pins.test_busy_wins_over_late_and_a_global_iteration_waits_for_everybody),
+    ("late if finished before the next activation, not before the next read",
+     "finish[first] > next_activated + tolerance_ms", "finish[first] > next_activated",
+     lag_pins.test_lag_states_hand_timeline_with_tolerance),
+    ("a process in time begins its next step when it finishes, not when the allreduce is done",
+     "finish[p] = taken + next_ms[p];", "finish[p] += next_ms[p];",
+     lag_pins.test_lag_states_hand_timeline_with_tolerance),
+    ("a late process does not activate the next allreduce",
+     "            if (finish[first] < next_activated)\n                next_activated = finish[first];",
+     "",
+     lambda: lag_pins.test_lag_states_against_an_event_queue(8, 5, 6, 30)),
 ]
 
 
