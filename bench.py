@@ -77,6 +77,9 @@ def main() -> int:
                     help="time wagma_step_tensors on the workload's tensor list (views into the same rows)")
     ap.add_argument("--graph", action="store_true",
                     help="capture the K steps in one HIP graph and time its replay (for launch-bound sizes)")
+    ap.add_argument("--lag", type=int, default=None, metavar="TOLERANCE_MS",
+                    help="lateness deeper than one iteration: wagma_lag_masks with this tolerance drive "
+                         "wagma_step_lag instead of the workload's Bernoulli mask")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-columns", type=int, default=131072)
     args = ap.parse_args()
@@ -123,7 +126,13 @@ def main() -> int:
         log("placement:", info)
     wk.fill_initial_state(wl, w, m, pub)
     wk.fill_gradients(wl, 0, g)       # one gradient slab, reused: generating it is not part of the path
-    masks = [ctx.stale_mask(wl.seed, t, wl.stale_threshold) for t in range(max(K, W))]
+    busy_masks = None
+    if args.lag is None:
+        masks = [ctx.stale_mask(wl.seed, t, wl.stale_threshold) for t in range(max(K, W))]
+    else:
+        both = [ctx.lag_masks(wl.seed, t, args.lag) for t in range(max(K, W))]
+        masks = [late for late, _ in both]
+        busy_masks = [busy for _, busy in both]
     stream = torch.cuda.current_stream()
 
     plan = None
@@ -144,10 +153,11 @@ def main() -> int:
         log("per-tensor layout: %d tensors per replica" % len(sizes))
 
     def step(t):
+        busy = None if busy_masks is None else busy_masks[t]
         if plan is not None:
-            plan.step(masks[t], wl.lr, wl.mu, t)
+            plan.step(masks[t], wl.lr, wl.mu, t, busy_mask=busy)
         else:
-            ctx.step(w, g, m, pub, masks[t], wl.lr, wl.mu, t)
+            ctx.step(w, g, m, pub, masks[t], wl.lr, wl.mu, t, busy_mask=busy)
 
     for t in range(W):
         step(t)
@@ -189,9 +199,11 @@ def main() -> int:
     grp = [t for t in range(K) if not is_global[t]]
     glb = [t for t in range(K) if is_global[t]]
     late = [0 if is_global[t] else popcount(masks[t]) for t in range(K)]
+    busy = [0 if is_global[t] or busy_masks is None else popcount(busy_masks[t]) for t in range(K)]
     # algorithmic bytes: read w, g, m and write w, m, pub for every replica-parameter
-    # (24 B), plus a 4 B send-buffer read for every late replica-parameter
-    bytes_of = [n * (24 * P + 4 * late[t]) for t in range(K)]
+    # (24 B), plus a 4 B send-buffer read for every late replica-parameter; of a process
+    # that is still computing only the send buffer is read (4 B)
+    bytes_of = [n * (24 * (P - busy[t]) + 4 * late[t] + 4 * busy[t]) for t in range(K)]
     grp_ms = sum(ms[t] for t in grp)
     glb_ms = sum(ms[t] for t in glb)
     assert torch.isfinite(w[:, :n]).all()
@@ -208,14 +220,18 @@ def main() -> int:
                 "avg_launch_ms": dom_ms / len(dom_ts), "launches": len(dom_ts),
                 "algorithmic_bytes_per_launch": sum(bytes_of[t] for t in dom_ts) / len(dom_ts),
                 "traffic": MEASURED_TRAFFIC_BYTES.get(wl.index)
-                if grp and not args.opt and not args.ld and plan is None else None}
+                if grp and not args.opt and not args.ld and plan is None and args.lag is None else None}
     out = {
         "metric": "replica-params averaged/sec", "value": P * n * K / wall, "unit": "replica-params/s",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": wall * 1e3 / K,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "P": P, "S": S, "n": n, "ld": ld, "tau": wl.tau,
-                   "late_probability": wl.q, "global_steps_in_run": len(glb),
+                   "late_probability": wl.q if args.lag is None else None,
+                   "lateness": "Bernoulli mask per iteration" if args.lag is None else
+                   "steps back to back, tolerance %d ms: %.3f of the process-iterations late, %.3f still computing"
+                   % (args.lag, sum(late) / max(1, P * len(grp)), sum(busy) / max(1, P * len(grp))),
+                   "global_steps_in_run": len(glb),
                    "options": args.opt, "allocation": placement,
                    "layout": "per-tensor" if plan is not None else "flat rows",
                    "launch": "one HIP graph of K steps" if args.graph else "one launch per step"},

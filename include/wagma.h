@@ -164,6 +164,31 @@ int wagma_step_tensors(wagma_ctx* ctx, const wagma_tensors* plan, const uint64_t
                        float lr, float mu, int64_t iter, void* stream);
 
 /*
+ * Lateness deeper than one iteration.  The execution snapshot of Section 4 shows a straggler
+ * whose send buffer is taken by a group allreduce while it is still computing; Assumption 1
+ * (item 3) lets that go on for up to tau iterations.  In wagma_step_lag a process is in one of
+ * three states in a group iteration:
+ *   in time          bit clear in both masks: Algorithm 2 lines 6-7 and 9-11;
+ *   late             bit set in late_mask: it contributes its send buffer, ends its local step
+ *                    afterwards and averages the group's sum with its W' (lines 12-13), exactly
+ *                    the stale_mask of wagma_step;
+ *   still computing  bit set in busy_mask (late_mask is then not looked at for it): it
+ *                    contributes its send buffer once more and nothing else of it is read or
+ *                    written: no gradient, no local step, send buffer not refreshed; the sum it
+ *                    would find in its receive buffer is overwritten by a later one.
+ * A global iteration ((iter+1) mod tau == 0) waits for everybody: both masks are ignored.
+ * late_mask, busy_mask: host, ceil(P/64) words each, bit p = process p, either may be NULL
+ * (nobody), consumed before the call returns.  With busy_mask NULL or empty the call is
+ * wagma_step.  All other arguments, errors and the absence of allocation, copies and
+ * synchronisation as for wagma_step and wagma_step_tensors.
+ */
+int wagma_step_lag(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub,
+                   const uint64_t* late_mask, const uint64_t* busy_mask, float lr, float mu,
+                   int64_t iter, void* stream);
+int wagma_step_tensors_lag(wagma_ctx* ctx, const wagma_tensors* plan, const uint64_t* late_mask,
+                           const uint64_t* busy_mask, float lr, float mu, int64_t iter, void* stream);
+
+/*
  * Seeded lateness model (not from the paper, whose lateness is physical; its
  * simulation delays random ranks, Section 6.2): process p is late in iteration
  * iter iff the upper 32 bits of a 64-bit hash of (seed, iter, p) are below
@@ -191,6 +216,26 @@ int wagma_straggler_mask(const wagma_ctx* ctx, uint64_t seed, int64_t iter, int 
                          uint64_t* mask_words);
 int wagma_clock_mask(const wagma_ctx* ctx, uint64_t seed, int64_t iter, uint32_t tolerance_ms,
                      uint64_t* mask_words, uint32_t* step_ms);
+
+/*
+ * The two masks of wagma_step_lag for iteration iter when nobody waits for anybody between two
+ * global iterations (Section 3.2): every process runs its local steps back to back with the step
+ * times of wagma_clock_mask (a step begun for the group allreduce of iteration k takes the time
+ * the process draws in iteration k); the first process to end a step begun for an allreduce
+ * activates it, the allreduce reads the models tolerance_ms later, and who arrived by then takes
+ * the average and goes on from that moment.  A process that ends a step after an allreduce has
+ * read and before the next one reads is late in that iteration and begins its next step at
+ * once; one that is still computing when the next one reads is busy.  The clocks restart after
+ * every global iteration, where everybody waits (both masks are empty there); a context with
+ * tau == 0 restarts them every `window` iterations (window >= 1; ignored when tau > 0), so that
+ * no send buffer is older than that (Assumption 1, item 3).
+ *   tolerance_ms  below 1700 (the shortest step), else WAGMA_EINVAL.
+ *   late_words, busy_words   host, out, ceil(P/64) words each; no process is in both.
+ * Integer only and reproducible; host work proportional to P times the iterations since the
+ * clocks restarted.
+ */
+int wagma_lag_masks(const wagma_ctx* ctx, uint64_t seed, int64_t iter, int window,
+                    uint32_t tolerance_ms, uint64_t* late_words, uint64_t* busy_words);
 
 /*
  * Optional allocator for the four P x ld arrays (device memory, contents unspecified).  A caller

@@ -28,7 +28,10 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <functional>
 #include <new>
+#include <queue>
+#include <vector>
 
 #include "wagma.h"
 #include "wagma_kernels.h"
@@ -346,47 +349,48 @@ int hip_failed(hipError_t e)
 
 // WAVES = resident wavefronts per SIMD the register allocation must allow
 // (2, 3 or 4: at most 256, 168 or 128 vector registers per lane).
-template <int S, bool NT, int BLOCK, int WAVES>
+template <int S, bool NT, bool LAG, int BLOCK, int WAVES>
 void launch_registers(const StepParams& p, unsigned grid, hipStream_t stream)
 {
-    hipLaunchKernelGGL((step_rows_in_registers<S, NT, BLOCK, WAVES>), dim3(grid), dim3(BLOCK), 0,
+    hipLaunchKernelGGL((step_rows_in_registers<S, NT, LAG, BLOCK, WAVES>), dim3(grid), dim3(BLOCK), 0,
                        stream, p);
 }
 
-template <bool NT, int BLOCK, int WAVES>
+template <bool NT, bool LAG, int BLOCK, int WAVES>
 void launch_variant(const StepParams& p, bool streamed, unsigned grid, hipStream_t stream)
 {
     if (streamed) {
-        hipLaunchKernelGGL((step_rows_streamed<NT, BLOCK, WAVES>), dim3(grid), dim3(BLOCK), 0,
+        hipLaunchKernelGGL((step_rows_streamed<NT, LAG, BLOCK, WAVES>), dim3(grid), dim3(BLOCK), 0,
                            stream, p);
         return;
     }
     switch (p.members) {
-    case 1: launch_registers<1, NT, BLOCK, 4>(p, grid, stream); break;
-    case 2: launch_registers<2, NT, BLOCK, 4>(p, grid, stream); break;
-    case 4: launch_registers<4, NT, BLOCK, 4>(p, grid, stream); break;
-    default: launch_registers<8, NT, BLOCK, WAVES>(p, grid, stream); break;
+    case 1: launch_registers<1, NT, LAG, BLOCK, 4>(p, grid, stream); break;
+    case 2: launch_registers<2, NT, LAG, BLOCK, 4>(p, grid, stream); break;
+    case 4: launch_registers<4, NT, LAG, BLOCK, 4>(p, grid, stream); break;
+    default: launch_registers<8, NT, LAG, BLOCK, WAVES>(p, grid, stream); break;
     }
 }
 
-template <bool NT, int BLOCK>
+template <bool NT, bool LAG, int BLOCK>
 void launch_waves(const StepParams& p, bool streamed, int waves, unsigned grid, hipStream_t stream)
 {
     switch (waves) {
-    case 2: launch_variant<NT, BLOCK, 2>(p, streamed, grid, stream); break;
-    case 3: launch_variant<NT, BLOCK, 3>(p, streamed, grid, stream); break;
-    default: launch_variant<NT, BLOCK, 4>(p, streamed, grid, stream); break;
+    case 2: launch_variant<NT, LAG, BLOCK, 2>(p, streamed, grid, stream); break;
+    case 3: launch_variant<NT, LAG, BLOCK, 3>(p, streamed, grid, stream); break;
+    default: launch_variant<NT, LAG, BLOCK, 4>(p, streamed, grid, stream); break;
     }
 }
 
-template <bool NT>
+// LAG: the kernels that also look at the busy mask (chosen only when a bit of it is set).
+template <bool NT, bool LAG>
 void launch_block(const StepParams& p, bool streamed, int block, int waves, unsigned grid,
                   hipStream_t stream)
 {
     if (block == 512)
-        launch_waves<NT, 512>(p, streamed, waves, grid, stream);
+        launch_waves<NT, LAG, 512>(p, streamed, waves, grid, stream);
     else
-        launch_waves<NT, 256>(p, streamed, waves, grid, stream);
+        launch_waves<NT, LAG, 256>(p, streamed, waves, grid, stream);
 }
 
 }  // namespace
@@ -425,25 +429,26 @@ struct wagma_tensors {
 namespace {
 constexpr int kTensorBlock = 256;  // threads per workgroup of the per-tensor kernels
 
-template <bool NT>
+template <bool NT, bool LAG>
 void launch_tensors(const StepParams& p, unsigned grid, hipStream_t stream)
 {
     const dim3 g(grid), b(kTensorBlock);
     switch (p.members) {
-    case 1: hipLaunchKernelGGL((step_tensors_in_registers<1, NT, kTensorBlock>), g, b, 0, stream, p); break;
-    case 2: hipLaunchKernelGGL((step_tensors_in_registers<2, NT, kTensorBlock>), g, b, 0, stream, p); break;
-    case 4: hipLaunchKernelGGL((step_tensors_in_registers<4, NT, kTensorBlock>), g, b, 0, stream, p); break;
-    case 8: hipLaunchKernelGGL((step_tensors_in_registers<8, NT, kTensorBlock>), g, b, 0, stream, p); break;
-    default: hipLaunchKernelGGL((step_tensors_streamed<NT, kTensorBlock>), g, b, 0, stream, p); break;
+    case 1: hipLaunchKernelGGL((step_tensors_in_registers<1, NT, LAG, kTensorBlock>), g, b, 0, stream, p); break;
+    case 2: hipLaunchKernelGGL((step_tensors_in_registers<2, NT, LAG, kTensorBlock>), g, b, 0, stream, p); break;
+    case 4: hipLaunchKernelGGL((step_tensors_in_registers<4, NT, LAG, kTensorBlock>), g, b, 0, stream, p); break;
+    case 8: hipLaunchKernelGGL((step_tensors_in_registers<8, NT, LAG, kTensorBlock>), g, b, 0, stream, p); break;
+    default: hipLaunchKernelGGL((step_tensors_streamed<NT, LAG, kTensorBlock>), g, b, 0, stream, p); break;
     }
 }
 }  // namespace
 
 namespace {
 
-// The part of the kernel arguments that both layouts share.
-void fill_common(const wagma_ctx* ctx, StepParams& p, bool global, const uint64_t* stale_mask,
-                        float lr, float mu, int64_t iter)
+// The part of the kernel arguments that both layouts share.  Returns true if some process is
+// still computing in this iteration (then the kernels that look at the busy mask are needed).
+bool fill_common(const wagma_ctx* ctx, StepParams& p, bool global, const uint64_t* stale_mask,
+                 const uint64_t* busy_mask, float lr, float mu, int64_t iter)
 {
     std::memset(&p, 0, sizeof(p));
     p.lr = lr;
@@ -454,13 +459,18 @@ void fill_common(const wagma_ctx* ctx, StepParams& p, bool global, const uint64_
     const int32_t* table = nullptr;
     wagma_group_schedule(ctx, iter, &table, nullptr);
     p.table = table;
-    if (!global && stale_mask) {
-        const int words = (ctx->P + 63) / 64;
-        for (int k = 0; k < words; ++k)
-            p.late[k] = stale_mask[k];
-        if (ctx->P < 64)
-            p.late[0] &= (UINT64_C(1) << ctx->P) - 1;
+    if (global)
+        return false;  // a global iteration waits for everybody
+    const int words = (ctx->P + 63) / 64;
+    const uint64_t in_use = ctx->P < 64 ? (UINT64_C(1) << ctx->P) - 1 : ~UINT64_C(0);
+    uint64_t any_busy = 0;
+    for (int k = 0; k < words; ++k) {
+        p.busy[k] = busy_mask ? busy_mask[k] & in_use : 0;
+        // a process that is still computing contributes its send buffer like a late one
+        p.late[k] = ((stale_mask ? stale_mask[k] : 0) & in_use) | p.busy[k];
+        any_busy |= p.busy[k];
     }
+    return any_busy != 0;
 }
 
 }  // namespace
@@ -470,7 +480,7 @@ namespace {
 // wagma_step; with group_only the iteration is treated as a group iteration whatever tau says
 // (the allocator times group steps with it).
 int step_flat(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub, const uint64_t* stale_mask,
-              float lr, float mu, int64_t iter, void* stream, bool group_only)
+              const uint64_t* busy_mask, float lr, float mu, int64_t iter, void* stream, bool group_only)
 {
     int global = wagma_is_global_iteration(ctx, iter);
     if (global < 0)
@@ -489,7 +499,7 @@ int step_flat(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub, co
         return WAGMA_EINVAL;
 
     StepParams p;
-    fill_common(ctx, p, global != 0, stale_mask, lr, mu, iter);
+    const bool lag = fill_common(ctx, p, global != 0, stale_mask, busy_mask, lr, mu, iter);
     if (group_only)
         p.table = ctx->d_table + (ctx->fixed_groups ? 0 : iter % ctx->period) * ctx->P;
     p.w = w;
@@ -520,10 +530,18 @@ int step_flat(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub, co
     if (grid > 0x7fffffff)
         return WAGMA_EINVAL;
 
-    if (ctx->opt_nontemporal)
-        launch_block<true>(p, streamed, block, ctx->opt_waves, (unsigned)grid, (hipStream_t)stream);
-    else
-        launch_block<false>(p, streamed, block, ctx->opt_waves, (unsigned)grid, (hipStream_t)stream);
+    const hipStream_t on = (hipStream_t)stream;
+    if (ctx->opt_nontemporal) {
+        if (lag)
+            launch_block<true, true>(p, streamed, block, ctx->opt_waves, (unsigned)grid, on);
+        else
+            launch_block<true, false>(p, streamed, block, ctx->opt_waves, (unsigned)grid, on);
+    } else {
+        if (lag)
+            launch_block<false, true>(p, streamed, block, ctx->opt_waves, (unsigned)grid, on);
+        else
+            launch_block<false, false>(p, streamed, block, ctx->opt_waves, (unsigned)grid, on);
+    }
     e = hipGetLastError();
     if (e != hipSuccess)
         return hip_failed(e);
@@ -674,7 +692,7 @@ double time_steps(wagma_ctx* ctx, const ArraySet& set)
         const int steps = ctx->period;
         ok = hipEventRecord(start, nullptr) == hipSuccess;
         for (int t = 0; t < steps && ok; ++t)
-            ok = step_flat(ctx, set.ptr[0], set.ptr[1], set.ptr[2], set.ptr[3], late, 0.0f, 0.0f, t, nullptr,
+            ok = step_flat(ctx, set.ptr[0], set.ptr[1], set.ptr[2], set.ptr[3], late, nullptr, 0.0f, 0.0f, t, nullptr,
                            true) == WAGMA_OK;
         ok = ok && hipEventRecord(stop, nullptr) == hipSuccess && hipEventSynchronize(stop) == hipSuccess;
         float ms = 0.0f;
@@ -927,7 +945,14 @@ int wagma_group_schedule(const wagma_ctx* ctx, int64_t iter, const int32_t** dev
 int wagma_step(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub,
                const uint64_t* stale_mask, float lr, float mu, int64_t iter, void* stream)
 {
-    return step_flat(ctx, w, g, m, pub, stale_mask, lr, mu, iter, stream, false);
+    return step_flat(ctx, w, g, m, pub, stale_mask, nullptr, lr, mu, iter, stream, false);
+}
+
+int wagma_step_lag(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub,
+                   const uint64_t* late_mask, const uint64_t* busy_mask, float lr, float mu, int64_t iter,
+                   void* stream)
+{
+    return step_flat(ctx, w, g, m, pub, late_mask, busy_mask, lr, mu, iter, stream, false);
 }
 
 // ---- per-tensor layout ------------------------------------------------------------------
@@ -1032,6 +1057,12 @@ int wagma_tensors_destroy(wagma_tensors* plan)
 int wagma_step_tensors(wagma_ctx* ctx, const wagma_tensors* plan, const uint64_t* stale_mask, float lr,
                        float mu, int64_t iter, void* stream)
 {
+    return wagma_step_tensors_lag(ctx, plan, stale_mask, nullptr, lr, mu, iter, stream);
+}
+
+int wagma_step_tensors_lag(wagma_ctx* ctx, const wagma_tensors* plan, const uint64_t* late_mask,
+                           const uint64_t* busy_mask, float lr, float mu, int64_t iter, void* stream)
+{
     const int global = wagma_is_global_iteration(ctx, iter);
     if (global < 0)
         return global;
@@ -1045,7 +1076,7 @@ int wagma_step_tensors(wagma_ctx* ctx, const wagma_tensors* plan, const uint64_t
         return WAGMA_EINVAL;
 
     StepParams p;
-    fill_common(ctx, p, global != 0, stale_mask, lr, mu, iter);
+    const bool lag = fill_common(ctx, p, global != 0, late_mask, busy_mask, lr, mu, iter);
     p.tw = plan->tw;
     p.tg = plan->tg;
     p.tm = plan->tm;
@@ -1056,10 +1087,18 @@ int wagma_step_tensors(wagma_ctx* ctx, const wagma_tensors* plan, const uint64_t
     p.tiles = plan->tiles;
     p.blocks = (int64_t)(ctx->P / p.members) * p.tiles;
     p.log2_chunks = p.members > kChunk ? exact_log2(p.members / kChunk) : 0;
-    if (ctx->opt_nontemporal)
-        launch_tensors<true>(p, (unsigned)p.blocks, (hipStream_t)stream);
-    else
-        launch_tensors<false>(p, (unsigned)p.blocks, (hipStream_t)stream);
+    const hipStream_t on = (hipStream_t)stream;
+    if (ctx->opt_nontemporal) {
+        if (lag)
+            launch_tensors<true, true>(p, (unsigned)p.blocks, on);
+        else
+            launch_tensors<true, false>(p, (unsigned)p.blocks, on);
+    } else {
+        if (lag)
+            launch_tensors<false, true>(p, (unsigned)p.blocks, on);
+        else
+            launch_tensors<false, false>(p, (unsigned)p.blocks, on);
+    }
     e = hipGetLastError();
     if (e != hipSuccess)
         return hip_failed(e);
@@ -1118,25 +1157,33 @@ int wagma_straggler_mask(const wagma_ctx* ctx, uint64_t seed, int64_t iter, int 
     return WAGMA_OK;
 }
 
-int wagma_clock_mask(const wagma_ctx* ctx, uint64_t seed, int64_t iter, uint32_t tolerance_ms,
-                     uint64_t* mask_words, uint32_t* step_ms)
+// The step times, in ms, that the P processes draw in iteration iter: nine in sixteen take
+// 1.7 s to 2 s, the others one of 16 geometric steps from 2 s to 43.5 s (the range and the
+// median of the reinforcement-learning workload of Section 6.4).
+static void clock_step_times(uint64_t seed, int64_t iter, int P, uint32_t* ms)
 {
-    // 16 geometric steps from 2 s to 43.5 s: the tail of the step-time distribution
     static const uint32_t kTailMs[16] = {2000, 2456, 3016, 3703, 4548, 5585, 6858, 8422,
                                          10342, 12700, 15595, 19151, 23517, 28879, 35463, 43500};
-    if (!ctx || iter < 0 || !mask_words)
-        return WAGMA_EINVAL;
-    uint32_t ms[WAGMA_MAX_P];
     const uint64_t iter_key =
         mix64((seed ^ UINT64_C(0x434C4F434B4D534B)) + ((uint64_t)iter + 1) * UINT64_C(0x9E3779B97F4A7C15));
-    uint32_t first_done = UINT32_MAX;
-    for (int rank = 0; rank < ctx->P; ++rank) {
+    for (int rank = 0; rank < P; ++rank) {
         const uint64_t h = mix64(iter_key + ((uint64_t)rank + 1) * UINT64_C(0xD1B54A32D192ED03));
         const bool in_tail = (h >> 60) >= 9;  // seven steps in sixteen
         ms[rank] = in_tail ? kTailMs[(h >> 56) & 15] : 1700u + (uint32_t)((h >> 32) & 0xFF) * 300u / 256u;
+    }
+}
+
+int wagma_clock_mask(const wagma_ctx* ctx, uint64_t seed, int64_t iter, uint32_t tolerance_ms,
+                     uint64_t* mask_words, uint32_t* step_ms)
+{
+    if (!ctx || iter < 0 || !mask_words)
+        return WAGMA_EINVAL;
+    uint32_t ms[WAGMA_MAX_P];
+    clock_step_times(seed, iter, ctx->P, ms);
+    uint32_t first_done = UINT32_MAX;
+    for (int rank = 0; rank < ctx->P; ++rank)
         if (ms[rank] < first_done)
             first_done = ms[rank];
-    }
     const int words = (ctx->P + 63) / 64;
     for (int k = 0; k < words; ++k)
         mask_words[k] = 0;
@@ -1145,6 +1192,95 @@ int wagma_clock_mask(const wagma_ctx* ctx, uint64_t seed, int64_t iter, uint32_t
             mask_words[rank >> 6] |= UINT64_C(1) << (rank & 63);
         if (step_ms)
             step_ms[rank] = ms[rank];
+    }
+    return WAGMA_OK;
+}
+
+int wagma_lag_masks(const wagma_ctx* ctx, uint64_t seed, int64_t iter, int window, uint32_t tolerance_ms,
+                    uint64_t* late_words, uint64_t* busy_words)
+{
+    if (!ctx || iter < 0 || !late_words || !busy_words || tolerance_ms >= 1700u ||
+        (ctx->tau == 0 && window < 1))
+        return WAGMA_EINVAL;
+    const int P = ctx->P;
+    const int words = (P + 63) / 64;
+    for (int k = 0; k < words; ++k)
+        late_words[k] = busy_words[k] = 0;
+    if (wagma_is_global_iteration(ctx, iter) == 1)
+        return WAGMA_OK;  // everybody waits for the global average
+    // The clocks start together after every global iteration (every `window` iterations when
+    // there is none) and run until the group allreduce after this iteration's has read.
+    const int64_t length = ctx->tau > 0 ? ctx->tau : window;
+    const int64_t first_iter = iter / length * length;
+    const int64_t target = iter - first_iter;  // allreduce number inside the window
+
+    // Time-ordered events.  A step's end is seen by a read that happens at the same time.
+    struct Event {
+        int64_t at;
+        int is_read;    // 0: a process ends a step, 1: the running allreduce reads the models
+        int rank;
+        int64_t begun;  // the allreduce the step was begun for
+        bool operator>(const Event& o) const
+        {
+            if (at != o.at)
+                return at > o.at;
+            if (is_read != o.is_read)
+                return is_read > o.is_read;
+            return rank > o.rank;
+        }
+    };
+    std::priority_queue<Event, std::vector<Event>, std::greater<Event>> events;
+    std::vector<int> waiting;                    // arrived at the running allreduce, not yet read
+    uint8_t went_on[WAGMA_MAX_P] = {0};          // ended a step since the target allreduce read
+    try {
+        // times[k & 1]: the step times drawn for steps begun for allreduce k
+        std::vector<uint32_t> times[2] = {std::vector<uint32_t>((size_t)P), std::vector<uint32_t>((size_t)P)};
+        clock_step_times(seed, first_iter, P, times[0].data());
+        clock_step_times(seed, first_iter + 1, P, times[1].data());
+        for (int rank = 0; rank < P; ++rank)
+            events.push(Event{(int64_t)times[0][(size_t)rank], 0, rank, 0});
+        int64_t running = 0;  // the allreduce that will read next
+        while (true) {
+            const Event ev = events.top();
+            events.pop();
+            if (ev.is_read && running == target + 1)
+                break;  // whoever ended a step since the target read was late in it
+            if (ev.is_read) {
+                // those who arrived in time take the average and go on together
+                for (int rank : waiting)
+                    events.push(Event{ev.at + (int64_t)times[(running + 1) & 1][(size_t)rank], 0, rank, running + 1});
+                if (running == target) {
+                    // everybody else contributes a send buffer; who also ends a step before
+                    // the next read is late, the rest is still computing
+                    for (int rank = 0; rank < P; ++rank)
+                        busy_words[rank >> 6] |= UINT64_C(1) << (rank & 63);
+                    for (int rank : waiting)
+                        busy_words[rank >> 6] &= ~(UINT64_C(1) << (rank & 63));
+                }
+                waiting.clear();
+                ++running;
+                clock_step_times(seed, first_iter + running + 1, P, times[(running + 1) & 1].data());
+            } else if (ev.begun == running) {
+                if (waiting.empty())  // the activator
+                    events.push(Event{ev.at + (int64_t)tolerance_ms, 1, -1, running});
+                waiting.push_back(ev.rank);
+            } else {
+                // the allreduce this step was begun for has read already: the process averages
+                // the sum it finds with its W' and begins the next step at once
+                events.push(Event{ev.at + (int64_t)times[running & 1][(size_t)ev.rank], 0, ev.rank, running});
+                if (running == target + 1)
+                    went_on[ev.rank] = 1;
+            }
+        }
+    } catch (const std::bad_alloc&) {
+        return WAGMA_ENOMEM;
+    }
+    for (int rank = 0; rank < P; ++rank) {
+        const uint64_t bit = UINT64_C(1) << (rank & 63);
+        if (went_on[rank] && (busy_words[rank >> 6] & bit)) {
+            busy_words[rank >> 6] &= ~bit;
+            late_words[rank >> 6] |= bit;
+        }
     }
     return WAGMA_OK;
 }

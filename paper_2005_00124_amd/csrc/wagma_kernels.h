@@ -35,7 +35,8 @@ struct StepParams {
     int64_t nvec;          // 16-byte column slices per row = ceil(n/4)
     int64_t tiles;         // workgroups per group = ceil(nvec / block)
     int64_t blocks;        // groups * tiles (grid may be padded beyond this)
-    uint64_t late[kMaskWords];
+    uint64_t late[kMaskWords];  // bit p: process p contributes its send buffer (late or still computing)
+    uint64_t busy[kMaskWords];  // bit p: process p is still computing an earlier step (LAG kernels only)
     float lr;
     float mu;
     float inv_members;     // 1/S (or 1/P): exact, a power of two
@@ -96,6 +97,14 @@ __device__ __forceinline__ bool is_late(const StepParams& p, int rank)
     return (p.late[rank >> 6] >> (rank & 63)) & 1u;
 }
 
+// A process that is still computing an earlier step when the group allreduce runs
+// (Section 4, the execution snapshot, over more than one iteration): its send buffer is
+// contributed once more, and nothing of it is read besides or written at all.
+__device__ __forceinline__ bool is_busy(const StepParams& p, int rank)
+{
+    return (p.busy[rank >> 6] >> (rank & 63)) & 1u;
+}
+
 // Balanced pairwise sum of N = 2^k values: adjacent members first, i.e. the
 // butterfly phases of Section 3.3 in the order Algorithm 1 runs them.
 template <int N, typename V>
@@ -134,20 +143,24 @@ struct TensorAddr {
     __device__ __forceinline__ float* pub(int rank) const { return p.tpub[slot(rank)] + lane_at; }
 };
 
-// One group of S <= 8 members, all member rows held in registers.
-template <int S, bool NT, typename V, typename Addr>
+// One group of S <= 8 members, all member rows held in registers.  LAG: some members may
+// be still computing (is_busy); without it the busy mask is not looked at.
+template <int S, bool NT, bool LAG, typename V, typename Addr>
 __device__ __forceinline__ void registers_body(const StepParams& p, const int32_t* member, const Addr& at)
 {
-    bool late[S];
+    bool late[S], busy[S];
     int rank[S];
     V wv[S], gv[S], mv[S], contrib[S];
 #pragma unroll
     for (int e = 0; e < S; ++e) {
         rank[e] = member[e];
         late[e] = is_late(p, rank[e]);
-        wv[e] = load_v<NT, V>(at.w(rank[e]));
-        gv[e] = load_v<NT, V>(at.g(rank[e]));
-        mv[e] = load_v<NT, V>(at.m(rank[e]));
+        busy[e] = LAG && is_busy(p, rank[e]);
+        if (!busy[e]) {
+            wv[e] = load_v<NT, V>(at.w(rank[e]));
+            gv[e] = load_v<NT, V>(at.g(rank[e]));
+            mv[e] = load_v<NT, V>(at.m(rank[e]));
+        }
     }
 #pragma unroll
     for (int e = 0; e < S; ++e)
@@ -158,6 +171,8 @@ __device__ __forceinline__ void registers_body(const StepParams& p, const int32_
     // no difference.)
 #pragma unroll
     for (int e = 0; e < S; ++e) {
+        if (busy[e])
+            continue;
         const V m_new = fma_v(p.mu, mv[e], gv[e]);
         wv[e] = fma_v(-p.lr, m_new, wv[e]);  // W'
         store_v<NT, V>(at.m(rank[e]), m_new);
@@ -168,6 +183,8 @@ __device__ __forceinline__ void registers_body(const StepParams& p, const int32_
     const V w_sum = tree_sum<S, V>(contrib);
 #pragma unroll
     for (int e = 0; e < S; ++e) {
+        if (busy[e])
+            continue;  // the sum would wait in its receive buffer, unread
         V out;
         if (late[e])
             out = (w_sum + wv[e]) / p.members_plus_1;
@@ -178,7 +195,7 @@ __device__ __forceinline__ void registers_body(const StepParams& p, const int32_
 }
 
 // One group of any size >= 8: member rows streamed 8 at a time.
-template <bool NT, typename V, typename Addr>
+template <bool NT, bool LAG, typename V, typename Addr>
 __device__ __forceinline__ void streamed_body(const StepParams& p, const int32_t* member, const Addr& at)
 {
     const int chunks = p.members / kChunk;
@@ -186,15 +203,18 @@ __device__ __forceinline__ void streamed_body(const StepParams& p, const int32_t
     V acc;
     for (int c = 0; c < chunks; ++c) {
         int rank[kChunk];
-        bool late[kChunk];
+        bool late[kChunk], busy[kChunk];
         V wv[kChunk], gv[kChunk], mv[kChunk], contrib[kChunk];
 #pragma unroll
         for (int i = 0; i < kChunk; ++i) {
             rank[i] = member[c * kChunk + i];
             late[i] = is_late(p, rank[i]);
-            wv[i] = load_v<NT, V>(at.w(rank[i]));
-            gv[i] = load_v<NT, V>(at.g(rank[i]));
-            mv[i] = load_v<NT, V>(at.m(rank[i]));
+            busy[i] = LAG && is_busy(p, rank[i]);
+            if (!busy[i]) {
+                wv[i] = load_v<NT, V>(at.w(rank[i]));
+                gv[i] = load_v<NT, V>(at.g(rank[i]));
+                mv[i] = load_v<NT, V>(at.m(rank[i]));
+            }
         }
 #pragma unroll
         for (int i = 0; i < kChunk; ++i)
@@ -202,6 +222,8 @@ __device__ __forceinline__ void streamed_body(const StepParams& p, const int32_t
                 contrib[i] = load_v<NT, V>(at.pub(rank[i]));
 #pragma unroll
         for (int i = 0; i < kChunk; ++i) {
+            if (busy[i])
+                continue;
             const V m_new = fma_v(p.mu, mv[i], gv[i]);
             wv[i] = fma_v(-p.lr, m_new, wv[i]);
             store_v<NT, V>(at.m(rank[i]), m_new);
@@ -238,6 +260,8 @@ __device__ __forceinline__ void streamed_body(const StepParams& p, const int32_t
 
     for (int e = 0; e < p.members; ++e) {
         const int rank = member[e];
+        if (LAG && is_busy(p, rank))
+            continue;
         V out = fresh;
         if (is_late(p, rank)) {
             // W' of this member: this thread stored it to the send buffer above.
@@ -292,31 +316,31 @@ __device__ __forceinline__ bool decode_block(const StepParams& p, int64_t& group
     return col < p.nvec;
 }
 
-template <int S, bool NT, int BLOCK, int WAVES>
+template <int S, bool NT, bool LAG, int BLOCK, int WAVES>
 __global__ void __launch_bounds__(BLOCK, WAVES) step_rows_in_registers(const StepParams p)
 {
     int64_t group, col;
     if (!decode_block<BLOCK>(p, group, col))
         return;
     const FlatAddr at{p, (uint32_t)col * 4u};
-    registers_body<S, NT, v4f>(p, p.table + group * S, at);
+    registers_body<S, NT, LAG, v4f>(p, p.table + group * S, at);
 }
 
-template <bool NT, int BLOCK, int WAVES>
+template <bool NT, bool LAG, int BLOCK, int WAVES>
 __global__ void __launch_bounds__(BLOCK, WAVES) step_rows_streamed(const StepParams p)
 {
     int64_t group, col;
     if (!decode_block<BLOCK>(p, group, col))
         return;
     const FlatAddr at{p, (uint32_t)col * 4u};
-    streamed_body<NT, v4f>(p, p.table + group * p.members, at);
+    streamed_body<NT, LAG, v4f>(p, p.table + group * p.members, at);
 }
 
 // Per-tensor layout.  Workgroup b owns tile b % tiles of group b / tiles; the tile table
 // names the tensor and the tile's first 16-byte slice inside it.  A lane whose slice is
 // cut off by the end of the tensor does the remaining 1..3 elements one by one; nothing
 // beyond a tensor's last element is touched.
-template <int S, bool NT, int BLOCK>
+template <int S, bool NT, bool LAG, int BLOCK>
 __global__ void __launch_bounds__(BLOCK, 2) step_tensors_in_registers(const StepParams p)
 {
     const int64_t group = blockIdx.x / p.tiles;
@@ -328,16 +352,16 @@ __global__ void __launch_bounds__(BLOCK, 2) step_tensors_in_registers(const Step
     const int32_t* member = p.table + group * S;
     TensorAddr at{p, ref.tensor, (uint32_t)first};
     if (first + 4 <= size) {
-        registers_body<S, NT, v4f>(p, member, at);
+        registers_body<S, NT, LAG, v4f>(p, member, at);
     } else {
         for (int64_t k = first; k < size; ++k) {
             at.lane_at = (uint32_t)k;
-            registers_body<S, NT, float>(p, member, at);
+            registers_body<S, NT, LAG, float>(p, member, at);
         }
     }
 }
 
-template <bool NT, int BLOCK>
+template <bool NT, bool LAG, int BLOCK>
 __global__ void __launch_bounds__(BLOCK, 2) step_tensors_streamed(const StepParams p)
 {
     const int64_t group = blockIdx.x / p.tiles;
@@ -349,11 +373,11 @@ __global__ void __launch_bounds__(BLOCK, 2) step_tensors_streamed(const StepPara
     const int32_t* member = p.table + group * p.members;
     TensorAddr at{p, ref.tensor, (uint32_t)first};
     if (first + 4 <= size) {
-        streamed_body<NT, v4f>(p, member, at);
+        streamed_body<NT, LAG, v4f>(p, member, at);
     } else {
         for (int64_t k = first; k < size; ++k) {
             at.lane_at = (uint32_t)k;
-            streamed_body<NT, float>(p, member, at);
+            streamed_body<NT, LAG, float>(p, member, at);
         }
     }
 }

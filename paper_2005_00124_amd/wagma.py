@@ -45,6 +45,13 @@ SYMBOLS = {
     "wagma_tensors_destroy": (ctypes.c_int, [ctypes.c_void_p]),
     "wagma_step_tensors": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, _u64p, ctypes.c_float,
                                           ctypes.c_float, ctypes.c_int64, ctypes.c_void_p]),
+    "wagma_step_lag": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                      ctypes.c_void_p, _u64p, _u64p, ctypes.c_float, ctypes.c_float,
+                                      ctypes.c_int64, ctypes.c_void_p]),
+    "wagma_step_tensors_lag": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, _u64p, _u64p, ctypes.c_float,
+                                              ctypes.c_float, ctypes.c_int64, ctypes.c_void_p]),
+    "wagma_lag_masks": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int64, ctypes.c_int,
+                                       ctypes.c_uint32, _u64p, _u64p]),
     "wagma_stale_mask": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int64,
                                         ctypes.c_uint32, _u64p]),
     "wagma_straggler_mask": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_int64, ctypes.c_int, _u64p]),
@@ -169,6 +176,25 @@ def wagma_step(ctx: int, w, g, m, pub, stale_mask: Optional[np.ndarray], lr: flo
            "wagma_step")
 
 
+def _mask_arg(mask: Optional[np.ndarray]):
+    """(object to keep alive, ctypes pointer or None) for a host mask of uint64 words."""
+    if mask is None:
+        return None, None
+    mask = np.ascontiguousarray(mask, dtype=np.uint64)
+    return mask, mask.ctypes.data_as(_u64p)
+
+
+def wagma_step_lag(ctx: int, w, g, m, pub, late_mask: Optional[np.ndarray], busy_mask: Optional[np.ndarray],
+                   lr: float, mu: float, it: int, stream: Optional[int] = None) -> None:
+    """wagma_step with a second mask: the processes that are still computing an earlier step."""
+    keep_late, late = _mask_arg(late_mask)
+    keep_busy, busy = _mask_arg(busy_mask)
+    if stream is None:
+        stream = _current_stream()
+    _check(load().wagma_step_lag(ctx, _ptr(w), _ptr(g), _ptr(m), _ptr(pub), late, busy, lr, mu, it, stream),
+           "wagma_step_lag")
+
+
 def wagma_tensors_create(ctx: int, sizes, w_ptrs, g_ptrs, m_ptrs, pub_ptrs) -> int:
     """sizes: T ints; *_ptrs: P*T device addresses each, entry p*T + k = tensor k of process p."""
     T = len(sizes)
@@ -192,6 +218,25 @@ def wagma_step_tensors(ctx: int, plan: int, stale_mask: Optional[np.ndarray], lr
     if stream is None:
         stream = _current_stream()
     _check(load().wagma_step_tensors(ctx, plan, mask, lr, mu, it, stream), "wagma_step_tensors")
+
+
+def wagma_step_tensors_lag(ctx: int, plan: int, late_mask: Optional[np.ndarray],
+                           busy_mask: Optional[np.ndarray], lr: float, mu: float, it: int,
+                           stream: Optional[int] = None) -> None:
+    keep_late, late = _mask_arg(late_mask)
+    keep_busy, busy = _mask_arg(busy_mask)
+    if stream is None:
+        stream = _current_stream()
+    _check(load().wagma_step_tensors_lag(ctx, plan, late, busy, lr, mu, it, stream), "wagma_step_tensors_lag")
+
+
+def wagma_lag_masks(ctx: int, seed: int, it: int, window: int, tolerance_ms: int, P: int):
+    """Returns (late words, busy words) of iteration ``it``."""
+    late = np.zeros((P + 63) // 64, dtype=np.uint64)
+    busy = np.zeros((P + 63) // 64, dtype=np.uint64)
+    _check(load().wagma_lag_masks(ctx, seed, it, window, tolerance_ms, late.ctypes.data_as(_u64p),
+                                  busy.ctypes.data_as(_u64p)), "wagma_lag_masks")
+    return late, busy
 
 
 def wagma_stale_mask(ctx: int, seed: int, it: int, threshold: int, P: int) -> np.ndarray:
@@ -291,6 +336,9 @@ class Wagma:
     def clock_mask(self, seed: int, it: int, tolerance_ms: int):
         return wagma_clock_mask(self.ctx, seed, it, tolerance_ms, self.P)
 
+    def lag_masks(self, seed: int, it: int, tolerance_ms: int, window: int = 64):
+        return wagma_lag_masks(self.ctx, seed, it, window, tolerance_ms, self.P)
+
     def alloc(self, device="cuda"):
         """Four (P, ld) fp32 device buffers w, g, m, pub (uninitialised)."""
         import torch
@@ -324,11 +372,16 @@ class Wagma:
                                  % (self.P, ld))
 
     def step(self, w, g, m, pub, stale_mask, lr: float, mu: float, it: int,
-             stream: Optional[int] = None) -> None:
+             stream: Optional[int] = None, busy_mask=None) -> None:
+        """busy_mask given: wagma_step_lag (processes still computing an earlier step)."""
         self._validate(w, g, m, pub)
-        if stale_mask is not None and len(stale_mask) != (self.P + 63) // 64:
-            raise ValueError("stale_mask must hold ceil(P/64) words")
-        wagma_step(self.ctx, w, g, m, pub, stale_mask, lr, mu, it, stream)
+        for mask in (stale_mask, busy_mask):
+            if mask is not None and len(mask) != (self.P + 63) // 64:
+                raise ValueError("a mask must hold ceil(P/64) words")
+        if busy_mask is None:
+            wagma_step(self.ctx, w, g, m, pub, stale_mask, lr, mu, it, stream)
+        else:
+            wagma_step_lag(self.ctx, w, g, m, pub, stale_mask, busy_mask, lr, mu, it, stream)
 
     def tensor_plan(self, w, g, m, pub) -> "TensorPlan":
         """w, g, m, pub: for every process a list of T one-dimensional fp32 CUDA tensors
@@ -370,10 +423,15 @@ class TensorPlan:
             tables.append(flat)
         self.plan = wagma_tensors_create(owner.ctx, sizes, *tables)
 
-    def step(self, stale_mask, lr: float, mu: float, it: int, stream: Optional[int] = None) -> None:
-        if stale_mask is not None and len(stale_mask) != (self.owner.P + 63) // 64:
-            raise ValueError("stale_mask must hold ceil(P/64) words")
-        wagma_step_tensors(self.owner.ctx, self.plan, stale_mask, lr, mu, it, stream)
+    def step(self, stale_mask, lr: float, mu: float, it: int, stream: Optional[int] = None,
+             busy_mask=None) -> None:
+        for mask in (stale_mask, busy_mask):
+            if mask is not None and len(mask) != (self.owner.P + 63) // 64:
+                raise ValueError("a mask must hold ceil(P/64) words")
+        if busy_mask is None:
+            wagma_step_tensors(self.owner.ctx, self.plan, stale_mask, lr, mu, it, stream)
+        else:
+            wagma_step_tensors_lag(self.owner.ctx, self.plan, stale_mask, busy_mask, lr, mu, it, stream)
 
     def destroy(self) -> None:
         if self.plan:

@@ -1,0 +1,191 @@
+"""GPU parity of the path for lateness deeper than one iteration (wagma_step_lag,
+wagma_step_tensors_lag, wagma_lag_masks) against the CPU oracle, through the C-ABI.
+
+Bar: masks bit-exact; w, m and pub bit-exact (same order of operations), rows of processes
+that are still computing untouched bit for bit, the gradient never written.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import wagma_oracle as orc
+from paper_2005_00124_amd import wagma as lw
+
+from test_gpu_parity import LR, MU, assert_same_bits, random_state, say
+
+pytestmark = pytest.mark.gpu
+
+
+def words(flags):
+    return orc.mask_words(np.asarray(flags, dtype=bool))
+
+
+def random_masks(rng, P, t):
+    """Late and busy sets of one iteration; every fourth iteration an extreme."""
+    late = rng.random(P) < 0.25
+    busy = rng.random(P) < 0.3
+    if t % 8 == 3:
+        busy[:] = True                 # nobody finishes anything
+    if t % 8 == 7:
+        busy[:] = False
+        late[:] = True
+    return late, busy
+
+
+@pytest.mark.parametrize("P,S,n,tau", [
+    (1, 1, 300, 0), (4, 2, 1000, 5), (8, 1, 515, 0), (16, 4, 70001, 10), (64, 8, 40000, 16),
+    (32, 8, 9999, 8), (64, 16, 5000, 0), (64, 64, 3001, 7), (256, 32, 2049, 6), (1024, 128, 1100, 0),
+])
+def test_step_lag_random_masks(P, S, n, tau):
+    say("lag case P=%d S=%d n=%d tau=%d" % (P, S, n, tau))
+    rng = np.random.default_rng(P * 131 + S)
+    with lw.Wagma(P, S, n, tau) as ctx:
+        ld = ctx.ld
+        w, g, m, pub, gen = random_state(P, ld, n, 99 + P + S)
+        ow, om, opub = (x.cpu().numpy().copy() for x in (w, m, pub))
+        for t in range(10):
+            g.normal_(0.0, 1e-2, generator=gen)
+            og = g.cpu().numpy()
+            late, busy = random_masks(rng, P, t)
+            before = [x.clone() for x in (w, m, pub)]
+            ctx.step(w, g, m, pub, words(late), LR, MU, t, busy_mask=words(busy))
+            orc.step_lag_f32(P, S, tau, t, ow, og, om, opub, late, busy, LR, MU, n=n)
+            torch.cuda.synchronize()
+            for have, want, what in ((w, ow, "w"), (m, om, "m"), (pub, opub, "pub")):
+                assert_same_bits(have.cpu().numpy()[:, :n], want[:, :n], "%s at t=%d" % (what, t))
+            if not ctx.is_global(t):
+                rows = torch.from_numpy(np.nonzero(busy)[0]).cuda()
+                for x, b in zip((w, m, pub), before):
+                    assert torch.equal(x[rows], b[rows]), "a busy process was written at t=%d" % t
+        assert torch.equal(g.cpu(), torch.from_numpy(og)), "g was written"
+
+
+@pytest.mark.parametrize("options", [
+    ((lw.WAGMA_OPT_BLOCK, 256), (lw.WAGMA_OPT_WAVES, 4)),
+    ((lw.WAGMA_OPT_NONTEMPORAL, 0), (lw.WAGMA_OPT_STRIPE_LOG2, 0), (lw.WAGMA_OPT_XCD_CHUNK_LOG2, 0)),
+    ((lw.WAGMA_OPT_FORCE_STREAM, 1), (lw.WAGMA_OPT_WAVES, 3)),
+])
+def test_step_lag_launch_options(options):
+    """The other launch shapes of the same kernels, S = 8 (in registers and streamed)."""
+    P, S, n, tau = 32, 8, 33333, 6
+    say("lag options", options)
+    rng = np.random.default_rng(17)
+    with lw.Wagma(P, S, n, tau) as ctx:
+        for opt, val in options:
+            ctx.set_option(opt, val)
+        w, g, m, pub, gen = random_state(P, ctx.ld, n, 5)
+        ow, om, opub = (x.cpu().numpy().copy() for x in (w, m, pub))
+        for t in range(7):
+            g.normal_(0.0, 1e-2, generator=gen)
+            og = g.cpu().numpy()
+            late, busy = random_masks(rng, P, t)
+            ctx.step(w, g, m, pub, words(late), LR, MU, t, busy_mask=words(busy))
+            orc.step_lag_f32(P, S, tau, t, ow, og, om, opub, late, busy, LR, MU, n=n)
+            torch.cuda.synchronize()
+            for have, want, what in ((w, ow, "w"), (m, om, "m"), (pub, opub, "pub")):
+                assert_same_bits(have.cpu().numpy()[:, :n], want[:, :n], "%s at t=%d" % (what, t))
+
+
+def test_lag_masks_bit_exact():
+    for P, tau in [(1, 0), (4, 5), (16, 10), (64, 16), (32, 8), (1024, 12), (128, 0)]:
+        with lw.Wagma(P, 1, 16, tau) as ctx:
+            for seed in (0, 200500128, 2 ** 64 - 1):
+                for tol in (0, 300, 1699):
+                    for window in (1, 7, 64):
+                        for t in list(range(0, 3 * max(tau, 8))) + [10 ** 6 + 3]:
+                            late, busy = ctx.lag_masks(seed, t, tol, window)
+                            olate, obusy = orc.lag_masks(seed, t, P, tau, window, tol)
+                            assert np.array_equal(late, olate), (P, tau, seed, tol, window, t)
+                            assert np.array_equal(busy, obusy), (P, tau, seed, tol, window, t)
+                        if tau:
+                            break          # the window only matters without a global period
+            with pytest.raises(lw.WagmaError):
+                ctx.lag_masks(1, 0, 1700, 8)
+            if tau == 0:
+                with pytest.raises(lw.WagmaError):
+                    ctx.lag_masks(1, 0, 10, 0)
+    say("lag masks: bit-exact")
+
+
+@pytest.mark.parametrize("P,S,n,tau,iters", [(16, 4, 50000, 10, 30), (64, 8, 20000, 16, 34), (32, 8, 4097, 0, 20)])
+def test_training_run_with_back_to_back_steps(P, S, n, tau, iters):
+    """A run in which the library's own lag masks drive the library and the oracle's own masks
+    drive the oracle; the states must stay equal bit for bit, the fp32 state within
+    1e-6 * max|w| of the fp64 shadow."""
+    say("lag run P=%d S=%d n=%d tau=%d" % (P, S, n, tau))
+    seed, tol, window = 200500124 + P, 250, 9
+    with lw.Wagma(P, S, n, tau) as ctx:
+        w, g, m, pub, gen = random_state(P, ctx.ld, n, seed % 1000)
+        pub.copy_(w)
+        ow, om, opub = (x.cpu().numpy().copy() for x in (w, m, pub))
+        dw, dm, dpub = (x.astype(np.float64) for x in (ow, om, opub))
+        seen_busy = seen_late = 0
+        for t in range(iters):
+            g.normal_(0.0, 1e-2, generator=gen)
+            og = g.cpu().numpy()
+            late, busy = ctx.lag_masks(seed, t, tol, window)
+            olate, obusy = orc.lag_masks(seed, t, P, tau, window, tol)
+            seen_busy += int(sum(bin(int(x)).count("1") for x in busy))
+            seen_late += int(sum(bin(int(x)).count("1") for x in late))
+            ctx.step(w, g, m, pub, late, LR, MU, t, busy_mask=busy)
+            orc.step_lag_f32(P, S, tau, t, ow, og, om, opub, olate, obusy, LR, MU, n=n)
+            orc.step_lag_f64(P, S, tau, t, dw, og.astype(np.float64), dm, dpub, olate, obusy,
+                             float(np.float32(LR)), float(np.float32(MU)), n=n)
+            torch.cuda.synchronize()
+            for have, want, what in ((w, ow, "w"), (m, om, "m"), (pub, opub, "pub")):
+                assert_same_bits(have.cpu().numpy()[:, :n], want[:, :n], "%s at t=%d" % (what, t))
+            assert np.abs(ow[:, :n] - dw[:, :n]).max() <= 1e-6 * np.abs(dw[:, :n]).max()
+        assert seen_busy > 0 and seen_late > 0
+        say("  busy process-iterations %d, late %d of %d" % (seen_busy, seen_late, P * iters))
+
+
+@pytest.mark.parametrize("P,S", [(4, 2), (16, 8), (32, 16)])
+def test_step_tensors_lag(P, S):
+    """Per-tensor layout: ragged tensors between sentinels, late and busy processes."""
+    sizes = [1, 7, 64, 1030, 5, 4096, 333]
+    n = sum(sizes)
+    tau = 4
+    say("lag tensors P=%d S=%d" % (P, S))
+    rng = np.random.default_rng(P + S)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(3 + P)
+    guard = 8
+    SENTINEL = 12345.0
+
+    def make(scale):
+        out = []
+        for _ in range(P):
+            per = []
+            for size in sizes:
+                pad = (size + 3) // 4 * 4
+                buf = torch.full((guard + pad + guard,), SENTINEL, device="cuda")
+                buf[guard:guard + size] = torch.randn(size, generator=gen, device="cuda") * scale
+                per.append(buf)
+            out.append(per)
+        return out
+
+    bufs = {name: make(scale) for name, scale in (("w", 0.05), ("g", 0.01), ("m", 0.01), ("pub", 0.05))}
+    views = {name: [[b[guard:guard + size] for b, size in zip(per, sizes)] for per in arr]
+             for name, arr in bufs.items()}
+
+    def flat(name):
+        return np.stack([np.concatenate([v.cpu().numpy() for v in per]) for per in views[name]])
+
+    ow, og, om, opub = (flat(k).copy() for k in ("w", "g", "m", "pub"))
+    with lw.Wagma(P, S, n, tau) as ctx:
+        plan = ctx.tensor_plan(views["w"], views["g"], views["m"], views["pub"])
+        try:
+            for t in range(6):
+                late, busy = random_masks(rng, P, t + 1)
+                plan.step(words(late), LR, MU, t, busy_mask=words(busy))
+                orc.step_lag_f32(P, S, tau, t, ow, og, om, opub, late, busy, LR, MU)
+                torch.cuda.synchronize()
+                for name, want in (("w", ow), ("m", om), ("pub", opub), ("g", og)):
+                    assert_same_bits(flat(name), want, "%s at t=%d" % (name, t))
+        finally:
+            plan.destroy()
+    for name, arr in bufs.items():
+        for per in arr:
+            for b, size in zip(per, sizes):
+                assert bool((b[:guard] == SENTINEL).all()) and bool((b[guard + size:] == SENTINEL).all()), \
+                    "wrote outside a tensor of %s" % name
