@@ -463,6 +463,44 @@ def test_workload_5_sampled():
     sampled_parity(5, count=20000)
 
 
+def test_longest_row():
+    """n = 2^31 - 1, the last row length but one that wagma_create takes (and a ragged one):
+    float indices inside a row need all 31 bits.  P = 2, S = 2, 69 GB in the four arrays; the
+    oracle follows a column sample that includes both ends of the row."""
+    P, S, tau = 2, 2, 3
+    n = 2 ** 31 - 1
+    say("longest row: n=%d" % n)
+    with pytest.raises(lw.WagmaError):
+        lw.Wagma(P, S, 2 ** 31 + 1, tau)
+    with lw.Wagma(P, S, n, tau) as ctx:
+        assert ctx.ld >= n + 1 and ctx.ld % 4 == 0
+        w, g, m, pub = ctx.alloc()
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(31)
+        w.normal_(0.0, 0.05, generator=gen)
+        m.normal_(0.0, 0.01, generator=gen)
+        pub.normal_(0.0, 0.05, generator=gen)
+        pad0 = (n + 3) // 4 * 4          # a 16-byte slice that holds a column < n is written whole
+        pad = [x[:, pad0:].clone() for x in (w, m, pub)]
+        cols = wk.sample_columns(n, 30000, 31).cuda()
+        ow, om, opub = (np.ascontiguousarray(x[:, cols].cpu().numpy()) for x in (w, m, pub))
+        for t in range(4):
+            g.normal_(0.0, 1e-2, generator=gen)
+            og = np.ascontiguousarray(g[:, cols].cpu().numpy())
+            mask = orc.mask_words(np.array([t == 1, t == 3]))
+            ctx.step(w, g, m, pub, mask, LR, MU, t)
+            orc.step_f32(P, S, tau, t, ow, og, om, opub, mask, LR, MU)
+            torch.cuda.synchronize()
+            for have, want, what in ((w, ow, "w"), (m, om, "m"), (pub, opub, "pub")):
+                assert_same_bits(have[:, cols].cpu().numpy(), want, "%s at t=%d" % (what, t))
+            if ctx.is_global(t):
+                assert torch.equal(w[0, :n], w[1, :n])
+        for x, k in zip((w, m, pub), pad):
+            assert torch.equal(x[:, pad0:], k), "columns beyond the last slice were written"
+        del w, g, m, pub, pad
+    torch.cuda.empty_cache()
+
+
 def test_steps_captured_in_a_hip_graph():
     """wagma_step allocates nothing and never synchronises, so a run of steps can be captured in a
     HIP graph (mask and iteration number are baked in at capture time).  Every replay, with eager
