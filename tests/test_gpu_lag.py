@@ -189,3 +189,54 @@ def test_step_tensors_lag(P, S):
             for b, size in zip(per, sizes):
                 assert bool((b[:guard] == SENTINEL).all()) and bool((b[guard + size:] == SENTINEL).all()), \
                     "wrote outside a tensor of %s" % name
+
+
+def test_seeded_random_configurations():
+    """Forty seeded draws of everything at once: sizes, period, row stride, grouping mode,
+    launch options, late and busy sets; flat layout, bit for bit against the oracle."""
+    rng = np.random.default_rng(20050012)
+    sizes = [1, 2, 4, 8, 16, 32, 64, 128, 256]
+    for case in range(40):
+        P = int(rng.choice(sizes))
+        S = int(rng.choice([s for s in sizes if s <= P]))
+        n = int(rng.integers(1, 30000))
+        tau = int(rng.integers(0, 6))
+        fixed = bool(rng.integers(0, 2))
+        options = []
+        if rng.integers(0, 2):
+            options.append((lw.WAGMA_OPT_BLOCK, int(rng.choice([256, 512]))))
+        if rng.integers(0, 2):
+            options.append((lw.WAGMA_OPT_WAVES, int(rng.choice([2, 3, 4]))))
+        if rng.integers(0, 2):
+            options.append((lw.WAGMA_OPT_NONTEMPORAL, int(rng.integers(0, 2))))
+        if rng.integers(0, 2):
+            options.append((lw.WAGMA_OPT_STRIPE_LOG2, int(rng.integers(0, 5))))
+        if rng.integers(0, 2):
+            options.append((lw.WAGMA_OPT_XCD_CHUNK_LOG2, int(rng.integers(0, 5))))
+        if rng.integers(0, 3) == 0:
+            options.append((lw.WAGMA_OPT_FORCE_STREAM, 1))
+        pad = int(rng.integers(0, 3)) * 4
+        say("random case %d: P=%d S=%d n=%d tau=%d fixed=%s pad=%d options=%s"
+            % (case, P, S, n, tau, fixed, pad, options))
+        with lw.Wagma(P, S, n, tau) as ctx:
+            if pad:
+                ctx.set_row_stride((n + 3) // 4 * 4 + pad)
+            for opt, val in options:
+                ctx.set_option(opt, val)
+            if fixed:
+                ctx.set_grouping(lw.WAGMA_GROUPING_FIXED)
+            w, g, m, pub, gen = random_state(P, ctx.ld, n, 1000 + case)
+            ow, om, opub = (x.cpu().numpy().copy() for x in (w, m, pub))
+            t0 = int(rng.integers(0, 1000))
+            for t in range(t0, t0 + 5):
+                g.normal_(0.0, 1e-2, generator=gen)
+                og = g.cpu().numpy()
+                late = rng.random(P) < 0.3
+                busy = rng.random(P) < 0.3 if rng.integers(0, 3) else None
+                ctx.step(w, g, m, pub, words(late), LR, MU, t,
+                         busy_mask=None if busy is None else words(busy))
+                orc.step_lag_f32(P, S, tau, t, ow, og, om, opub, late, busy, LR, MU, n=n, fixed_groups=fixed)
+                torch.cuda.synchronize()
+                for have, want, what in ((w, ow, "w"), (m, om, "m"), (pub, opub, "pub")):
+                    assert_same_bits(have.cpu().numpy()[:, :n], want[:, :n],
+                                     "%s at t=%d of case %d" % (what, t, case))
