@@ -68,7 +68,8 @@ int wagma_destroy(wagma_ctx* ctx);
  * negative error code.  The caller allocates P*ld floats per buffer. */
 int64_t wagma_row_stride(const wagma_ctx* ctx);
 
-/* Override the row stride (before the first step): ld >= 4*ceil(n/4), ld % 4 == 0. */
+/* Override the row stride (before the first step): ld >= 4*ceil(n/4), ld % 4 == 0.  While arrays
+ * of wagma_alloc_buffers exist, a stride above the one they were sized for is WAGMA_EINVAL. */
 int wagma_set_row_stride(wagma_ctx* ctx, int64_t ld);
 
 /*
@@ -286,7 +287,9 @@ int wagma_placement_info(const wagma_ctx* ctx, int* mode, int* candidates, int* 
 #define WAGMA_OPT_STRIPE_LOG2 7  /* 0..16: the wavefronts of a workgroup work 2^v KiB apart in
                                     every row (0 = one contiguous tile per workgroup)      */
 #define WAGMA_OPT_XCD_CHUNK_LOG2 8 /* 0..13: each XCD works on runs of 2^v consecutive column
-                                    tiles of a row instead of every 8th tile                */
+                                    tiles of a row instead of every 8th tile; a per-tensor plan
+                                    takes the value at wagma_tensors_create (its tiles are
+                                    half as long: runs of 2^(v+1), at most 256, tiles)     */
 #define WAGMA_OPT_PLACEMENT 9    /* how wagma_alloc_buffers places the arrays: WAGMA_PLACE_*  */
 #define WAGMA_PLACE_PLAIN 0      /* four ordinary allocations                                  */
 #define WAGMA_PLACE_ARRAYS 1     /* whole arrays in different HBM regions                      */

@@ -403,6 +403,7 @@ struct wagma_ctx {
     int32_t* h_table;  // host mirror
     int opt_block, opt_nontemporal, opt_force_stream, opt_swizzle, opt_tile_major, opt_waves, opt_stripe_log2, opt_xcd_chunk_log2;
     float* placed[4];        // w, g, m, pub handed out by wagma_alloc_buffers (or all NULL)
+    int64_t placed_ld;       // the row stride those arrays were sized for
     VmmArrays* vmm;          // not NULL: the four arrays are chunk-mapped, not hipMalloc'ed
     int opt_placement;       // WAGMA_PLACE_*
     int place_mode;          // the WAGMA_PLACE_* that the last wagma_alloc_buffers ended with
@@ -836,6 +837,7 @@ int wagma_create(wagma_ctx** out, int P, int S, int64_t n, int tau)
     ctx->h_table = nullptr;
     for (int k = 0; k < 4; ++k)
         ctx->placed[k] = nullptr;
+    ctx->placed_ld = 0;
     ctx->vmm = nullptr;
     ctx->opt_placement = WAGMA_PLACE_AUTO;
     ctx->place_mode = WAGMA_PLACE_PLAIN;
@@ -904,6 +906,8 @@ int wagma_set_row_stride(wagma_ctx* ctx, int64_t ld)
 {
     if (!ctx || ld % 4 != 0 || ld < (ctx->n + 3) / 4 * 4 || ld > 2 * kMaxN)
         return WAGMA_EINVAL;
+    if (ctx->placed[0] && ld > ctx->placed_ld)
+        return WAGMA_EINVAL;  // rows would reach beyond the arrays of wagma_alloc_buffers
     ctx->ld = ld;
     return WAGMA_OK;
 }
@@ -972,6 +976,12 @@ int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64
         total += sizes[k];
         tiles += ((sizes[k] + 3) / 4 + kTensorBlock - 1) / kTensorBlock;
     }
+    // Workgroup b of a launch runs on XCD b mod 8.  As in the flat layout, each XCD gets runs of
+    // consecutive tiles (here of 4 KiB per row, so twice as many as there for the same run
+    // length): the table is padded with empty tiles to whole rounds of 8 runs and permuted below.
+    const int run_log2 = ctx->opt_xcd_chunk_log2 > 0 ? (ctx->opt_xcd_chunk_log2 < 7 ? ctx->opt_xcd_chunk_log2 + 1 : 8) : 0;
+    const int64_t round_tiles = int64_t(kNumXcd) << run_log2;
+    tiles = (tiles + round_tiles - 1) / round_tiles * round_tiles;
     if (total != ctx->n || tiles * (int64_t)ctx->P > 0x7fffffff)
         return WAGMA_EINVAL;
     const size_t slots = (size_t)ctx->P * (size_t)T;
@@ -1007,13 +1017,32 @@ int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64
     std::memcpy(host + 3 * table_bytes, pub, slots * sizeof(void*));
     std::memcpy(host + 4 * table_bytes, sizes, (size_t)T * sizeof(int64_t));
     TileRef* refs = (TileRef*)(host + 4 * table_bytes + sizes_bytes);
-    int64_t at = 0;
-    for (int k = 0; k < T; ++k) {
-        const int64_t slices = (sizes[k] + 3) / 4;
-        for (int64_t first = 0; first < slices; first += kTensorBlock) {
-            refs[at].tensor = k;
-            refs[at].first_slice = first;
-            ++at;
+    {
+        // slot i of the table (the tile of workgroups i, i + tiles, ...) holds tile number
+        // `linear` of the walk through the tensors: the XCD number i mod 8 moves from bits [0,3)
+        // of the tile number up to bits [run_log2, run_log2 + 3)
+        std::vector<TileRef> in_order;
+        try {
+            in_order.reserve((size_t)tiles);
+        } catch (const std::bad_alloc&) {
+            std::free(host);
+            delete plan;
+            return WAGMA_ENOMEM;
+        }
+        for (int k = 0; k < T; ++k) {
+            const int64_t slices = (sizes[k] + 3) / 4;
+            for (int64_t first = 0; first < slices; first += kTensorBlock)
+                in_order.push_back(TileRef{k, 0, first});
+        }
+        // an empty tile: its first slice lies beyond tensor 0, so every lane of it returns at once
+        const int64_t beyond = ((sizes[0] + 3) / 4 + kTensorBlock - 1) / kTensorBlock * kTensorBlock;
+        while ((int64_t)in_order.size() < tiles)
+            in_order.push_back(TileRef{0, 0, beyond});
+        for (int64_t i = 0; i < tiles; ++i) {
+            const int64_t xcd = i & (kNumXcd - 1), hi = i >> 3;
+            const int64_t linear =
+                ((hi >> run_log2) << (run_log2 + 3)) | (xcd << run_log2) | (hi & ((int64_t(1) << run_log2) - 1));
+            refs[i] = in_order[(size_t)linear];
         }
     }
     char* dev = nullptr;
@@ -1355,6 +1384,7 @@ int wagma_alloc_buffers(wagma_ctx* ctx, float** w, float** g, float** m, float**
     ctx->place_g_with_w = best.g_with_w;
     ctx->place_same_gbs = best.slow_gbs;
     ctx->place_split_gbs = best.fast_gbs;
+    ctx->placed_ld = ctx->ld;
     ctx->placed[0] = *w = best.ptr[0];
     ctx->placed[1] = *g = best.ptr[1];
     ctx->placed[2] = *m = best.ptr[2];

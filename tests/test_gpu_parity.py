@@ -314,6 +314,9 @@ def test_library_allocator_small_arrays():
         assert len({x.data_ptr() for x in (w, g, m, pub)}) == 4
         with pytest.raises(lw.WagmaError):
             ctx.alloc_placed()                       # one set per context
+        with pytest.raises(lw.WagmaError):
+            ctx.set_row_stride(ctx.ld + 4)           # rows would leave the arrays
+        ctx.set_row_stride(ctx.ld)
         gen = torch.Generator(device="cuda")
         gen.manual_seed(3)
         for x in (w, m, pub):
