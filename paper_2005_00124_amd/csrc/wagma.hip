@@ -28,13 +28,12 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
-#include <functional>
 #include <new>
-#include <queue>
 #include <vector>
 
 #include "wagma.h"
 #include "wagma_kernels.h"
+#include "wagma_masks.h"
 #include "wagma_placement.h"
 #include "wagma_chunks.h"
 
@@ -929,7 +928,7 @@ int wagma_is_global_iteration(const wagma_ctx* ctx, int64_t iter)
 {
     if (!ctx || iter < 0 || iter == INT64_MAX)
         return WAGMA_EINVAL;
-    return (ctx->tau > 0 && (iter + 1) % ctx->tau == 0) ? 1 : 0;
+    return wagma_masks::is_global_iteration(ctx->tau, iter) ? 1 : 0;
 }
 
 int wagma_group_schedule(const wagma_ctx* ctx, int64_t iter, const int32_t** dev_table,
@@ -1134,31 +1133,12 @@ int wagma_step_tensors_lag(wagma_ctx* ctx, const wagma_tensors* plan, const uint
     return WAGMA_OK;
 }
 
-// 64-bit finaliser of the public splitmix64 generator (Steele, Lea, Flood 2014).
-static uint64_t mix64(uint64_t z)
-{
-    z = (z ^ (z >> 30)) * UINT64_C(0xBF58476D1CE4E5B9);
-    z = (z ^ (z >> 27)) * UINT64_C(0x94D049BB133111EB);
-    return z ^ (z >> 31);
-}
-
 int wagma_stale_mask(const wagma_ctx* ctx, uint64_t seed, int64_t iter, uint32_t threshold,
                      uint64_t* mask_words)
 {
     if (!ctx || iter < 0 || !mask_words)
         return WAGMA_EINVAL;
-    const int words = (ctx->P + 63) / 64;
-    const uint64_t iter_key = mix64(seed + ((uint64_t)iter + 1) * UINT64_C(0x9E3779B97F4A7C15));
-    for (int k = 0; k < words; ++k) {
-        uint64_t word = 0;
-        for (int b = 0; b < 64 && k * 64 + b < ctx->P; ++b) {
-            const uint64_t rank = (uint64_t)(k * 64 + b);
-            const uint64_t h = mix64(iter_key + (rank + 1) * UINT64_C(0xD1B54A32D192ED03));
-            if ((uint32_t)(h >> 32) < threshold)
-                word |= UINT64_C(1) << b;
-        }
-        mask_words[k] = word;
-    }
+    wagma_masks::bernoulli(ctx->P, seed, iter, threshold, mask_words);
     return WAGMA_OK;
 }
 
@@ -1167,39 +1147,8 @@ int wagma_straggler_mask(const wagma_ctx* ctx, uint64_t seed, int64_t iter, int 
 {
     if (!ctx || iter < 0 || count < 0 || count > ctx->P || !mask_words)
         return WAGMA_EINVAL;
-    const int words = (ctx->P + 63) / 64;
-    for (int k = 0; k < words; ++k)
-        mask_words[k] = 0;
-    // the key differs from that of wagma_stale_mask by a tag, so the two models are independent
-    const uint64_t iter_key =
-        mix64((seed ^ UINT64_C(0x5354524147474C52)) + ((uint64_t)iter + 1) * UINT64_C(0x9E3779B97F4A7C15));
-    int picked = 0;
-    for (uint64_t draw = 1; picked < count; ++draw) {
-        const uint64_t h = mix64(iter_key + draw * UINT64_C(0xD1B54A32D192ED03));
-        const int rank = ctx->G == 0 ? 0 : (int)(h >> (64 - ctx->G));
-        const uint64_t bit = UINT64_C(1) << (rank & 63);
-        if (mask_words[rank >> 6] & bit)
-            continue;  // already selected: draw again
-        mask_words[rank >> 6] |= bit;
-        ++picked;
-    }
+    wagma_masks::stragglers(ctx->P, ctx->G, seed, iter, count, mask_words);
     return WAGMA_OK;
-}
-
-// The step times, in ms, that the P processes draw in iteration iter: nine in sixteen take
-// 1.7 s to 2 s, the others one of 16 geometric steps from 2 s to 43.5 s (the range and the
-// median of the reinforcement-learning workload of Section 6.4).
-static void clock_step_times(uint64_t seed, int64_t iter, int P, uint32_t* ms)
-{
-    static const uint32_t kTailMs[16] = {2000, 2456, 3016, 3703, 4548, 5585, 6858, 8422,
-                                         10342, 12700, 15595, 19151, 23517, 28879, 35463, 43500};
-    const uint64_t iter_key =
-        mix64((seed ^ UINT64_C(0x434C4F434B4D534B)) + ((uint64_t)iter + 1) * UINT64_C(0x9E3779B97F4A7C15));
-    for (int rank = 0; rank < P; ++rank) {
-        const uint64_t h = mix64(iter_key + ((uint64_t)rank + 1) * UINT64_C(0xD1B54A32D192ED03));
-        const bool in_tail = (h >> 60) >= 9;  // seven steps in sixteen
-        ms[rank] = in_tail ? kTailMs[(h >> 56) & 15] : 1700u + (uint32_t)((h >> 32) & 0xFF) * 300u / 256u;
-    }
 }
 
 int wagma_clock_mask(const wagma_ctx* ctx, uint64_t seed, int64_t iter, uint32_t tolerance_ms,
@@ -1207,20 +1156,10 @@ int wagma_clock_mask(const wagma_ctx* ctx, uint64_t seed, int64_t iter, uint32_t
 {
     if (!ctx || iter < 0 || !mask_words)
         return WAGMA_EINVAL;
-    uint32_t ms[WAGMA_MAX_P];
-    clock_step_times(seed, iter, ctx->P, ms);
-    uint32_t first_done = UINT32_MAX;
-    for (int rank = 0; rank < ctx->P; ++rank)
-        if (ms[rank] < first_done)
-            first_done = ms[rank];
-    const int words = (ctx->P + 63) / 64;
-    for (int k = 0; k < words; ++k)
-        mask_words[k] = 0;
-    for (int rank = 0; rank < ctx->P; ++rank) {
-        if ((uint64_t)ms[rank] > (uint64_t)first_done + tolerance_ms)
-            mask_words[rank >> 6] |= UINT64_C(1) << (rank & 63);
-        if (step_ms)
-            step_ms[rank] = ms[rank];
+    try {
+        wagma_masks::clock(ctx->P, seed, iter, tolerance_ms, mask_words, step_ms);
+    } catch (const std::bad_alloc&) {
+        return WAGMA_ENOMEM;
     }
     return WAGMA_OK;
 }
@@ -1228,88 +1167,13 @@ int wagma_clock_mask(const wagma_ctx* ctx, uint64_t seed, int64_t iter, uint32_t
 int wagma_lag_masks(const wagma_ctx* ctx, uint64_t seed, int64_t iter, int window, uint32_t tolerance_ms,
                     uint64_t* late_words, uint64_t* busy_words)
 {
-    if (!ctx || iter < 0 || !late_words || !busy_words || tolerance_ms >= 1700u ||
+    if (!ctx || iter < 0 || !late_words || !busy_words || tolerance_ms >= wagma_masks::kShortestStepMs ||
         (ctx->tau == 0 && window < 1))
         return WAGMA_EINVAL;
-    const int P = ctx->P;
-    const int words = (P + 63) / 64;
-    for (int k = 0; k < words; ++k)
-        late_words[k] = busy_words[k] = 0;
-    if (wagma_is_global_iteration(ctx, iter) == 1)
-        return WAGMA_OK;  // everybody waits for the global average
-    // The clocks start together after every global iteration (every `window` iterations when
-    // there is none) and run until the group allreduce after this iteration's has read.
-    const int64_t length = ctx->tau > 0 ? ctx->tau : window;
-    const int64_t first_iter = iter / length * length;
-    const int64_t target = iter - first_iter;  // allreduce number inside the window
-
-    // Time-ordered events.  A step's end is seen by a read that happens at the same time.
-    struct Event {
-        int64_t at;
-        int is_read;    // 0: a process ends a step, 1: the running allreduce reads the models
-        int rank;
-        int64_t begun;  // the allreduce the step was begun for
-        bool operator>(const Event& o) const
-        {
-            if (at != o.at)
-                return at > o.at;
-            if (is_read != o.is_read)
-                return is_read > o.is_read;
-            return rank > o.rank;
-        }
-    };
-    std::priority_queue<Event, std::vector<Event>, std::greater<Event>> events;
-    std::vector<int> waiting;                    // arrived at the running allreduce, not yet read
-    uint8_t went_on[WAGMA_MAX_P] = {0};          // ended a step since the target allreduce read
     try {
-        // times[k & 1]: the step times drawn for steps begun for allreduce k
-        std::vector<uint32_t> times[2] = {std::vector<uint32_t>((size_t)P), std::vector<uint32_t>((size_t)P)};
-        clock_step_times(seed, first_iter, P, times[0].data());
-        clock_step_times(seed, first_iter + 1, P, times[1].data());
-        for (int rank = 0; rank < P; ++rank)
-            events.push(Event{(int64_t)times[0][(size_t)rank], 0, rank, 0});
-        int64_t running = 0;  // the allreduce that will read next
-        while (true) {
-            const Event ev = events.top();
-            events.pop();
-            if (ev.is_read && running == target + 1)
-                break;  // whoever ended a step since the target read was late in it
-            if (ev.is_read) {
-                // those who arrived in time take the average and go on together
-                for (int rank : waiting)
-                    events.push(Event{ev.at + (int64_t)times[(running + 1) & 1][(size_t)rank], 0, rank, running + 1});
-                if (running == target) {
-                    // everybody else contributes a send buffer; who also ends a step before
-                    // the next read is late, the rest is still computing
-                    for (int rank = 0; rank < P; ++rank)
-                        busy_words[rank >> 6] |= UINT64_C(1) << (rank & 63);
-                    for (int rank : waiting)
-                        busy_words[rank >> 6] &= ~(UINT64_C(1) << (rank & 63));
-                }
-                waiting.clear();
-                ++running;
-                clock_step_times(seed, first_iter + running + 1, P, times[(running + 1) & 1].data());
-            } else if (ev.begun == running) {
-                if (waiting.empty())  // the activator
-                    events.push(Event{ev.at + (int64_t)tolerance_ms, 1, -1, running});
-                waiting.push_back(ev.rank);
-            } else {
-                // the allreduce this step was begun for has read already: the process averages
-                // the sum it finds with its W' and begins the next step at once
-                events.push(Event{ev.at + (int64_t)times[running & 1][(size_t)ev.rank], 0, ev.rank, running});
-                if (running == target + 1)
-                    went_on[ev.rank] = 1;
-            }
-        }
+        wagma_masks::lag(ctx->P, ctx->tau, window, seed, iter, tolerance_ms, late_words, busy_words);
     } catch (const std::bad_alloc&) {
         return WAGMA_ENOMEM;
-    }
-    for (int rank = 0; rank < P; ++rank) {
-        const uint64_t bit = UINT64_C(1) << (rank & 63);
-        if (went_on[rank] && (busy_words[rank >> 6] & bit)) {
-            busy_words[rank >> 6] &= ~bit;
-            late_words[rank >> 6] |= bit;
-        }
     }
     return WAGMA_OK;
 }
