@@ -39,7 +39,7 @@ extern "C" {
 #define WAGMA_EINVAL (-1) /* bad argument: P or S not a power of two, S > P, n < 1,
                              tau < 0, NULL or misaligned pointer, negative iter, ... */
 #define WAGMA_EHIP (-2)   /* a HIP runtime call failed; see wagma_last_hip_error() */
-#define WAGMA_ENOMEM (-3) /* host or device allocation failed in wagma_create */
+#define WAGMA_ENOMEM (-3) /* a host or device allocation failed */
 
 #define WAGMA_MAX_P 1024 /* largest supported number of processes */
 
