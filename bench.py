@@ -19,9 +19,11 @@ import time
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 
 # HBM bytes per launch of the dominant kernel from two `rocprofv3 --pmc` runs (FETCH_SIZE scaled by
-# 2.000, WRITE_SIZE by 1.000, the factors a plain copy of known size gave in the same runs); valid
-# for the default launch options only.  Source: profiles/group_step_S8__resnet50-25.6M_P64_S8.md
-MEASURED_TRAFFIC_BYTES = {4: 40.94e9}
+# 2.000, WRITE_SIZE by 1.000, the factors a plain copy of known size gave in the same runs), averaged
+# over the group launches of `bench.py --steps 20` (10 for workload 5); valid for the default launch
+# options only.  Source: the files under profiles/ for these kernels and workloads.
+MEASURED_TRAFFIC_BYTES = {2: 10.116e9, 3: 24.016e9, 4: 40.94e9, 5: 166.41e9}
+MEASURED_TRAFFIC_BYTES_PER_TENSOR = {4: 40.94e9}
 
 OPTS = {"block": 1, "nontemporal": 2, "force_stream": 3, "xcd_swizzle": 4, "tile_major": 5, "waves": 6,
         "stripe_log2": 7, "xcd_chunk_log2": 8, "placement": 9}
@@ -219,8 +221,8 @@ def main() -> int:
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                 "avg_launch_ms": dom_ms / len(dom_ts), "launches": len(dom_ts),
                 "algorithmic_bytes_per_launch": sum(bytes_of[t] for t in dom_ts) / len(dom_ts),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(wl.index)
-                if grp and not args.opt and not args.ld and plan is None and args.lag is None else None}
+                "traffic": (MEASURED_TRAFFIC_BYTES if plan is None else MEASURED_TRAFFIC_BYTES_PER_TENSOR).get(wl.index)
+                if grp and not args.opt and not args.ld and args.lag is None else None}
     out = {
         "metric": "replica-params averaged/sec", "value": P * n * K / wall, "unit": "replica-params/s",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": wall * 1e3 / K,
