@@ -98,3 +98,22 @@ def test_device_code_has_no_packed_fp32_instructions(tmp_path):
     text = asm.read_text()
     assert "step_rows_in_registers" in text and "global_load_dwordx4" in text
     assert not re.search(r"\bv_pk_(add|mul|fma)_f32\b", text)
+
+
+def test_header_is_plain_c_and_links_against_the_library(lib, tmp_path):
+    """include/wagma.h compiles as strict C99 (no C++ or HIP in the boundary), and a C program
+    that names every entry point links against libwagma.so (built here, not run: no GPU)."""
+    import subprocess
+    names = declared_symbols()
+    src = tmp_path / "uses_wagma.c"
+    src.write_text('#include "wagma.h"\n#include <stddef.h>\n'
+                   "typedef void (*fn)(void);\n"
+                   "fn table[] = {\n" + "".join("    (fn)%s,\n" % n for n in names) + "};\n"
+                   "int main(void) { return table[0] == NULL; }\n")
+    exe = tmp_path / "uses_wagma"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-Wno-cast-function-type",
+                    "-I", os.path.join(ROOT, "include"), "-o", str(exe), str(src),
+                    "-L", os.path.dirname(libwagma.LIB_PATH), "-lwagma",
+                    "-Wl,--allow-shlib-undefined"], check=True, timeout=120)
+    subprocess.run(["gcc", "-std=c99", "-pedantic-errors", "-Wall", "-Wextra", "-Werror", "-fsyntax-only",
+                    "-x", "c", os.path.join(ROOT, "include", "wagma.h")], check=True, timeout=120)
