@@ -239,6 +239,8 @@ def main() -> int:
                    "launch": "one HIP graph of K steps" if args.graph else "one launch per step"},
         "hbm_gbs_all_steps": sum(bytes_of) / ((grp_ms + glb_ms) * 1e-3) / 1e9,
         "group_step_ms": (grp_ms / len(grp)) if grp else None,
+        "group_step_ms_median": float(np.median([ms[t] for t in grp])) if grp else None,
+        "group_step_ms_min": min(ms[t] for t in grp) if grp else None,
         "global_step_ms": (glb_ms / len(glb)) if glb else None,
         "global_step_gbs": (sum(bytes_of[t] for t in glb) / (glb_ms * 1e-3) / 1e9) if glb else None,
         "roofline": roofline,

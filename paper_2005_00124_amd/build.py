@@ -7,7 +7,10 @@ import sys
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
-SRC = os.path.join(PKG, "csrc", "wagma.hip")   # includes wagma_kernels.h and wagma_placement.h
+# wagma.hip: the step (kernels in wagma_kernels.h, lateness generators in wagma_masks.h);
+# wagma_alloc.hip: the optional allocator (searches in wagma_placement.h and wagma_chunks.h)
+SOURCES = [os.path.join(PKG, "csrc", "wagma.hip"), os.path.join(PKG, "csrc", "wagma_alloc.hip")]
+SRC = SOURCES[0]
 LIB = os.path.join(PKG, "libwagma.so")
 
 # IEEE fp32 throughout: no contraction (the two fused multiply-adds are explicit), no
@@ -31,9 +34,9 @@ def hipcc() -> str:
 
 
 def build(verbose: bool = False) -> str:
-    """Compile csrc/wagma.hip into paper_2005_00124_amd/libwagma.so; returns the path."""
+    """Compile csrc/*.hip into paper_2005_00124_amd/libwagma.so; returns the path."""
     tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [hipcc(), *HIPCC_FLAGS, "-o", tmp, SRC]
+    cmd = [hipcc(), *HIPCC_FLAGS, "-o", tmp, *SOURCES]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

@@ -91,12 +91,14 @@ def test_device_code_has_no_packed_fp32_instructions(tmp_path):
     assembly of our own source must hold none of v_pk_add/mul/fma_f32."""
     import subprocess
     from paper_2005_00124_amd import build
-    asm = tmp_path / "wagma_device.s"
     flags = [f for f in build.HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
-    subprocess.run([build.hipcc(), *flags, "--cuda-device-only", "-S", "-o", str(asm), build.SRC],
-                   check=True, capture_output=True)
-    text = asm.read_text()
-    assert "step_rows_in_registers" in text and "global_load_dwordx4" in text
+    text = ""
+    for k, source in enumerate(build.SOURCES):
+        asm = tmp_path / ("unit%d.s" % k)
+        subprocess.run([build.hipcc(), *flags, "--cuda-device-only", "-S", "-o", str(asm), source],
+                       check=True, capture_output=True, timeout=600)
+        text += asm.read_text()
+    assert "step_rows_in_registers" in text and "placement_probe" in text and "global_load_dwordx4" in text
     assert not re.search(r"\bv_pk_(add|mul|fma)_f32\b", text)
 
 
