@@ -50,6 +50,15 @@
  *     buffer is overwritten by a later one before it looks.  A global
  *     iteration waits for everybody, so nobody is late or absent in it.
  *
+ * Parity unpinned: where the paper is silent the reading above is a choice; the
+ * pins fix the arithmetic of the choice (hand values, brute force), nothing in
+ * the paper fixes the choice itself.  These are: what the send buffer holds
+ * after a global iteration and before the first iteration (the caller sets
+ * it); what a process that is still computing does in an iteration
+ * (oracle_step_lag_*) and the clock model that says who is in time, late or
+ * still computing (oracle_lag_states, oracle_lag_masks); and the three seeded
+ * lateness generators, which stand in for physical lateness.
+ *
  * Build: gcc -O2 -ffp-contract=off -fno-fast-math -shared -fPIC ... -lm
  * (no contraction, no fast-math, no flush-to-zero: IEEE fp32 throughout).
  */
