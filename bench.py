@@ -71,6 +71,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", type=int, default=4, help="1..5; 4 = the headline P=64 S=8 25.6M")
+    ap.add_argument("--P", type=int, default=None, help="override the workload's number of replicas")
+    ap.add_argument("--S", type=int, default=None, help="override the workload's group size")
+    ap.add_argument("--tau", type=int, default=None, help="override the workload's global period")
     ap.add_argument("--opt", action="append", default=[], help="tuning knob NAME=VALUE (%s)" % ", ".join(OPTS))
     ap.add_argument("--ld", type=int, default=None, help="row stride override (floats)")
     ap.add_argument("--plain-alloc", action="store_true",
@@ -104,6 +107,11 @@ def main() -> int:
         build.build()
 
     wl = wk.workload(args.workload)
+    custom = {k: v for k, v in (("P", args.P), ("S", args.S), ("tau", args.tau)) if v is not None}
+    if custom:
+        import dataclasses
+        wl = dataclasses.replace(wl, **custom)
+        wl = dataclasses.replace(wl, name="%s with %s" % (wl.name, ", ".join("%s=%d" % kv for kv in custom.items())))
     K = wl.iters if args.steps is None else args.steps
     W = args.warmup
     P, S, n = wl.P, wl.S, wl.n
@@ -222,7 +230,7 @@ def main() -> int:
                 "avg_launch_ms": dom_ms / len(dom_ts), "launches": len(dom_ts),
                 "algorithmic_bytes_per_launch": sum(bytes_of[t] for t in dom_ts) / len(dom_ts),
                 "traffic": (MEASURED_TRAFFIC_BYTES if plan is None else MEASURED_TRAFFIC_BYTES_PER_TENSOR).get(wl.index)
-                if grp and not args.opt and not args.ld and args.lag is None else None}
+                if grp and not args.opt and not args.ld and args.lag is None and not custom else None}
     out = {
         "metric": "replica-params averaged/sec", "value": P * n * K / wall, "unit": "replica-params/s",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": wall * 1e3 / K,

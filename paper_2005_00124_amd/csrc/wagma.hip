@@ -223,8 +223,8 @@ int step_flat(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub, co
     p.swizzle = ctx->opt_swizzle;
     p.tile_major = ctx->opt_tile_major;
 
-    const bool streamed = p.members > kChunk || (ctx->opt_force_stream && p.members == kChunk);
-    p.log2_chunks = streamed ? exact_log2(p.members / kChunk) : 0;
+    const bool streamed = p.members > kRegisterRows || (ctx->opt_force_stream && p.members == kRegisterRows);
+    p.log2_chunks = streamed ? exact_log2(p.members / streamed_chunk(lag)) : 0;
     const int block = ctx->opt_block;
     p.stripe_log2 = ctx->opt_stripe_log2;
     // whole stripes: tiles is a multiple of 2^stripe_log2 (the surplus lanes find col >= nvec)
@@ -586,7 +586,7 @@ int wagma_step_tensors_lag(wagma_ctx* ctx, const wagma_tensors* plan, const uint
     p.num_tensors = plan->T;
     p.tiles = plan->tiles;
     p.blocks = (int64_t)(ctx->P / p.members) * p.tiles;
-    p.log2_chunks = p.members > kChunk ? exact_log2(p.members / kChunk) : 0;
+    p.log2_chunks = p.members > kRegisterRows ? exact_log2(p.members / streamed_chunk(lag)) : 0;
     const hipStream_t on = (hipStream_t)stream;
     if (ctx->opt_nontemporal) {
         if (lag)
