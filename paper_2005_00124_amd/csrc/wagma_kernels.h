@@ -225,8 +225,13 @@ __device__ __forceinline__ void streamed_body(const StepParams& p, const int32_t
         }
 #pragma unroll
         for (int i = 0; i < kChunk; ++i)
-            if (late[i])
-                contrib[i] = load_v<NT, V>(at.pub(rank[i]));
+            if (late[i]) {
+                // An ordinary load: this line is stored to below and read once more in the
+                // second pass.  After a non-temporal load the L2 lets go of it early and that
+                // last read goes out to memory again (measured: the late rows then cost twice
+                // their bytes, and 6 % of the time in the per-tensor layout).
+                contrib[i] = load_v<false, V>(at.pub(rank[i]));
+            }
 #pragma unroll
         for (int i = 0; i < kChunk; ++i) {
             if (busy[i])
