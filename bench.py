@@ -85,6 +85,9 @@ def main() -> int:
     ap.add_argument("--lag", type=int, default=None, metavar="TOLERANCE_MS",
                     help="lateness deeper than one iteration: wagma_lag_masks with this tolerance drive "
                          "wagma_step_lag instead of the workload's Bernoulli mask")
+    ap.add_argument("--all-workloads", action="store_true",
+                    help="afterwards run the other four seeded workloads too (child processes of this "
+                         "script) and attach their throughput and bandwidth as \"workloads\"")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-columns", type=int, default=131072)
     args = ap.parse_args()
@@ -258,6 +261,24 @@ def main() -> int:
     del w, g, m, pub
     ctx.destroy()
     torch.cuda.empty_cache()
+    if args.all_workloads:
+        import subprocess
+        summary = {wl.index: {"workload": wl.name, "value": out["value"], "ms_per_step": out["ms_per_step"],
+                              "group_step_gbs": roofline["achieved"], "frac": roofline["frac"]}}
+        for k in range(1, len(wk.WORKLOADS) + 1):
+            if k == wl.index:
+                continue
+            log("workload %d ..." % k)
+            child = subprocess.run([sys.executable, os.path.abspath(__file__), "--workload", str(k),
+                                    "--no-cpu-baseline", "--warmup", str(W)], capture_output=True, text=True)
+            line = [x for x in child.stdout.splitlines() if x.startswith("{")]
+            if child.returncode != 0 or not line:
+                summary[k] = {"error": child.stderr[-300:]}
+                continue
+            o = json.loads(line[-1])
+            summary[k] = {"workload": o["config"]["workload"], "value": o["value"], "ms_per_step": o["ms_per_step"],
+                          "group_step_gbs": o["roofline"]["achieved"], "frac": o["roofline"]["frac"]}
+        out["workloads"] = {str(k): summary[k] for k in sorted(summary)}
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a slice ...")
         out["cpu_baseline"] = cpu_baseline(wl, args.cpu_columns, min(K, wl.iters))
