@@ -639,8 +639,8 @@ int wagma_clock_mask(const wagma_ctx* ctx, uint64_t seed, int64_t iter, uint32_t
 int wagma_lag_masks(const wagma_ctx* ctx, uint64_t seed, int64_t iter, int window, uint32_t tolerance_ms,
                     uint64_t* late_words, uint64_t* busy_words)
 {
-    if (!ctx || iter < 0 || !late_words || !busy_words || tolerance_ms >= wagma_masks::kShortestStepMs ||
-        (ctx->tau == 0 && window < 1))
+    if (!ctx || iter < 0 || iter > INT64_MAX - 4 || !late_words || !busy_words ||
+        tolerance_ms >= wagma_masks::kShortestStepMs || (ctx->tau == 0 && window < 1))
         return WAGMA_EINVAL;
     try {
         wagma_masks::lag(ctx->P, ctx->tau, window, seed, iter, tolerance_ms, late_words, busy_words);
