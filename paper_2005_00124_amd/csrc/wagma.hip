@@ -16,12 +16,15 @@
 // Two kernels cover all group sizes:
 //   step_rows_in_registers<S>  S <= 8 member rows are held in registers
 //                              (3*S independent 128-bit loads in flight per lane).
-//   step_rows_streamed         any S >= 8: member rows are streamed 8 at a time,
-//                              the partial sums kept on a log2(S/8)-deep pairwise
-//                              stack; late members re-read their own W' from the
-//                              send buffer they just wrote.
+//   step_rows_streamed         any S >= 8: member rows are streamed 8 at a time (4 when
+//                              some processes are still computing), the partial sums
+//                              kept on a pairwise stack; late members re-read their own
+//                              W' from the send buffer they just wrote (an L2 hit).
 // The global average (Algorithm 2 lines 15-16) is the same computation with
-// one group of all P ranks in natural order and nobody late.
+// one group of all P ranks in natural order and nobody late.  The same bodies serve the
+// per-tensor layout (step_tensors_*) through an address functor, and each kernel has a
+// second instantiation (LAG) that also honours the mask of processes still computing.
+// The optional allocator lives in wagma_alloc.hip.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
