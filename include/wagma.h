@@ -276,7 +276,7 @@ int wagma_placement_info(const wagma_ctx* ctx, int* mode, int* candidates, int* 
 
 /* Tuning knobs; the defaults are the measured best on MI355X.  Results do not
  * depend on them (same summation order in every variant). */
-#define WAGMA_OPT_BLOCK 1        /* threads per workgroup: 256 or 512                    */
+#define WAGMA_OPT_BLOCK 1        /* threads per workgroup: 256 (default) or 512          */
 #define WAGMA_OPT_NONTEMPORAL 2  /* 0/1: non-temporal hint on loads and stores (default: 1
                                     unless the four arrays fit in 256 MB together)     */
 #define WAGMA_OPT_FORCE_STREAM 3 /* 0/1: use the row-streaming kernel for every S     */

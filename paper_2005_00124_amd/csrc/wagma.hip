@@ -297,8 +297,10 @@ int wagma_create(wagma_ctx** out, int P, int S, int64_t n, int tau)
     ctx->ld = (n + row_align - 1) / row_align * row_align;
     if ((ctx->ld * 4) % (int64_t(1) << 20) == 0)
         ctx->ld += 5 * row_align;
-    // measured best on MI355X for the P=64, S=8, 25.6M-parameter workload
-    ctx->opt_block = 512;
+    // Measured best on MI355X, options side by side on the same arrays: 256-thread workgroups
+    // (three of them fit a compute unit with the S = 8 kernel's registers, against one of 512
+    // threads) are 0.8-1 % faster than 512-thread ones on workloads 2, 4 and 5, level on 3.
+    ctx->opt_block = 256;
     // Streaming hints help only when the arrays stream from HBM: four arrays that fit in the
     // 256 MB Infinity Cache together run 6 % faster without them (P=4, n=2^20).
     ctx->opt_nontemporal = (size_t)4 * (size_t)P * (size_t)ctx->ld * sizeof(float) > (size_t(256) << 20) ? 1 : 0;

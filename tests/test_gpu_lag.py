@@ -62,6 +62,7 @@ def test_step_lag_random_masks(P, S, n, tau):
 
 @pytest.mark.parametrize("options", [
     ((lw.WAGMA_OPT_BLOCK, 256), (lw.WAGMA_OPT_WAVES, 4)),
+    ((lw.WAGMA_OPT_BLOCK, 512), (lw.WAGMA_OPT_WAVES, 2)),
     ((lw.WAGMA_OPT_NONTEMPORAL, 0), (lw.WAGMA_OPT_STRIPE_LOG2, 0), (lw.WAGMA_OPT_XCD_CHUNK_LOG2, 0)),
     ((lw.WAGMA_OPT_FORCE_STREAM, 1), (lw.WAGMA_OPT_WAVES, 3)),
 ])

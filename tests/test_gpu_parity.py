@@ -170,6 +170,7 @@ def test_step_row_stride_variants():
 
 OPTION_SETS = [
     ((lw.WAGMA_OPT_BLOCK, 512),),
+    ((lw.WAGMA_OPT_BLOCK, 256),),
     ((lw.WAGMA_OPT_NONTEMPORAL, 0),),
     ((lw.WAGMA_OPT_FORCE_STREAM, 1),),
     ((lw.WAGMA_OPT_XCD_SWIZZLE, 1),),
