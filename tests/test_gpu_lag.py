@@ -241,3 +241,67 @@ def test_seeded_random_configurations():
                 for have, want, what in ((w, ow, "w"), (m, om, "m"), (pub, opub, "pub")):
                     assert_same_bits(have.cpu().numpy()[:, :n], want[:, :n],
                                      "%s at t=%d of case %d" % (what, t, case))
+
+
+def test_lag_steps_captured_in_a_hip_graph():
+    """The lag entry points launch only, like wagma_step: a run of flat and per-tensor steps with
+    busy processes, captured once in a HIP graph, must reproduce the eager result on every
+    replay (eager work and synchronisations in between), and the oracle's."""
+    P, S, tau, iters = 16, 4, 5, 9
+    sizes = [5000, 36, 1024, 2051]          # every tensor begins 16-byte aligned, the last one is ragged
+    n = sum(sizes)
+    seed, tol = 7, 300
+    with lw.Wagma(P, S, n, tau) as ctx:
+        w, g, m, pub, gen = random_state(P, ctx.ld, n, 11)
+        g.normal_(0.0, 1e-2, generator=gen)
+        start = [x.clone() for x in (w, m, pub)]
+
+        def views(buf):
+            out = []
+            for p in range(P):
+                at, row = 0, []
+                for size in sizes:
+                    row.append(buf[p, at:at + size])
+                    at += size
+                out.append(row)
+            return out
+        plan = ctx.tensor_plan(views(w), views(g), views(m), views(pub))
+        masks = [ctx.lag_masks(seed, t, tol) for t in range(iters)]
+
+        def run():
+            for t in range(iters):
+                late, busy = masks[t]
+                if t % 2:
+                    plan.step(late, LR, MU, t, busy_mask=busy)
+                else:
+                    ctx.step(w, g, m, pub, late, LR, MU, t, busy_mask=busy)
+        run()
+        torch.cuda.synchronize()
+        want = [x.clone() for x in (w, m, pub)]
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for x, s in zip((w, m, pub), start):
+                x.copy_(s)
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                run()
+        torch.cuda.current_stream().wait_stream(side)
+        for replay in range(4):
+            for x, s in zip((w, m, pub), start):
+                x.copy_(s)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for have, ref, what in zip((w, m, pub), want, "wmp"):
+                assert torch.equal(have, ref), "%s differs on replay %d" % (what, replay)
+            g.add_(0.0)
+            torch.cuda.synchronize()
+        ow, om, opub = (s.cpu().numpy().copy() for s in start)
+        og = g.cpu().numpy()
+        for t in range(iters):
+            late, busy = masks[t]
+            orc.step_lag_f32(P, S, tau, t, ow, og, om, opub, late, busy, LR, MU, n=n)
+        assert_same_bits(w.cpu().numpy()[:, :n], ow[:, :n], "w after the graph")
+        plan.destroy()
