@@ -234,6 +234,9 @@ def main() -> int:
                 "algorithmic_bytes_per_launch": sum(bytes_of[t] for t in dom_ts) / len(dom_ts),
                 "traffic": (MEASURED_TRAFFIC_BYTES if plan is None else MEASURED_TRAFFIC_BYTES_PER_TENSOR).get(wl.index)
                 if grp and not args.opt and not args.ld and args.lag is None and not custom else None}
+    if roofline["traffic"]:
+        # counter-based rate: the measured HBM bytes of such a launch over this run's launch time
+        roofline["traffic_gbs"] = roofline["traffic"] / (roofline["avg_launch_ms"] * 1e-3) / 1e9
     out = {
         "metric": "replica-params averaged/sec", "value": P * n * K / wall, "unit": "replica-params/s",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": wall * 1e3 / K,
