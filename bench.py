@@ -22,7 +22,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 # 2.000, WRITE_SIZE by 1.000, the factors a plain copy of known size gave in the same runs), averaged
 # over the group launches of `bench.py --steps 20` (10 for workload 5); valid for the default launch
 # options only.  Source: the files under profiles/ for these kernels and workloads.
-MEASURED_TRAFFIC_BYTES = {2: 10.116e9, 3: 24.016e9, 4: 40.94e9, 5: 166.41e9}
+MEASURED_TRAFFIC_BYTES = {2: 10.116e9, 3: 24.016e9, 4: 40.92e9, 5: 166.41e9}
 MEASURED_TRAFFIC_BYTES_PER_TENSOR = {4: 40.94e9}
 
 OPTS = {"block": 1, "nontemporal": 2, "force_stream": 3, "xcd_swizzle": 4, "tile_major": 5, "waves": 6,
