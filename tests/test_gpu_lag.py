@@ -305,3 +305,35 @@ def test_lag_steps_captured_in_a_hip_graph():
             orc.step_lag_f32(P, S, tau, t, ow, og, om, opub, late, busy, LR, MU, n=n)
         assert_same_bits(w.cpu().numpy()[:, :n], ow[:, :n], "w after the graph")
         plan.destroy()
+
+
+def test_library_masks_equal_the_stored_ones():
+    """The stored lateness masks of the five workloads (tests/golden/lateness_masks.txt, written
+    from the oracle) against what the library draws."""
+    import os
+    from paper_2005_00124_amd import workloads as wk
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "lateness_masks.txt")
+    ctxs = {wl.index: lw.Wagma(wl.P, wl.S, 16, wl.tau) for wl in wk.WORKLOADS}
+    try:
+        checked = 0
+        for line in open(path):
+            if line.startswith("#") or not line.strip():
+                continue
+            head, values = line.split(":")
+            kind, index, t = head.split()
+            wl, t = wk.workload(int(index)), int(t)
+            ctx = ctxs[wl.index]
+            parts = [np.array([int(x, 16) for x in part.split()], dtype=np.uint64) for part in values.split("|")]
+            if kind == "bernoulli":
+                have = [ctx.stale_mask(wl.seed, t, wl.stale_threshold)]
+            elif kind == "stragglers2":
+                have = [ctx.straggler_mask(wl.seed, t, min(2, wl.P))]
+            else:
+                have = list(ctx.lag_masks(wl.seed, t, 300))
+            for h, want in zip(have, parts):
+                assert np.array_equal(h, want), line
+            checked += 1
+        assert checked == 60
+    finally:
+        for ctx in ctxs.values():
+            ctx.destroy()

@@ -62,3 +62,18 @@ def test_sample_columns_cover_both_ends():
     assert cols[0] == 0 and cols[-1] == 25557031 and len(cols) >= 5000
     assert torch.all(cols[1:] > cols[:-1])
     assert wk.workload(4).stale_threshold == 1 << 30
+
+
+def test_lateness_masks_of_the_workloads_are_frozen():
+    """The masks the five workloads draw in their first iterations equal the stored ones
+    (tests/golden/lateness_masks.txt, written by tests/golden/make_lateness_masks.py from the
+    oracle): a change of a seed, a threshold or a generator shows up here."""
+    import importlib.util
+    import os
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("make_lateness_masks",
+                                                  os.path.join(here, "golden", "make_lateness_masks.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    stored = open(os.path.join(here, "golden", "lateness_masks.txt")).read().split("\n")
+    assert [x for x in stored if x] == list(mod.lines())
