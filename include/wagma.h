@@ -190,6 +190,28 @@ int wagma_step_tensors_lag(wagma_ctx* ctx, const wagma_tensors* plan, const uint
                            const uint64_t* busy_mask, float lr, float mu, int64_t iter, void* stream);
 
 /*
+ * wagma_step for callers that cannot allocate device memory or keep a context: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  The one piece of device
+ * memory the step's kernels use beyond the caller's arrays, the group-schedule table that
+ * wagma_create allocates, lives here in a static device array of WAGMA_STATIC_TABLE_BYTES that
+ * each GPU the library runs on holds until the process ends.  The call writes the table for
+ * (P, S) into that array with a kernel on `stream` and then launches the same step kernel as
+ * wagma_step on `stream`: same arithmetic, same results.  It allocates nothing, copies nothing
+ * and does not synchronise.
+ *   P, S, n, tau   as for wagma_create (P <= WAGMA_MAX_P is what the array holds; beyond it,
+ *                  and for every other bad size, WAGMA_EINVAL before anything is launched).
+ *   ld             row stride in floats (multiple of 4, >= 4*ceil(n/4)), or 0 for the stride
+ *                  wagma_create would choose for this n.
+ *   w, g, m, pub, stale_mask, lr, mu, iter, stream   as for wagma_step, on the current device.
+ * Every call on one GPU shares that GPU's array: calls that may overlap on one GPU (different
+ * streams, or graphs replayed concurrently) race on it unless they use the same P and S.
+ */
+#define WAGMA_STATIC_TABLE_BYTES 45056 /* 11 * WAGMA_MAX_P int32: (log2 P + 1) schedules of P ranks */
+int wagma_step_static(int P, int S, int64_t n, int tau, int64_t ld, float* w, const float* g,
+                      float* m, float* pub, const uint64_t* stale_mask, float lr, float mu,
+                      int64_t iter, void* stream);
+
+/*
  * Seeded lateness model (not from the paper, whose lateness is physical; its
  * simulation delays random ranks, Section 6.2): process p is late in iteration
  * iter iff the upper 32 bits of a 64-bit hash of (seed, iter, p) are below

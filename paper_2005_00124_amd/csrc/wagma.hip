@@ -27,6 +27,7 @@
 // The optional allocator lives in wagma_alloc.hip.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
@@ -80,6 +81,53 @@ int gcd_int(int a, int b)
         b = r;
     }
     return a;
+}
+
+// Everything of a context that needs no memory: the sizes, the row stride, the launch options.
+void set_defaults(wagma_ctx* ctx, int P, int S, int G, int g, int64_t n, int tau)
+{
+    ctx->P = P;
+    ctx->S = S;
+    ctx->G = G;
+    ctx->g = g;
+    ctx->tau = tau;
+    ctx->n = n;
+    ctx->period = (g == 0 || G == 0) ? 1 : G / gcd_int(g, G);
+    // Row stride.  Measured on MI355X: rows on 16 KiB boundaries run about 1% faster than rows
+    // on 256 B boundaries (and rows off a 128 B boundary up to 10% slower); strides that are a
+    // multiple of 1 MiB put all member rows of a group on the same memory channels (20% slower),
+    // so such a stride is skewed by a few row alignments.  Small models keep the padding small.
+    const int64_t row_align = n >= (int64_t(1) << 20) ? 4096 : 64;  // floats
+    ctx->ld = (n + row_align - 1) / row_align * row_align;
+    if ((ctx->ld * 4) % (int64_t(1) << 20) == 0)
+        ctx->ld += 5 * row_align;
+    // Measured best on MI355X, options side by side on the same arrays: 256-thread workgroups
+    // (three of them fit a compute unit with the S = 8 kernel's registers, against one of 512
+    // threads) are 0.8-1 % faster than 512-thread ones on workloads 2, 4 and 5, level on 3.
+    ctx->opt_block = 256;
+    // Streaming hints help only when the arrays stream from HBM: four arrays that fit in the
+    // 256 MB Infinity Cache together run 6 % faster without them (P=4, n=2^20).
+    ctx->opt_nontemporal = (size_t)4 * (size_t)P * (size_t)ctx->ld * sizeof(float) > (size_t(256) << 20) ? 1 : 0;
+    ctx->opt_force_stream = 0;
+    ctx->opt_swizzle = 0;
+    ctx->opt_tile_major = 0;
+    ctx->opt_waves = 2;
+    ctx->opt_stripe_log2 = 2;
+    ctx->opt_xcd_chunk_log2 = 2;
+    ctx->fixed_groups = 0;
+    ctx->d_table = nullptr;
+    ctx->h_table = nullptr;
+    for (int k = 0; k < 4; ++k)
+        ctx->placed[k] = nullptr;
+    ctx->placed_ld = 0;
+    ctx->vmm = nullptr;
+    ctx->opt_placement = WAGMA_PLACE_AUTO;
+    ctx->place_mode = WAGMA_PLACE_PLAIN;
+    ctx->place_candidates = 0;
+    ctx->place_regions = 0;
+    ctx->place_g_with_w = 0;
+    ctx->place_same_gbs = 0.0;
+    ctx->place_split_gbs = 0.0;
 }
 
 // WAVES = resident wavefronts per SIMD the register allocation must allow
@@ -282,48 +330,7 @@ int wagma_create(wagma_ctx** out, int P, int S, int64_t n, int tau)
     wagma_ctx* ctx = new (std::nothrow) wagma_ctx();
     if (!ctx)
         return WAGMA_ENOMEM;
-    ctx->P = P;
-    ctx->S = S;
-    ctx->G = G;
-    ctx->g = g;
-    ctx->tau = tau;
-    ctx->n = n;
-    ctx->period = (g == 0 || G == 0) ? 1 : G / gcd_int(g, G);
-    // Row stride.  Measured on MI355X: rows on 16 KiB boundaries run about 1% faster than rows
-    // on 256 B boundaries (and rows off a 128 B boundary up to 10% slower); strides that are a
-    // multiple of 1 MiB put all member rows of a group on the same memory channels (20% slower),
-    // so such a stride is skewed by a few row alignments.  Small models keep the padding small.
-    const int64_t row_align = n >= (int64_t(1) << 20) ? 4096 : 64;  // floats
-    ctx->ld = (n + row_align - 1) / row_align * row_align;
-    if ((ctx->ld * 4) % (int64_t(1) << 20) == 0)
-        ctx->ld += 5 * row_align;
-    // Measured best on MI355X, options side by side on the same arrays: 256-thread workgroups
-    // (three of them fit a compute unit with the S = 8 kernel's registers, against one of 512
-    // threads) are 0.8-1 % faster than 512-thread ones on workloads 2, 4 and 5, level on 3.
-    ctx->opt_block = 256;
-    // Streaming hints help only when the arrays stream from HBM: four arrays that fit in the
-    // 256 MB Infinity Cache together run 6 % faster without them (P=4, n=2^20).
-    ctx->opt_nontemporal = (size_t)4 * (size_t)P * (size_t)ctx->ld * sizeof(float) > (size_t(256) << 20) ? 1 : 0;
-    ctx->opt_force_stream = 0;
-    ctx->opt_swizzle = 0;
-    ctx->opt_tile_major = 0;
-    ctx->opt_waves = 2;
-    ctx->opt_stripe_log2 = 2;
-    ctx->opt_xcd_chunk_log2 = 2;
-    ctx->fixed_groups = 0;
-    ctx->d_table = nullptr;
-    ctx->h_table = nullptr;
-    for (int k = 0; k < 4; ++k)
-        ctx->placed[k] = nullptr;
-    ctx->placed_ld = 0;
-    ctx->vmm = nullptr;
-    ctx->opt_placement = WAGMA_PLACE_AUTO;
-    ctx->place_mode = WAGMA_PLACE_PLAIN;
-    ctx->place_candidates = 0;
-    ctx->place_regions = 0;
-    ctx->place_g_with_w = 0;
-    ctx->place_same_gbs = 0.0;
-    ctx->place_split_gbs = 0.0;
+    set_defaults(ctx, P, S, G, g, n, tau);
 
     const size_t entries = (size_t)(ctx->period + 1) * (size_t)P;
     hipError_t e = hipGetDevice(&ctx->device);
@@ -435,6 +442,75 @@ int wagma_step_lag(wagma_ctx* ctx, float* w, const float* g, float* m, float* pu
                    void* stream)
 {
     return step_flat(ctx, w, g, m, pub, late_mask, busy_mask, lr, mu, iter, stream, false);
+}
+
+// ---- wagma_step without a context: the schedule table lives in a static device array ------
+
+namespace {
+
+// (period + 1) * P entries with period <= log2 P <= 10 and P <= WAGMA_MAX_P.
+constexpr size_t kStaticTableEntries = (size_t)11 * WAGMA_MAX_P;
+static_assert(kStaticTableEntries * sizeof(int32_t) == WAGMA_STATIC_TABLE_BYTES, "size stated in wagma.h");
+static __device__ __align__(256) int32_t scratch[kStaticTableEntries];
+
+// Device address of `scratch` on each GPU (every GPU holds its own copy of the array); looked up
+// once per device, with that device current.  In host code the array's name is not that address.
+constexpr int kMaxDevices = 64;
+std::atomic<int32_t*> g_static_table[kMaxDevices];
+
+int static_table(int device, int32_t** out)
+{
+    if (device < 0 || device >= kMaxDevices)
+        return WAGMA_EINVAL;
+    int32_t* ptr = g_static_table[device].load(std::memory_order_acquire);
+    if (!ptr) {
+        const hipError_t e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess)
+            return hip_failed(e);
+        if (!ptr)
+            return WAGMA_EHIP;
+        g_static_table[device].store(ptr, std::memory_order_release);
+    }
+    *out = ptr;
+    return WAGMA_OK;
+}
+
+}  // namespace
+
+int wagma_step_static(int P, int S, int64_t n, int tau, int64_t ld, float* w, const float* g, float* m,
+                      float* pub, const uint64_t* stale_mask, float lr, float mu, int64_t iter, void* stream)
+{
+    const int G = exact_log2(P), log2_S = exact_log2(S);
+    if (G < 0 || log2_S < 0 || P > WAGMA_MAX_P || S > P || n < 1 || tau < 0 || n > kMaxN)
+        return WAGMA_EINVAL;
+    wagma_ctx ctx;  // on the stack: nothing of it outlives the call
+    set_defaults(&ctx, P, S, G, log2_S, n, tau);
+    if ((size_t)(ctx.period + 1) * (size_t)P > kStaticTableEntries)
+        return WAGMA_EINVAL;  // cannot happen while P <= WAGMA_MAX_P; the array's size is the limit
+    if (ld != 0) {
+        if (ld % 4 != 0 || ld < (n + 3) / 4 * 4 || ld > 2 * kMaxN)
+            return WAGMA_EINVAL;
+        ctx.ld = ld;
+    }
+    if (iter < 0 || iter == INT64_MAX || !w || !g || !m || !pub)
+        return WAGMA_EINVAL;
+    if ((((uintptr_t)w) | ((uintptr_t)g) | ((uintptr_t)m) | ((uintptr_t)pub)) & 15u)
+        return WAGMA_EINVAL;
+    hipError_t e = hipGetDevice(&ctx.device);
+    if (e != hipSuccess)
+        return hip_failed(e);
+    int rc = static_table(ctx.device, &ctx.d_table);
+    if (rc != WAGMA_OK)
+        return rc;
+    // The table of this (P, S) overwrites whatever the last call on this GPU left there, on the
+    // caller's stream, ahead of the step that reads it.
+    const unsigned entries = (unsigned)((ctx.period + 1) * P), threads = 256;
+    hipLaunchKernelGGL(build_schedule_table, dim3((entries + threads - 1) / threads), dim3(threads), 0,
+                       (hipStream_t)stream, ctx.d_table, P, G, log2_S, ctx.period);
+    e = hipGetLastError();
+    if (e != hipSuccess)
+        return hip_failed(e);
+    return step_flat(&ctx, w, g, m, pub, stale_mask, nullptr, lr, mu, iter, stream, false);
 }
 
 // ---- per-tensor layout ------------------------------------------------------------------

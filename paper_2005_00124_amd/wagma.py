@@ -40,6 +40,9 @@ SYMBOLS = {
     "wagma_step": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                   ctypes.c_void_p, _u64p, ctypes.c_float, ctypes.c_float,
                                   ctypes.c_int64, ctypes.c_void_p]),
+    "wagma_step_static": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int, ctypes.c_int64,
+                                         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                         _u64p, ctypes.c_float, ctypes.c_float, ctypes.c_int64, ctypes.c_void_p]),
     "wagma_tensors_create": (ctypes.c_int, [ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p), ctypes.c_int,
                                             ctypes.POINTER(ctypes.c_int64)] + [ctypes.POINTER(ctypes.c_void_p)] * 4),
     "wagma_tensors_destroy": (ctypes.c_int, [ctypes.c_void_p]),
@@ -174,6 +177,17 @@ def wagma_step(ctx: int, w, g, m, pub, stale_mask: Optional[np.ndarray], lr: flo
         stream = _current_stream()
     _check(load().wagma_step(ctx, _ptr(w), _ptr(g), _ptr(m), _ptr(pub), mask, lr, mu, it, stream),
            "wagma_step")
+
+
+def wagma_step_static(P: int, S: int, n: int, tau: int, ld: int, w, g, m, pub,
+                      stale_mask: Optional[np.ndarray], lr: float, mu: float, it: int,
+                      stream: Optional[int] = None) -> None:
+    """wagma_step without a context and without any allocation (static schedule table)."""
+    keep, mask = _mask_arg(stale_mask)
+    if stream is None:
+        stream = _current_stream()
+    _check(load().wagma_step_static(P, S, n, tau, ld, _ptr(w), _ptr(g), _ptr(m), _ptr(pub), mask, lr, mu,
+                                    it, stream), "wagma_step_static")
 
 
 def _mask_arg(mask: Optional[np.ndarray]):
