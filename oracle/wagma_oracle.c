@@ -14,7 +14,8 @@
  *                                 text after Algorithm 1) turned into an
  *                                 ordered member list per group.
  *   - oracle_step_f32 / _f64    : Algorithm 2 lines 6-17 for one iteration t
- *                                 on P model replicas held as P rows.
+ *                                 on P model replicas held as P rows, as
+ *                                 printed (functions of their own).
  *   - oracle_step_lag_f32/_f64  : the same iteration when some processes are
  *                                 still computing an earlier step and take
  *                                 part only through their send buffer
@@ -91,44 +92,38 @@ static int uf_find(int32_t *parent, int p)
 }
 
 /*
- * Algorithm 1, taken literally: every process starts as its own group; for
- * each of the log2(S) phases, every pair p == p XOR mask is an equivalence
- * and the two groups holding them are merged.
- * rep[p] receives the smallest member of p's group (the group's name).
+ * Algorithm 1 as a union-find over the P ranks.  All ranks begin in sets of
+ * one.  Iteration t runs log2(S) butterfly phases; the first works on address
+ * bit (t * log2 S) mod log2 P and each later one on the next bit, cyclically.
+ * A phase on bit b joins the sets of every two ranks that differ in bit b only.
+ * rep[p] receives the smallest member of p's set, which names the group.
  */
 int oracle_grouping_unionfind(int P, int S, int64_t t, int32_t *rep)
 {
-    int global_phases = exact_log2(P);
-    int group_phases = exact_log2(S);
-    if (global_phases < 0 || group_phases < 0 || S > P || t < 0 || !rep)
+    int log2_P = exact_log2(P);
+    int log2_S = exact_log2(S);
+    if (log2_P < 0 || log2_S < 0 || S > P || t < 0 || !rep)
         return ORACLE_EINVAL;
 
     int32_t *parent = (int32_t *)malloc(sizeof(int32_t) * (size_t)P);
     if (!parent)
         return ORACLE_ENOMEM;
     for (int p = 0; p < P; ++p)
-        parent[p] = p; /* make each process an individual group */
+        parent[p] = p;
 
-    int shift = 0;
-    if (global_phases > 0)
-        shift = (int)((t * (int64_t)group_phases) % global_phases);
-
-    for (int r = 1; r <= group_phases; ++r) {
-        int mask = 1 << shift;
+    int bit = log2_P > 0 ? (int)((t * (int64_t)log2_S) % log2_P) : 0;
+    for (int phase = 0; phase < log2_S; ++phase) {
         for (int p = 0; p < P; ++p) {
-            int q = p ^ mask; /* equivalence relation p == q */
-            int group_p = uf_find(parent, p);
-            int group_q = uf_find(parent, q);
-            if (group_p != group_q) {
-                /* merge; the smaller name survives so that the final
-                 * representative is the smallest member */
-                if (group_p < group_q)
-                    parent[group_q] = group_p;
-                else
-                    parent[group_p] = group_q;
-            }
+            int partner = p ^ (1 << bit); /* the rank p exchanges with in this phase */
+            int root_a = uf_find(parent, p);
+            int root_b = uf_find(parent, partner);
+            /* the smaller root stays on top, so a set's root is its smallest member */
+            if (root_a < root_b)
+                parent[root_b] = root_a;
+            else if (root_b < root_a)
+                parent[root_a] = root_b;
         }
-        shift = (shift + 1) % global_phases;
+        bit = (bit + 1) % log2_P;
     }
     for (int p = 0; p < P; ++p)
         rep[p] = uf_find(parent, p);
@@ -222,17 +217,150 @@ static int mask_bit(const uint64_t *stale_mask, int p)
 }
 
 /*
- * One iteration t of Algorithm 2 (lines 6-17) for all P replicas, fp32.
+ * Algorithm 2, lines 6-17, as printed: one iteration t for all P replicas, in
+ * which every process finishes its local step inside the iteration (nobody is
+ * still computing an earlier one).  w, g, m, pub: P rows of ld floats, n used
+ * columns; w, m, pub are updated in place, g is read only.  stale_mask: bit p
+ * set = process p is late (NULL = nobody).  fixed_groups != 0: the groups of
+ * iteration 0 in every group iteration (the second ablation of Section 6.2).
+ * Written out on its own so that it can be read against the paper
+ * without the third state; a CPU test pins oracle_step_lag_f32(busy_mask = NULL)
+ * to it bit for bit.
+ */
+int oracle_step_f32(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
+                    float *w, const float *g, float *m, float *pub,
+                    const uint64_t *stale_mask, float lr, float mu, int fixed_groups)
+{
+    if (exact_log2(P) < 0 || exact_log2(S) < 0 || S > P || n < 1 || ld < n ||
+        tau < 0 || t < 0 || !w || !g || !m || !pub)
+        return ORACLE_EINVAL;
+
+    int32_t *table = (int32_t *)malloc(sizeof(int32_t) * (size_t)P);
+    float *w_prime = (float *)malloc(sizeof(float) * (size_t)P);
+    float *contrib = (float *)malloc(sizeof(float) * (size_t)P);
+    if (!table || !w_prime || !contrib) {
+        free(table);
+        free(w_prime);
+        free(contrib);
+        return ORACLE_ENOMEM;
+    }
+    int global = oracle_is_global_iteration(tau, t);
+    if (!global)
+        oracle_member_table(P, S, fixed_groups ? 0 : t, table);
+
+    for (int64_t j = 0; j < n; ++j) {
+        /* lines 6-7: W' = W + U(G, W, t), heavy-ball momentum */
+        for (int i = 0; i < P; ++i) {
+            int64_t at = (int64_t)i * ld + j;
+            float m_new = fmaf(mu, m[at], g[at]);
+            w_prime[i] = fmaf(-lr, m_new, w[at]);
+            m[at] = m_new;
+        }
+        if (global) {
+            /* lines 15-16: W_{t+1} = (1/P) * sum over all processes of W' */
+            float avg = tree_sum_f32(w_prime, P) * (1.0f / (float)P);
+            for (int i = 0; i < P; ++i)
+                w[(int64_t)i * ld + j] = avg;
+        } else {
+            for (int k = 0; k < P / S; ++k) {
+                const int32_t *member = table + (int64_t)k * S;
+                /* line 9: W_sum; a late process is represented by its send buffer */
+                for (int e = 0; e < S; ++e) {
+                    int p = member[e];
+                    contrib[e] = mask_bit(stale_mask, p) ? pub[(int64_t)p * ld + j] : w_prime[p];
+                }
+                float w_sum = tree_sum_f32(contrib, S);
+                for (int e = 0; e < S; ++e) {
+                    int p = member[e];
+                    if (!mask_bit(stale_mask, p))
+                        w[(int64_t)p * ld + j] = w_sum * (1.0f / (float)S);            /* lines 10-11 */
+                    else
+                        w[(int64_t)p * ld + j] = (w_sum + w_prime[p]) / (float)(S + 1); /* lines 12-13 */
+                }
+            }
+        }
+        /* Section 4: the send buffer is refreshed with W' */
+        for (int i = 0; i < P; ++i)
+            pub[(int64_t)i * ld + j] = w_prime[i];
+    }
+    free(table);
+    free(w_prime);
+    free(contrib);
+    return ORACLE_OK;
+}
+
+/* The same in fp64 (the shadow that bounds the rounding of the fp32 path). */
+int oracle_step_f64(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
+                    double *w, const double *g, double *m, double *pub,
+                    const uint64_t *stale_mask, double lr, double mu, int fixed_groups)
+{
+    if (exact_log2(P) < 0 || exact_log2(S) < 0 || S > P || n < 1 || ld < n ||
+        tau < 0 || t < 0 || !w || !g || !m || !pub)
+        return ORACLE_EINVAL;
+
+    int32_t *table = (int32_t *)malloc(sizeof(int32_t) * (size_t)P);
+    double *w_prime = (double *)malloc(sizeof(double) * (size_t)P);
+    double *contrib = (double *)malloc(sizeof(double) * (size_t)P);
+    if (!table || !w_prime || !contrib) {
+        free(table);
+        free(w_prime);
+        free(contrib);
+        return ORACLE_ENOMEM;
+    }
+    int global = oracle_is_global_iteration(tau, t);
+    if (!global)
+        oracle_member_table(P, S, fixed_groups ? 0 : t, table);
+
+    for (int64_t j = 0; j < n; ++j) {
+        for (int i = 0; i < P; ++i) {
+            int64_t at = (int64_t)i * ld + j;
+            double m_new = mu * m[at] + g[at];
+            w_prime[i] = w[at] - lr * m_new;
+            m[at] = m_new;
+        }
+        if (global) {
+            double avg = tree_sum_f64(w_prime, P) / (double)P;
+            for (int i = 0; i < P; ++i)
+                w[(int64_t)i * ld + j] = avg;
+        } else {
+            for (int k = 0; k < P / S; ++k) {
+                const int32_t *member = table + (int64_t)k * S;
+                for (int e = 0; e < S; ++e) {
+                    int p = member[e];
+                    contrib[e] = mask_bit(stale_mask, p) ? pub[(int64_t)p * ld + j] : w_prime[p];
+                }
+                double w_sum = tree_sum_f64(contrib, S);
+                for (int e = 0; e < S; ++e) {
+                    int p = member[e];
+                    if (!mask_bit(stale_mask, p))
+                        w[(int64_t)p * ld + j] = w_sum / (double)S;
+                    else
+                        w[(int64_t)p * ld + j] = (w_sum + w_prime[p]) / (double)(S + 1);
+                }
+            }
+        }
+        for (int i = 0; i < P; ++i)
+            pub[(int64_t)i * ld + j] = w_prime[i];
+    }
+    free(table);
+    free(w_prime);
+    free(contrib);
+    return ORACLE_OK;
+}
+
+/*
+ * The iteration of oracle_step_f32 with a third state beside "in time" and
+ * "late": a process that is still computing an earlier step when this
+ * iteration's group allreduce runs (the execution snapshot of Section 4,
+ * carried beyond one iteration).
  * w, g, m, pub: P rows of ld floats, n used columns.  w, m, pub are updated
  * in place; g is read only.  stale_mask: bit p set = process p is late in
  * this iteration (NULL = nobody): it contributes its send buffer, finishes its
  * local step afterwards and averages the group's sum with its own W' (lines
- * 12-13).  busy_mask: bit p set = process p is still computing an earlier step
- * when this iteration's group allreduce runs (the execution snapshot of
- * Section 4, carried beyond one iteration; NULL = nobody): it contributes its
- * send buffer again and nothing of it changes.  busy wins over late.  Both
- * masks are ignored in a global iteration, which every process enters after
- * the same number of steps.
+ * 12-13).  busy_mask: bit p set = process p is still computing (NULL =
+ * nobody): it contributes its send buffer again and nothing of it changes.
+ * busy wins over late.  Both masks are ignored in a global iteration, which
+ * every process enters after the same number of steps.
  * fixed_groups != 0 is the paper's second ablation (Section 6.2): group model
  * averaging without the dynamic grouping strategy, i.e. the groups of
  * iteration 0 in every group iteration.
@@ -375,23 +503,6 @@ int oracle_step_lag_f64(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
     free(w_prime);
     free(contrib);
     return ORACLE_OK;
-}
-
-/* Algorithm 2 as printed: every process finishes its local step inside the iteration. */
-int oracle_step_f32(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
-                    float *w, const float *g, float *m, float *pub,
-                    const uint64_t *stale_mask, float lr, float mu, int fixed_groups)
-{
-    return oracle_step_lag_f32(P, S, n, ld, tau, t, w, g, m, pub, stale_mask, NULL, lr, mu,
-                               fixed_groups);
-}
-
-int oracle_step_f64(int P, int S, int64_t n, int64_t ld, int tau, int64_t t,
-                    double *w, const double *g, double *m, double *pub,
-                    const uint64_t *stale_mask, double lr, double mu, int fixed_groups)
-{
-    return oracle_step_lag_f64(P, S, n, ld, tau, t, w, g, m, pub, stale_mask, NULL, lr, mu,
-                               fixed_groups);
 }
 
 /*

@@ -130,17 +130,32 @@ def test_lag_step_brute_force(P):
 
 
 def test_no_busy_process_is_algorithm_2_as_printed():
+    """oracle_step_lag_* with nobody busy against oracle_step_*, Algorithm 2 written out on its
+    own: bit for bit on random inputs, over group and global iterations, both precisions,
+    dynamic and fixed groups, with and without late processes."""
     rng = np.random.default_rng(5)
-    P, S, n = 16, 4, 33
-    state = [rng.normal(0, 1, (P, n)).astype(np.float32) for _ in range(4)]
-    late = rng.random(P) < 0.3
-    for busy in (None, np.zeros(P, dtype=bool)):
-        a = [x.copy() for x in state]
-        b = [x.copy() for x in state]
-        orc.step_f32(P, S, 0, 3, *a, late, 0.1, 0.9)
-        orc.step_lag_f32(P, S, 0, 3, *b, late, busy, 0.1, 0.9)
-        for x, y in zip(a, b):
-            assert np.array_equal(x.view(np.uint32), y.view(np.uint32))
+    for P, S, tau in ((16, 4, 3), (8, 8, 0), (32, 2, 2), (4, 1, 5), (64, 8, 4)):
+        n = 33
+        state = [rng.normal(0, 1, (P, n)).astype(np.float32) for _ in range(4)]
+        for fixed in (False, True):
+            for busy in (None, np.zeros(P, dtype=bool)):
+                a = [x.copy() for x in state]
+                b = [x.copy() for x in state]
+                a64 = [x.astype(np.float64) for x in state]
+                b64 = [x.astype(np.float64) for x in state]
+                for t in range(7):
+                    late = (rng.random(P) < 0.3) if t % 3 else None
+                    g = rng.normal(0, 1e-2, (P, n)).astype(np.float32)
+                    a[1], b[1] = g, g.copy()
+                    a64[1], b64[1] = g.astype(np.float64), g.astype(np.float64)
+                    orc.step_f32(P, S, tau, t, *a, late, 0.1, 0.9, fixed_groups=fixed)
+                    orc.step_lag_f32(P, S, tau, t, *b, late, busy, 0.1, 0.9, fixed_groups=fixed)
+                    orc.step_f64(P, S, tau, t, *a64, late, 0.1, 0.9, fixed_groups=fixed)
+                    orc.step_lag_f64(P, S, tau, t, *b64, late, busy, 0.1, 0.9, fixed_groups=fixed)
+                    for x, y in zip(a, b):
+                        assert np.array_equal(x.view(np.uint32), y.view(np.uint32)), (P, S, tau, t)
+                    for x, y in zip(a64, b64):
+                        assert np.array_equal(x.view(np.uint64), y.view(np.uint64)), (P, S, tau, t)
 
 
 def test_busy_wins_over_late_and_a_global_iteration_waits_for_everybody():

@@ -21,7 +21,9 @@ MUTATIONS = [
     ("sign of the learning rate",
      "fmaf(-lr, m_new, w[at])", "fmaf(lr, m_new, w[at])", pins.test_local_update_hand_value),
     ("cumulative mask in Algorithm 1",
-     "int mask = 1 << shift;", "static int mask; if (r == 1) mask = 1; mask <<= shift;",
+     "        for (int p = 0; p < P; ++p) {\n            int partner = p ^ (1 << bit);",
+     "        static int mask; if (phase == 0) mask = 1; mask <<= bit;\n"
+     "        for (int p = 0; p < P; ++p) {\n            int partner = p ^ mask;",
      pins.test_alg1_printed_example_p8_s4),
     ("momentum line not fused",
      "float m_new = fmaf(mu, m[at], g[at]);", "float m_new = mu * m[at] + g[at];",
@@ -33,21 +35,33 @@ MUTATIONS = [
      "float right = 0; for (int i = count / 2; i < count; ++i) left += c[i];",
      pins.test_sum_is_a_pairwise_tree_in_member_order),
     ("late member contributes W' instead of its send buffer",
-     "? pub[(int64_t)p * ld + j] /* send buffer */", "? w_prime[p]", pins.test_stale_rule_hand_value),
+     "contrib[e] = mask_bit(stale_mask, p) ? pub[(int64_t)p * ld + j] : w_prime[p];", "contrib[e] = w_prime[p];",
+     pins.test_stale_rule_hand_value),
     ("reciprocal multiply for 1/(S+1)",
-     "w[at] = (w_sum + w_prime[p]) / (float)(S + 1);",
-     "w[at] = (w_sum + w_prime[p]) * (1.0f / (float)(S + 1));",
+     "w[(int64_t)p * ld + j] = (w_sum + w_prime[p]) / (float)(S + 1);",
+     "w[(int64_t)p * ld + j] = (w_sum + w_prime[p]) * (1.0f / (float)(S + 1));",
      pins.test_stale_divisor_is_a_true_division),
     ("member digits in reverse phase order",
      "p |= 1 << bits[r];\n            table", "p |= 1 << bits[group_phases - 1 - r];\n            table",
      pins.test_alg1_phase_bits_wrap_order),
     ("send buffer gets W instead of W'",
-     "            if (global || !mask_bit(busy_mask, i))\n                pub[(int64_t)i * ld + j] = w_prime[i];",
-     "            if (global || !mask_bit(busy_mask, i))\n                pub[(int64_t)i * ld + j] = w[(int64_t)i * ld + j];",
+     "        for (int i = 0; i < P; ++i)\n            pub[(int64_t)i * ld + j] = w_prime[i];",
+     "        for (int i = 0; i < P; ++i)\n            pub[(int64_t)i * ld + j] = w[(int64_t)i * ld + j];",
      pins.test_stale_rule_hand_value),
     ("global average ignores half of the replicas",
-     "float sum = tree_sum_f32(w_prime, P);", "float sum = 2.0f * tree_sum_f32(w_prime, P / 2 ? P / 2 : 1);",
+     "float avg = tree_sum_f32(w_prime, P) * (1.0f / (float)P);",
+     "float avg = 2.0f * tree_sum_f32(w_prime, P / 2 ? P / 2 : 1) * (1.0f / (float)P);",
      pins.test_snapshot_script_p4_s2_f32),
+    ("late divisor S instead of S+1 in the function with the third state",
+     "w[at] = (w_sum + w_prime[p]) / (float)(S + 1);", "w[at] = (w_sum + w_prime[p]) / (float)(S);",
+     lag_pins.test_no_busy_process_is_algorithm_2_as_printed),
+    ("send buffer gets W instead of W' in the function with the third state",
+     "            if (global || !mask_bit(busy_mask, i))\n                pub[(int64_t)i * ld + j] = w_prime[i];",
+     "            if (global || !mask_bit(busy_mask, i))\n                pub[(int64_t)i * ld + j] = w[(int64_t)i * ld + j];",
+     lag_pins.test_no_busy_process_is_algorithm_2_as_printed),
+    ("global sum over half the replicas in the function with the third state",
+     "float sum = tree_sum_f32(w_prime, P);", "float sum = 2.0f * tree_sum_f32(w_prime, P / 2 ? P / 2 : 1);",
+     lag_pins.test_no_busy_process_is_algorithm_2_as_printed),
     ("a process that is still computing contributes W' instead of its send buffer",
      "contrib[e] = (mask_bit(stale_mask, p) || mask_bit(busy_mask, p))\n"
      "                                     ? pub[(int64_t)p * ld + j] /* send buffer */",
