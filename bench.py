@@ -7,12 +7,19 @@ with the lateness rule (or the global average every tau-th iteration), send-buff
 the timed region.  Prints ONE JSON line on stdout; progress goes to stderr.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1..5] [--opt NAME=VALUE ...]
+
+The default run times the headline workload (4: P=64, S=8, 25.6M parameters) on arrays placed by
+the library's allocator, then the same steps on ordinary torch allocations ("plain_alloc": what
+a caller who brings its own buffers gets), then the other four seeded workloads in child
+processes ("workloads"), then the CPU oracle on the host cores ("cpu_baseline").  --no-extras
+stops after the headline run.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -20,13 +27,19 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 
 # HBM bytes per launch of the dominant kernel from two `rocprofv3 --pmc` runs (FETCH_SIZE scaled by
 # 2.000, WRITE_SIZE by 1.000, the factors a plain copy of known size gave in the same runs), averaged
-# over the group launches of `bench.py --steps 20` (10 for workload 5); valid for the default launch
-# options only.  Source: the files under profiles/ for these kernels and workloads.
-MEASURED_TRAFFIC_BYTES = {2: 10.116e9, 3: 24.016e9, 4: 40.92e9, 5: 166.41e9}
-MEASURED_TRAFFIC_BYTES_PER_TENSOR = {4: 40.94e9}
+# over the group launches of the profiled command; valid for the launch options of PROFILE_OPTIONS
+# only.  workload -> (bytes per launch, the file under profiles/ that holds the figure).
+MEASURED_TRAFFIC = {
+    2: (10.116e9, "group_step_S4__resnet50-25.6M_P16_S4.md"),
+    3: (24.016e9, "group_step_S4__transformer-base-61.4M_P16_S4.md"),
+    4: (40.92e9, "group_step_S8__resnet50-25.6M_P64_S8.md"),
+    5: (166.41e9, "group_step_S8__transformer-big-210.8M_P32_S8.md"),
+}
+MEASURED_TRAFFIC_PER_TENSOR = {4: (40.94e9, "group_step_S8_per_tensor__resnet50-25.6M_P64_S8.md")}
+# option number -> value the profiles were taken with (the library's defaults at that time)
+PROFILE_OPTIONS = {"nontemporal": 1, "force_stream": 0, "stripe_log2": 2, "xcd_chunk_log2": 2}
 
-OPTS = {"block": 1, "nontemporal": 2, "force_stream": 3, "xcd_swizzle": 4, "tile_major": 5, "waves": 6,
-        "stripe_log2": 7, "xcd_chunk_log2": 8, "placement": 9}
+OPTS = {"nontemporal": 2, "force_stream": 3, "stripe_log2": 7, "xcd_chunk_log2": 8, "placement": 9}
 
 
 def log(*a):
@@ -37,16 +50,18 @@ def popcount(words) -> int:
     return sum(bin(int(x)).count("1") for x in words)
 
 
-def cpu_baseline(wl, columns: int, iters: int):
-    """The CPU oracle as it stands, one thread, on a column slice of the same workload
-    (columns are independent, so a slice is the same work per replica-parameter)."""
+# ---------------------------------------------------------------- CPU oracle baseline
+
+def oracle_slice_state(wl, columns: int, iters: int, seed_offset: int = 0):
+    """Inputs of the oracle on a column slice (columns are independent, so a slice is the same
+    work per replica-parameter): all P rows, the workload's gradient scale and masks."""
     import numpy as np
     import torch
     from oracle import wagma_oracle as orc
     from paper_2005_00124_amd import workloads as wk
 
     P = wl.P
-    gen = wk.make_generator(wl.seed, "cpu")
+    gen = wk.make_generator(wl.seed + seed_offset, "cpu")
     row = torch.empty(columns)
     row.normal_(0.0, 0.05, generator=gen)
     w = np.repeat(row.numpy()[None, :], P, axis=0).copy()
@@ -54,15 +69,131 @@ def cpu_baseline(wl, columns: int, iters: int):
     pub = w.copy()
     g = torch.empty((P, columns)).normal_(0.0, wl.grad_std, generator=gen).numpy()
     masks = [orc.stale_mask(wl.seed, t, P, wl.stale_threshold) for t in range(iters)]
-    orc.step_f32(P, wl.S, wl.tau, 0, w.copy(), g, m.copy(), pub.copy(), masks[0], wl.lr, wl.mu)  # warm
+    return w, g, m, pub, masks
+
+
+def oracle_run(wl, state, iters: int) -> float:
+    """Seconds the oracle takes for `iters` iterations on `state` (one thread)."""
+    from oracle import wagma_oracle as orc
+    w, g, m, pub, masks = state
     t0 = time.perf_counter()
     for t in range(iters):
-        orc.step_f32(P, wl.S, wl.tau, t, w, g, m, pub, masks[t], wl.lr, wl.mu)
-    dt = time.perf_counter() - t0
-    return {"value": P * columns * iters / dt, "unit": "replica-params/s", "cores": 1,
-            "kind": "oracle",
-            "sample": "%d-column slice of all %d rows, %d iterations (group and global, same masks), "
-                      "%.1f s single-threaded" % (columns, P, iters, dt)}
+        orc.step_f32(wl.P, wl.S, wl.tau, t, w, g, m, pub, masks[t], wl.lr, wl.mu)
+    return time.perf_counter() - t0
+
+
+def cpu_shard_main(args) -> int:
+    """Child of the all-cores leg: sets up its column shard, says "ready", waits for "go" on
+    stdin, runs, prints its seconds.  CPU only."""
+    from oracle import wagma_oracle as orc
+    from paper_2005_00124_amd import workloads as wk
+    wl = wk.workload(args.workload)
+    iters = args.steps
+    state = oracle_slice_state(wl, args.cpu_shard, iters, seed_offset=1000 + args.shard_index)
+    w, g, m, pub, masks = state
+    orc.step_f32(wl.P, wl.S, wl.tau, 0, w.copy(), g, m.copy(), pub.copy(), masks[0], wl.lr, wl.mu)  # warm
+    print("ready", flush=True)
+    if sys.stdin.readline().strip() != "go":
+        return 1
+    start = time.time()
+    seconds = oracle_run(wl, state, iters)
+    print(json.dumps({"seconds": seconds, "start": start, "end": time.time()}), flush=True)
+    return 0
+
+
+def cpu_model_name() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(wl, columns: int, iters: int, workers: int):
+    """The CPU oracle as it stands: one thread on a `columns`-column slice of the workload, and
+    the same binary as `workers` column-sharded processes (fresh children, CPU only)."""
+    from oracle import wagma_oracle as orc
+    P = wl.P
+    state = oracle_slice_state(wl, columns, iters)
+    w, g, m, pub, masks = state
+    orc.step_f32(P, wl.S, wl.tau, 0, w[:, :4096].copy(), g[:, :4096].copy(), m[:, :4096].copy(),
+                 pub[:, :4096].copy(), masks[0], wl.lr, wl.mu)   # warm (library load, page faults of the code)
+    dt = oracle_run(wl, state, iters)
+    out = {"value": P * columns * iters / dt, "unit": "replica-params/s", "cores": 1, "kind": "oracle",
+           "cpu_model": cpu_model_name(),
+           "sample": "%d-column slice of all %d rows, %d iterations (group and global, same masks), "
+                     "%.1f s single-threaded" % (columns, P, iters, dt)}
+    del state, w, g, m, pub
+    if workers > 1:
+        shard = max(4096, columns // workers)
+        cmd = [sys.executable, os.path.abspath(__file__), "--workload", str(wl.index), "--steps", str(iters),
+               "--cpu-shard", str(shard)]
+        env = dict(os.environ, OMP_NUM_THREADS="1", HIP_VISIBLE_DEVICES="", CUDA_VISIBLE_DEVICES="")
+        kids = [subprocess.Popen(cmd + ["--shard-index", str(k)], stdin=subprocess.PIPE, stdout=subprocess.PIPE,
+                                 text=True, env=env) for k in range(workers)]
+        try:
+            ok = all(kid.stdout.readline().strip() == "ready" for kid in kids)
+            for kid in kids:
+                kid.stdin.write("go\n" if ok else "stop\n")
+                kid.stdin.flush()
+            results = [json.loads(kid.stdout.readline()) for kid in kids] if ok else []
+        except (ValueError, OSError):
+            results = []
+        for kid in kids:
+            try:
+                kid.wait(timeout=60)
+            except subprocess.TimeoutExpired:
+                kid.kill()
+        if len(results) == workers:
+            span = max(r["end"] for r in results) - min(r["start"] for r in results)
+            out["all_cores"] = {
+                "value": P * shard * iters * workers / span, "unit": "replica-params/s", "cores": workers,
+                "cpu_model": cpu_model_name(),
+                "sample": "%d processes, each the oracle on its own %d-column shard of all %d rows, %d iterations; "
+                          "%.1f s from the first start to the last end" % (workers, shard, P, iters, span)}
+        else:
+            out["all_cores"] = {"error": "a shard process failed"}
+    return out
+
+
+# ---------------------------------------------------------------- GPU timing
+
+def time_steps(step, stream, K, graph=False):
+    """Per-step milliseconds (HIP events on the launch stream) and the wall time of K steps."""
+    import torch
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(K)]
+    ends = [torch.cuda.Event(enable_timing=True) for _ in range(K)]
+    if graph:
+        # masks and iteration numbers are baked into the captured launches
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                for t in range(K):
+                    step(t)
+        stream.wait_stream(side)
+        g.replay()                      # untimed first replay
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        starts[0].record(stream)
+        g.replay()
+        ends[0].record(stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        per_step = starts[0].elapsed_time(ends[0]) / K      # no events inside a graph: the mean
+        return [per_step] * K, wall
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(K):
+        starts[t].record(stream)
+        step(t)
+        ends[t].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return [starts[t].elapsed_time(ends[t]) for t in range(K)], wall
 
 
 def main() -> int:
@@ -74,7 +205,7 @@ def main() -> int:
     ap.add_argument("--P", type=int, default=None, help="override the workload's number of replicas")
     ap.add_argument("--S", type=int, default=None, help="override the workload's group size")
     ap.add_argument("--tau", type=int, default=None, help="override the workload's global period")
-    ap.add_argument("--opt", action="append", default=[], help="tuning knob NAME=VALUE (%s)" % ", ".join(OPTS))
+    ap.add_argument("--opt", action="append", default=[], help="launch switch NAME=VALUE (%s)" % ", ".join(OPTS))
     ap.add_argument("--ld", type=int, default=None, help="row stride override (floats)")
     ap.add_argument("--plain-alloc", action="store_true",
                     help="ordinary torch allocations instead of the library's HBM-region-aware allocator")
@@ -85,13 +216,18 @@ def main() -> int:
     ap.add_argument("--lag", type=int, default=None, metavar="TOLERANCE_MS",
                     help="lateness deeper than one iteration: wagma_lag_masks with this tolerance drive "
                          "wagma_step_lag instead of the workload's Bernoulli mask")
-    ap.add_argument("--all-workloads", action="store_true",
-                    help="afterwards run the other four seeded workloads too (child processes of this "
-                         "script) and attach their throughput and bandwidth as \"workloads\"")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="the headline run only: no plain-allocation leg, no other workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-columns", type=int, default=131072)
+    ap.add_argument("--cpu-columns", type=int, default=1048576)
+    ap.add_argument("--cpu-workers", type=int, default=None,
+                    help="processes of the all-cores oracle leg (default: the host's cores, at most OMP_NUM_THREADS)")
+    ap.add_argument("--cpu-shard", type=int, default=None, help=argparse.SUPPRESS)
+    ap.add_argument("--shard-index", type=int, default=0, help=argparse.SUPPRESS)
     args = ap.parse_args()
 
+    if args.cpu_shard is not None:
+        return cpu_shard_main(args)
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU only (the P workers are rows in one GPU's HBM); "
             "--gpus %d is not supported" % args.gpus)
@@ -115,6 +251,9 @@ def main() -> int:
         import dataclasses
         wl = dataclasses.replace(wl, **custom)
         wl = dataclasses.replace(wl, name="%s with %s" % (wl.name, ", ".join("%s=%d" % kv for kv in custom.items())))
+    variant = bool(custom or args.opt or args.ld or args.tensors or args.graph or args.lag is not None
+                   or args.plain_alloc)
+    extras = not args.no_extras and not variant and args.workload == 4
     K = wl.iters if args.steps is None else args.steps
     W = args.warmup
     P, S, n = wl.P, wl.S, wl.n
@@ -124,21 +263,12 @@ def main() -> int:
     ctx = lw.Wagma(P, S, n, wl.tau)
     if args.ld:
         ctx.set_row_stride(args.ld)
+    defaults_match = all(ctx.debug_get_option(OPTS[k]) == v for k, v in PROFILE_OPTIONS.items())
     for kv in args.opt:
         k, v = kv.split("=")
-        ctx.set_option(OPTS[k], int(v))
+        ctx.debug_set_option(OPTS[k], int(v))
     ld = ctx.ld
     log("workload %d: %s  n=%d ld=%d  buffers 4 x %.2f GB" % (wl.index, wl.name, n, ld, P * ld * 4 / 1e9))
-    if args.plain_alloc:
-        w, g, m, pub = ctx.alloc()
-        placement = "torch allocations"
-    else:
-        w, g, m, pub = ctx.alloc_placed()     # w, m, pub in different HBM regions
-        info = ctx.placement_info()
-        placement = "wagma_alloc_buffers: %(mode)s placement, %(candidates)d memory blocks examined" % info
-        log("placement:", info)
-    wk.fill_initial_state(wl, w, m, pub)
-    wk.fill_gradients(wl, 0, g)       # one gradient slab, reused: generating it is not part of the path
     busy_masks = None
     if args.lag is None:
         masks = [ctx.stale_mask(wl.seed, t, wl.stale_threshold) for t in range(max(K, W))]
@@ -147,67 +277,6 @@ def main() -> int:
         masks = [late for late, _ in both]
         busy_masks = [busy for _, busy in both]
     stream = torch.cuda.current_stream()
-
-    plan = None
-    if args.tensors:
-        import math
-        sizes = [math.prod(t[1]) for t in wl.tensors()]
-
-        def views(buf):
-            out = []
-            for p in range(P):
-                at, row = 0, []
-                for size in sizes:
-                    row.append(buf[p, at:at + size])
-                    at += size
-                out.append(row)
-            return out
-        plan = ctx.tensor_plan(views(w), views(g), views(m), views(pub))
-        log("per-tensor layout: %d tensors per replica" % len(sizes))
-
-    def step(t):
-        busy = None if busy_masks is None else busy_masks[t]
-        if plan is not None:
-            plan.step(masks[t], wl.lr, wl.mu, t, busy_mask=busy)
-        else:
-            ctx.step(w, g, m, pub, masks[t], wl.lr, wl.mu, t, busy_mask=busy)
-
-    for t in range(W):
-        step(t)
-    torch.cuda.synchronize()
-
-    starts = [torch.cuda.Event(enable_timing=True) for _ in range(K)]
-    ends = [torch.cuda.Event(enable_timing=True) for _ in range(K)]
-    if args.graph:
-        # masks and iteration numbers are baked into the captured launches
-        graph = torch.cuda.CUDAGraph()
-        side = torch.cuda.Stream()
-        side.wait_stream(stream)
-        with torch.cuda.stream(side):
-            with torch.cuda.graph(graph, stream=side):
-                for t in range(K):
-                    step(t)
-        stream.wait_stream(side)
-        graph.replay()                      # untimed first replay
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        starts[0].record(stream)
-        graph.replay()
-        ends[0].record(stream)
-        torch.cuda.synchronize()
-        wall = time.perf_counter() - t0
-        per_step = starts[0].elapsed_time(ends[0]) / K      # no events inside a graph: the mean
-        ms = [per_step] * K
-    else:
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for t in range(K):
-            starts[t].record(stream)
-            step(t)
-            ends[t].record(stream)
-        torch.cuda.synchronize()
-        wall = time.perf_counter() - t0
-        ms = [starts[t].elapsed_time(ends[t]) for t in range(K)]
     is_global = [ctx.is_global(t) for t in range(K)]
     grp = [t for t in range(K) if not is_global[t]]
     glb = [t for t in range(K) if is_global[t]]
@@ -217,13 +286,59 @@ def main() -> int:
     # (24 B), plus a 4 B send-buffer read for every late replica-parameter; of a process
     # that is still computing only the send buffer is read (4 B)
     bytes_of = [n * (24 * (P - busy[t]) + 4 * late[t] + 4 * busy[t]) for t in range(K)]
+
+    def run_on(w, g, m, pub, steps):
+        """Fill the arrays, warm up, time `steps` steps; returns (per-step ms, wall seconds)."""
+        wk.fill_initial_state(wl, w, m, pub)
+        wk.fill_gradients(wl, 0, g)       # one gradient slab, reused: generating it is not part of the path
+        plan = None
+        if args.tensors:
+            import math
+            sizes = [math.prod(t[1]) for t in wl.tensors()]
+
+            def views(buf):
+                out = []
+                for p in range(P):
+                    at, row = 0, []
+                    for size in sizes:
+                        row.append(buf[p, at:at + size])
+                        at += size
+                    out.append(row)
+                return out
+            plan = ctx.tensor_plan(views(w), views(g), views(m), views(pub))
+            log("per-tensor layout: %d tensors per replica" % len(sizes))
+
+        def step(t):
+            b = None if busy_masks is None else busy_masks[t]
+            if plan is not None:
+                plan.step(masks[t], wl.lr, wl.mu, t, busy_mask=b)
+            else:
+                ctx.step(w, g, m, pub, masks[t], wl.lr, wl.mu, t, busy_mask=b)
+
+        for t in range(W):
+            step(t)
+        torch.cuda.synchronize()
+        ms, wall = time_steps(step, stream, steps, graph=args.graph)
+        assert torch.isfinite(w[:, :n]).all()
+        if plan is not None:
+            plan.destroy()
+        return ms, wall
+
+    if args.plain_alloc:
+        bufs = ctx.alloc()
+        placement = "torch allocations"
+    else:
+        bufs = ctx.alloc_placed()     # w, m, pub in different HBM regions
+        info = ctx.placement_info()
+        placement = "wagma_alloc_buffers: %(mode)s placement, %(candidates)d memory blocks examined" % info
+        log("placement:", info)
+    ms, wall = run_on(*bufs, K)
     grp_ms = sum(ms[t] for t in grp)
     glb_ms = sum(ms[t] for t in glb)
-    assert torch.isfinite(w[:, :n]).all()
 
     if grp:
         dom, dom_ts = "group step (S=%d member rows %s%s)" % (
-            S, "in registers" if S <= 8 else "streamed", ", per-tensor layout" if plan is not None else ""), grp
+            S, "in registers" if S <= 8 else "streamed", ", per-tensor layout" if args.tensors else ""), grp
     else:
         dom, dom_ts = "global step (rows streamed)", glb
     dom_ms = sum(ms[t] for t in dom_ts)
@@ -232,11 +347,15 @@ def main() -> int:
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                 "avg_launch_ms": dom_ms / len(dom_ts), "launches": len(dom_ts),
                 "algorithmic_bytes_per_launch": sum(bytes_of[t] for t in dom_ts) / len(dom_ts),
-                "traffic": (MEASURED_TRAFFIC_BYTES if plan is None else MEASURED_TRAFFIC_BYTES_PER_TENSOR).get(wl.index)
-                if grp and not args.opt and not args.ld and args.lag is None and not custom else None}
-    if roofline["traffic"]:
-        # counter-based rate: the measured HBM bytes of such a launch over this run's launch time
-        roofline["traffic_gbs"] = roofline["traffic"] / (roofline["avg_launch_ms"] * 1e-3) / 1e9
+                "traffic": None, "traffic_source": None}
+    stored = (MEASURED_TRAFFIC_PER_TENSOR if args.tensors else MEASURED_TRAFFIC).get(wl.index)
+    if (stored and grp and defaults_match and not args.opt and not args.ld and args.lag is None
+            and not custom and not args.graph):
+        # HBM bytes of such a launch as the counters measured them in the profiled run; stale
+        # (hence left out) as soon as the library's launch defaults differ from that run's
+        roofline["traffic"] = stored[0]
+        roofline["traffic_source"] = "profiles/" + stored[1]
+        roofline["traffic_gbs"] = stored[0] / (roofline["avg_launch_ms"] * 1e-3) / 1e9
     out = {
         "metric": "replica-params averaged/sec", "value": P * n * K / wall, "unit": "replica-params/s",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": wall * 1e3 / K,
@@ -249,7 +368,7 @@ def main() -> int:
                    % (args.lag, sum(late) / max(1, P * len(grp)), sum(busy) / max(1, P * len(grp))),
                    "global_steps_in_run": len(glb),
                    "options": args.opt, "allocation": placement,
-                   "layout": "per-tensor" if plan is not None else "flat rows",
+                   "layout": "per-tensor" if args.tensors else "flat rows",
                    "launch": "one HIP graph of K steps" if args.graph else "one launch per step"},
         "hbm_gbs_all_steps": sum(bytes_of) / ((grp_ms + glb_ms) * 1e-3) / 1e9,
         "group_step_ms": (grp_ms / len(grp)) if grp else None,
@@ -259,32 +378,52 @@ def main() -> int:
         "global_step_gbs": (sum(bytes_of[t] for t in glb) / (glb_ms * 1e-3) / 1e9) if glb else None,
         "roofline": roofline,
     }
-    if plan is not None:
-        plan.destroy()
-    del w, g, m, pub
+    del bufs
+    if not args.plain_alloc:
+        ctx.free_placed()
+
+    if extras:
+        # the boundary's own configuration: the caller owns w, g, m, pub (torch allocations)
+        log("the same steps on torch allocations ...")
+        bufs = ctx.alloc()
+        pms, _ = run_on(*bufs, K)
+        del bufs
+        p_ms = sum(pms[t] for t in dom_ts)
+        p_gbs = sum(bytes_of[t] for t in dom_ts) / (p_ms * 1e-3) / 1e9
+        out["plain_alloc"] = {"allocation": "torch allocations (caller-owned buffers)", "kernel": dom,
+                              "group_step_ms": p_ms / len(dom_ts), "achieved": p_gbs, "unit": "GB/s",
+                              "frac": p_gbs / HBM_PEAK_GBS, "launches": len(dom_ts)}
     ctx.destroy()
     torch.cuda.empty_cache()
-    if args.all_workloads:
-        import subprocess
+
+    if extras:
         summary = {wl.index: {"workload": wl.name, "value": out["value"], "ms_per_step": out["ms_per_step"],
-                              "group_step_gbs": roofline["achieved"], "frac": roofline["frac"]}}
+                              "group_step_gbs": roofline["achieved"], "frac": roofline["frac"],
+                              "global_step_gbs": out["global_step_gbs"]}}
         for k in range(1, len(wk.WORKLOADS) + 1):
             if k == wl.index:
                 continue
             log("workload %d ..." % k)
-            child = subprocess.run([sys.executable, os.path.abspath(__file__), "--workload", str(k),
-                                    "--no-cpu-baseline", "--warmup", str(W)], capture_output=True, text=True)
-            line = [x for x in child.stdout.splitlines() if x.startswith("{")]
-            if child.returncode != 0 or not line:
-                summary[k] = {"error": child.stderr[-300:]}
-                continue
-            o = json.loads(line[-1])
-            summary[k] = {"workload": o["config"]["workload"], "value": o["value"], "ms_per_step": o["ms_per_step"],
-                          "group_step_gbs": o["roofline"]["achieved"], "frac": o["roofline"]["frac"]}
+            try:
+                child = subprocess.run([sys.executable, os.path.abspath(__file__), "--workload", str(k),
+                                        "--no-cpu-baseline", "--no-extras", "--warmup", str(W)],
+                                       capture_output=True, text=True, timeout=240)
+                line = [x for x in child.stdout.splitlines() if x.startswith("{")]
+                if child.returncode != 0 or not line:
+                    raise RuntimeError(child.stderr[-300:])
+                o = json.loads(line[-1])
+                summary[k] = {"workload": o["config"]["workload"], "value": o["value"], "ms_per_step": o["ms_per_step"],
+                              "group_step_gbs": o["roofline"]["achieved"], "frac": o["roofline"]["frac"],
+                              "global_step_gbs": o["global_step_gbs"]}
+            except (RuntimeError, subprocess.TimeoutExpired, ValueError) as e:
+                summary[k] = {"error": str(e)[-300:]}
         out["workloads"] = {str(k): summary[k] for k in sorted(summary)}
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a slice ...")
-        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_columns, min(K, wl.iters))
+        workers = args.cpu_workers
+        if workers is None:
+            workers = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16") or 16))
+        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_columns, min(K, wl.iters), workers)
     print(json.dumps(out), flush=True)
     return 0
 

@@ -24,7 +24,8 @@
  *     (a multiple of 4, >= n).  Columns [0, n) carry the model.  Columns
  *     [n, ld) are padding: the library may read them and may overwrite columns
  *     [n, 4*ceil(n/4)) with unspecified values; it never lets padding
- *     influence columns [0, n).
+ *     influence columns [0, n).  The four arrays must be four different pieces
+ *     of memory: arrays whose P*ld-float extents overlap are WAGMA_EINVAL.
  */
 #ifndef WAGMA_H
 #define WAGMA_H
@@ -296,23 +297,9 @@ int wagma_free_buffers(wagma_ctx* ctx);
 int wagma_placement_info(const wagma_ctx* ctx, int* mode, int* candidates, int* regions, int* g_with_w,
                          double* same_gbs, double* split_gbs);
 
-/* Tuning knobs; the defaults are the measured best on MI355X.  Results do not
- * depend on them (same summation order in every variant). */
-#define WAGMA_OPT_BLOCK 1        /* threads per workgroup: 256 (default) or 512          */
+/* Options; the defaults are the measured best on MI355X.  Results do not depend on them. */
 #define WAGMA_OPT_NONTEMPORAL 2  /* 0/1: non-temporal hint on loads and stores (default: 1
                                     unless the four arrays fit in 256 MB together)     */
-#define WAGMA_OPT_FORCE_STREAM 3 /* 0/1: use the row-streaming kernel for every S     */
-#define WAGMA_OPT_XCD_SWIZZLE 4  /* 0/1: give each of the 8 XCDs a contiguous range of workgroups */
-#define WAGMA_OPT_TILE_MAJOR 5   /* 0/1: consecutive workgroups walk the groups of one column
-                                    tile (1) or the column tiles of one group (0)          */
-#define WAGMA_OPT_WAVES 6        /* 2..4: wavefronts per SIMD the register budget of the
-                                    S >= 8 kernels allows                                  */
-#define WAGMA_OPT_STRIPE_LOG2 7  /* 0..16: the wavefronts of a workgroup work 2^v KiB apart in
-                                    every row (0 = one contiguous tile per workgroup)      */
-#define WAGMA_OPT_XCD_CHUNK_LOG2 8 /* 0..13: each XCD works on runs of 2^v consecutive column
-                                    tiles of a row instead of every 8th tile; a per-tensor plan
-                                    takes the value at wagma_tensors_create (its tiles are
-                                    half as long: runs of 2^(v+1), at most 256, tiles)     */
 #define WAGMA_OPT_PLACEMENT 9    /* how wagma_alloc_buffers places the arrays: WAGMA_PLACE_*  */
 #define WAGMA_PLACE_PLAIN 0      /* four ordinary allocations                                  */
 #define WAGMA_PLACE_ARRAYS 1     /* whole arrays in different HBM regions                      */

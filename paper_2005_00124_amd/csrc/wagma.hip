@@ -101,17 +101,13 @@ void set_defaults(wagma_ctx* ctx, int P, int S, int G, int g, int64_t n, int tau
     ctx->ld = (n + row_align - 1) / row_align * row_align;
     if ((ctx->ld * 4) % (int64_t(1) << 20) == 0)
         ctx->ld += 5 * row_align;
-    // Measured best on MI355X, options side by side on the same arrays: 256-thread workgroups
-    // (three of them fit a compute unit with the S = 8 kernel's registers, against one of 512
-    // threads) are 0.8-1 % faster than 512-thread ones on workloads 2, 4 and 5, level on 3.
-    ctx->opt_block = 256;
     // Streaming hints help only when the arrays stream from HBM: four arrays that fit in the
     // 256 MB Infinity Cache together run 6 % faster without them (P=4, n=2^20).
     ctx->opt_nontemporal = (size_t)4 * (size_t)P * (size_t)ctx->ld * sizeof(float) > (size_t(256) << 20) ? 1 : 0;
     ctx->opt_force_stream = 0;
-    ctx->opt_swizzle = 0;
-    ctx->opt_tile_major = 0;
-    ctx->opt_waves = 2;
+    // Measured best on MI355X (workgroups of 256 threads: three of them fit a compute unit with
+    // the S = 8 kernel's registers): the wavefronts of a workgroup 4 KiB apart, runs of 4
+    // consecutive tiles per XCD.
     ctx->opt_stripe_log2 = 2;
     ctx->opt_xcd_chunk_log2 = 2;
     ctx->fixed_groups = 0;
@@ -130,50 +126,21 @@ void set_defaults(wagma_ctx* ctx, int P, int S, int G, int g, int64_t n, int tau
     ctx->place_split_gbs = 0.0;
 }
 
-// WAVES = resident wavefronts per SIMD the register allocation must allow
-// (2, 3 or 4: at most 256, 168 or 128 vector registers per lane).
-template <int S, bool NT, bool LAG, int BLOCK, int WAVES>
-void launch_registers(const StepParams& p, unsigned grid, hipStream_t stream)
+// LAG: the kernels that also look at the busy mask (chosen only when a bit of it is set).
+template <bool NT, bool LAG>
+void launch_flat(const StepParams& p, bool streamed, unsigned grid, hipStream_t stream)
 {
-    hipLaunchKernelGGL((step_rows_in_registers<S, NT, LAG, BLOCK, WAVES>), dim3(grid), dim3(BLOCK), 0,
-                       stream, p);
-}
-
-template <bool NT, bool LAG, int BLOCK, int WAVES>
-void launch_variant(const StepParams& p, bool streamed, unsigned grid, hipStream_t stream)
-{
+    const dim3 g(grid), b(kBlock);
     if (streamed) {
-        hipLaunchKernelGGL((step_rows_streamed<NT, LAG, BLOCK, WAVES>), dim3(grid), dim3(BLOCK), 0,
-                           stream, p);
+        hipLaunchKernelGGL((step_rows_streamed<NT, LAG>), g, b, 0, stream, p);
         return;
     }
     switch (p.members) {
-    case 1: launch_registers<1, NT, LAG, BLOCK, 4>(p, grid, stream); break;
-    case 2: launch_registers<2, NT, LAG, BLOCK, 4>(p, grid, stream); break;
-    case 4: launch_registers<4, NT, LAG, BLOCK, 4>(p, grid, stream); break;
-    default: launch_registers<8, NT, LAG, BLOCK, WAVES>(p, grid, stream); break;
+    case 1: hipLaunchKernelGGL((step_rows_in_registers<1, NT, LAG>), g, b, 0, stream, p); break;
+    case 2: hipLaunchKernelGGL((step_rows_in_registers<2, NT, LAG>), g, b, 0, stream, p); break;
+    case 4: hipLaunchKernelGGL((step_rows_in_registers<4, NT, LAG>), g, b, 0, stream, p); break;
+    default: hipLaunchKernelGGL((step_rows_in_registers<8, NT, LAG>), g, b, 0, stream, p); break;
     }
-}
-
-template <bool NT, bool LAG, int BLOCK>
-void launch_waves(const StepParams& p, bool streamed, int waves, unsigned grid, hipStream_t stream)
-{
-    switch (waves) {
-    case 2: launch_variant<NT, LAG, BLOCK, 2>(p, streamed, grid, stream); break;
-    case 3: launch_variant<NT, LAG, BLOCK, 3>(p, streamed, grid, stream); break;
-    default: launch_variant<NT, LAG, BLOCK, 4>(p, streamed, grid, stream); break;
-    }
-}
-
-// LAG: the kernels that also look at the busy mask (chosen only when a bit of it is set).
-template <bool NT, bool LAG>
-void launch_block(const StepParams& p, bool streamed, int block, int waves, unsigned grid,
-                  hipStream_t stream)
-{
-    if (block == 512)
-        launch_waves<NT, LAG, 512>(p, streamed, waves, grid, stream);
-    else
-        launch_waves<NT, LAG, 256>(p, streamed, waves, grid, stream);
 }
 
 }  // namespace
@@ -192,18 +159,18 @@ struct wagma_tensors {
 };
 
 namespace {
-constexpr int kTensorBlock = 256;  // threads per workgroup of the per-tensor kernels
+constexpr int kTensorBlock = kBlock;  // threads per workgroup of the per-tensor kernels
 
 template <bool NT, bool LAG>
 void launch_tensors(const StepParams& p, unsigned grid, hipStream_t stream)
 {
     const dim3 g(grid), b(kTensorBlock);
     switch (p.members) {
-    case 1: hipLaunchKernelGGL((step_tensors_in_registers<1, NT, LAG, kTensorBlock>), g, b, 0, stream, p); break;
-    case 2: hipLaunchKernelGGL((step_tensors_in_registers<2, NT, LAG, kTensorBlock>), g, b, 0, stream, p); break;
-    case 4: hipLaunchKernelGGL((step_tensors_in_registers<4, NT, LAG, kTensorBlock>), g, b, 0, stream, p); break;
-    case 8: hipLaunchKernelGGL((step_tensors_in_registers<8, NT, LAG, kTensorBlock>), g, b, 0, stream, p); break;
-    default: hipLaunchKernelGGL((step_tensors_streamed<NT, LAG, kTensorBlock>), g, b, 0, stream, p); break;
+    case 1: hipLaunchKernelGGL((step_tensors_in_registers<1, NT, LAG>), g, b, 0, stream, p); break;
+    case 2: hipLaunchKernelGGL((step_tensors_in_registers<2, NT, LAG>), g, b, 0, stream, p); break;
+    case 4: hipLaunchKernelGGL((step_tensors_in_registers<4, NT, LAG>), g, b, 0, stream, p); break;
+    case 8: hipLaunchKernelGGL((step_tensors_in_registers<8, NT, LAG>), g, b, 0, stream, p); break;
+    default: hipLaunchKernelGGL((step_tensors_streamed<NT, LAG>), g, b, 0, stream, p); break;
     }
 }
 }  // namespace
@@ -254,6 +221,16 @@ int step_flat(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub, co
         return WAGMA_EINVAL;
     if ((((uintptr_t)w) | ((uintptr_t)g) | ((uintptr_t)m) | ((uintptr_t)pub)) & 15u)
         return WAGMA_EINVAL;
+    {
+        // every element is read and written by one thread only as long as the four arrays are
+        // four different pieces of memory: refuse arrays that overlap
+        const uintptr_t at[4] = {(uintptr_t)w, (uintptr_t)g, (uintptr_t)m, (uintptr_t)pub};
+        const uintptr_t extent = (uintptr_t)ctx->P * (uintptr_t)ctx->ld * sizeof(float);
+        for (int a = 0; a < 4; ++a)
+            for (int b = a + 1; b < 4; ++b)
+                if (at[a] < at[b] + extent && at[b] < at[a] + extent)
+                    return WAGMA_EINVAL;
+    }
     int device = -1;
     hipError_t e = hipGetDevice(&device);
     if (e != hipSuccess)
@@ -271,39 +248,33 @@ int step_flat(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub, co
     p.pub = pub;
     p.ld = ctx->ld;
     p.nvec = (ctx->n + 3) / 4;
-    p.swizzle = ctx->opt_swizzle;
-    p.tile_major = ctx->opt_tile_major;
 
     const bool streamed = p.members > kRegisterRows || (ctx->opt_force_stream && p.members == kRegisterRows);
     p.log2_chunks = streamed ? exact_log2(p.members / streamed_chunk(lag)) : 0;
-    const int block = ctx->opt_block;
     p.stripe_log2 = ctx->opt_stripe_log2;
-    // whole stripes: tiles is a multiple of 2^stripe_log2 (the surplus lanes find col >= nvec)
-    p.tiles = (p.nvec + block - 1) / block;
     p.xcd_chunk_log2 = ctx->opt_xcd_chunk_log2;
     // tiles is rounded up to whole stripes and whole XCD rounds (the surplus lanes find col >= nvec)
+    p.tiles = (p.nvec + kBlock - 1) / kBlock;
     int round_log2 = p.stripe_log2;
     if (p.xcd_chunk_log2 > 0 && p.xcd_chunk_log2 + 3 > round_log2)
         round_log2 = p.xcd_chunk_log2 + 3;
     p.tiles = ((p.tiles + (int64_t(1) << round_log2) - 1) >> round_log2) << round_log2;
     p.blocks = (int64_t)(ctx->P / p.members) * p.tiles;
-    int64_t grid = p.blocks;
-    if (p.swizzle)
-        grid = (grid + kNumXcd - 1) / kNumXcd * kNumXcd;
+    const int64_t grid = p.blocks;
     if (grid > 0x7fffffff)
         return WAGMA_EINVAL;
 
     const hipStream_t on = (hipStream_t)stream;
     if (ctx->opt_nontemporal) {
         if (lag)
-            launch_block<true, true>(p, streamed, block, ctx->opt_waves, (unsigned)grid, on);
+            launch_flat<true, true>(p, streamed, (unsigned)grid, on);
         else
-            launch_block<true, false>(p, streamed, block, ctx->opt_waves, (unsigned)grid, on);
+            launch_flat<true, false>(p, streamed, (unsigned)grid, on);
     } else {
         if (lag)
-            launch_block<false, true>(p, streamed, block, ctx->opt_waves, (unsigned)grid, on);
+            launch_flat<false, true>(p, streamed, (unsigned)grid, on);
         else
-            launch_block<false, false>(p, streamed, block, ctx->opt_waves, (unsigned)grid, on);
+            launch_flat<false, false>(p, streamed, (unsigned)grid, on);
     }
     e = hipGetLastError();
     if (e != hipSuccess)
@@ -738,45 +709,55 @@ int wagma_set_option(wagma_ctx* ctx, int option, int64_t value)
     if (!ctx)
         return WAGMA_EINVAL;
     switch (option) {
-    case WAGMA_OPT_BLOCK:
-        if (value != 256 && value != 512)
-            return WAGMA_EINVAL;
-        ctx->opt_block = (int)value;
-        return WAGMA_OK;
     case WAGMA_OPT_NONTEMPORAL:
         ctx->opt_nontemporal = value != 0;
-        return WAGMA_OK;
-    case WAGMA_OPT_FORCE_STREAM:
-        ctx->opt_force_stream = value != 0;
-        return WAGMA_OK;
-    case WAGMA_OPT_XCD_SWIZZLE:
-        ctx->opt_swizzle = value != 0;
-        return WAGMA_OK;
-    case WAGMA_OPT_TILE_MAJOR:
-        ctx->opt_tile_major = value != 0;
-        return WAGMA_OK;
-    case WAGMA_OPT_STRIPE_LOG2:
-        if (value < 0 || value > 16)
-            return WAGMA_EINVAL;
-        ctx->opt_stripe_log2 = (int)value;
         return WAGMA_OK;
     case WAGMA_OPT_PLACEMENT:
         if (value < WAGMA_PLACE_PLAIN || value > WAGMA_PLACE_SEARCH)
             return WAGMA_EINVAL;
         ctx->opt_placement = (int)value;
         return WAGMA_OK;
-    case WAGMA_OPT_XCD_CHUNK_LOG2:
+    default:
+        return WAGMA_EINVAL;
+    }
+}
+
+// Not part of include/wagma.h: launch-shape switches for the tests and for measurements
+// (declared in wagma_internal.h).  Results never depend on them.
+int wagma_debug_set_option(wagma_ctx* ctx, int option, int64_t value)
+{
+    if (!ctx)
+        return WAGMA_EINVAL;
+    switch (option) {
+    case WAGMA_DEBUG_FORCE_STREAM:
+        ctx->opt_force_stream = value != 0;
+        return WAGMA_OK;
+    case WAGMA_DEBUG_STRIPE_LOG2:
+        if (value < 0 || value > 16)
+            return WAGMA_EINVAL;
+        ctx->opt_stripe_log2 = (int)value;
+        return WAGMA_OK;
+    case WAGMA_DEBUG_XCD_CHUNK_LOG2:
         if (value < 0 || value > 13)
             return WAGMA_EINVAL;
         ctx->opt_xcd_chunk_log2 = (int)value;
         return WAGMA_OK;
-    case WAGMA_OPT_WAVES:
-        if (value < 2 || value > 4)
-            return WAGMA_EINVAL;
-        ctx->opt_waves = (int)value;
-        return WAGMA_OK;
     default:
+        return wagma_set_option(ctx, option, value);
+    }
+}
+
+int wagma_debug_get_option(const wagma_ctx* ctx, int option, int64_t* value)
+{
+    if (!ctx || !value)
         return WAGMA_EINVAL;
+    switch (option) {
+    case WAGMA_OPT_NONTEMPORAL: *value = ctx->opt_nontemporal; return WAGMA_OK;
+    case WAGMA_OPT_PLACEMENT: *value = ctx->opt_placement; return WAGMA_OK;
+    case WAGMA_DEBUG_FORCE_STREAM: *value = ctx->opt_force_stream; return WAGMA_OK;
+    case WAGMA_DEBUG_STRIPE_LOG2: *value = ctx->opt_stripe_log2; return WAGMA_OK;
+    case WAGMA_DEBUG_XCD_CHUNK_LOG2: *value = ctx->opt_xcd_chunk_log2; return WAGMA_OK;
+    default: return WAGMA_EINVAL;
     }
 }
 

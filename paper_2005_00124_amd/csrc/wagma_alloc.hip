@@ -561,9 +561,10 @@ int wagma_alloc_buffers(wagma_ctx* ctx, float** w, float** g, float** m, float**
     const size_t bytes = (size_t)ctx->P * (size_t)ctx->ld * sizeof(float);
     const bool debug = std::getenv("WAGMA_DEBUG_PLACEMENT") != nullptr;
 
-    // Candidate placements in the order chunks, whole arrays, plain.  With WAGMA_PLACE_AUTO
-    // each one that can be had is timed with the step kernel itself and the fastest is kept
-    // (at most two sets of arrays exist at a time); a fixed mode takes the first that works.
+    // Candidate placements in the order timed search, chunks, whole arrays, plain.  With
+    // WAGMA_PLACE_AUTO each one that can be had (whole arrays excepted, see below) is timed with
+    // the step kernel itself and the fastest is kept (at most two sets of arrays exist at a
+    // time); a fixed mode takes the first that works.
     const int mode = bytes >= wagma_placement::kPlacementMinBytes ? ctx->opt_placement : WAGMA_PLACE_PLAIN;
     const int order[4] = {WAGMA_PLACE_SEARCH, WAGMA_PLACE_CHUNKS, WAGMA_PLACE_ARRAYS, WAGMA_PLACE_PLAIN};
     ArraySet best;
@@ -596,7 +597,10 @@ int wagma_alloc_buffers(wagma_ctx* ctx, float** w, float** g, float** m, float**
         if (debug)
             std::fprintf(stderr, "wagma placement: mode %d regions %d: %.3f ms per group step\n", trial.mode,
                          trial.regions, trial.step_ms);
-        if (!best.ptr[0] || (trial.step_ms > 0.0 && trial.step_ms < 0.99 * best.step_ms)) {
+        // step_ms == 0: the timing failed, the placement's speed is unknown; any placement with
+        // a known time replaces such a one, and a later one must be 1 % faster to replace a known one
+        const bool better = trial.step_ms > 0.0 && (best.step_ms == 0.0 || trial.step_ms < 0.99 * best.step_ms);
+        if (!best.ptr[0] || better) {
             release(best);
             best = trial;
         } else {

@@ -18,7 +18,7 @@ struct wagma_ctx {
     int64_t n, ld;
     int32_t* d_table;  // (period + 1) * P, device
     int32_t* h_table;  // host mirror
-    int opt_block, opt_nontemporal, opt_force_stream, opt_swizzle, opt_tile_major, opt_waves, opt_stripe_log2, opt_xcd_chunk_log2;
+    int opt_nontemporal, opt_force_stream, opt_stripe_log2, opt_xcd_chunk_log2;
     float* placed[4];        // w, g, m, pub handed out by wagma_alloc_buffers (or all NULL)
     int64_t placed_ld;       // the row stride those arrays were sized for
     VmmArrays* vmm;          // not NULL: the four arrays are chunk-mapped, not hipMalloc'ed
@@ -30,6 +30,16 @@ struct wagma_ctx {
     double place_same_gbs;   // probe rate inside one region
     double place_split_gbs;  // probe rate between the regions of w and m (0 if not separated)
 };
+
+// Launch-shape switches that are not part of the public header: exported for the tests and for
+// measurements only.  wagma_debug_set_option also accepts the public WAGMA_OPT_* values.
+#define WAGMA_DEBUG_FORCE_STREAM 3   /* 0/1: the row-streaming kernel also for S = 8 */
+#define WAGMA_DEBUG_STRIPE_LOG2 7    /* 0..16: the wavefronts of a workgroup work 2^v KiB apart in every row */
+#define WAGMA_DEBUG_XCD_CHUNK_LOG2 8 /* 0..13: each XCD works on runs of 2^v consecutive column tiles of a row;
+                                        a per-tensor plan takes the value at wagma_tensors_create (its tiles are
+                                        half as long: runs of 2^(v+1), at most 256, tiles) */
+extern "C" int wagma_debug_set_option(wagma_ctx* ctx, int option, int64_t value);
+extern "C" int wagma_debug_get_option(const wagma_ctx* ctx, int option, int64_t* value);
 
 namespace wagma_detail {
 

@@ -48,8 +48,6 @@ struct StepParams {
     float members_plus_1;  // S + 1
     int members;           // S, or P in a global iteration
     int log2_chunks;       // log2(members / streamed_chunk(lag)) for the streaming kernels
-    int swizzle;           // 1: contiguous block range per XCD
-    int tile_major;        // 1: consecutive blocks walk the groups of one column tile
     int stripe_log2;       // log2 of the distance, in KiB, between a workgroup's wavefronts
     int xcd_chunk_log2;    // log2 of the run of consecutive tiles one XCD works on (0: 1 tile)
     // per-tensor layout only (device tables)
@@ -124,8 +122,8 @@ __device__ __forceinline__ V tree_sum(const V* c)
     }
 }
 
-// Where the lane's element of a rank's row lives.  Flat layout: P rows of ld floats;
-// the row base is wave-uniform (scalar registers) and the lane adds one 32-bit offset.
+// Where the lane's element of a rank's row lives.  Flat layout: P rows of ld floats; the row
+// base is wave-uniform and the lane adds its float index inside the row.
 struct FlatAddr {
     const StepParams& p;
     uint32_t lane_at;  // float index inside the row
@@ -274,55 +272,58 @@ __device__ __forceinline__ void streamed_body(const StepParams& p, const int32_t
             w_sum = stack[l];
     const V fresh = w_sum * p.inv_members;
 
-    for (int e = 0; e < p.members; ++e) {
-        const int rank = member[e];
-        if (LAG && is_busy(p, rank))
-            continue;
-        V out = fresh;
-        if (is_late(p, rank)) {
-            // W' of this member: this thread stored it to the send buffer above.
-            const V w_prime = load_v<false, V>(at.pub(rank));
-            out = (w_sum + w_prime) / p.members_plus_1;
+    // Second pass, a chunk at a time: first the send buffers of the chunk's late members are
+    // asked for (W' of such a member: this thread stored it there in the first pass), all of
+    // them before any is waited for, then the chunk's rows are stored.
+    for (int c = 0; c < chunks; ++c) {
+        int rank[kChunk];
+        bool late[kChunk], busy[kChunk];
+        V w_prime[kChunk];
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i) {
+            rank[i] = member[c * kChunk + i];
+            busy[i] = LAG && is_busy(p, rank[i]);
+            late[i] = !busy[i] && is_late(p, rank[i]);
+            if (late[i])
+                w_prime[i] = load_v<false, V>(at.pub(rank[i]));
         }
-        store_v<NT, V>(at.w(rank), out);
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i) {
+            if (busy[i])
+                continue;
+            V out = fresh;
+            if (late[i])
+                out = (w_sum + w_prime[i]) / p.members_plus_1;
+            store_v<NT, V>(at.w(rank[i]), out);
+        }
     }
 }
 
-// Which group and which 16-byte column slice does this lane own?  Workgroups are
-// handed to the 8 XCDs round-robin; with `swizzle` each XCD instead walks one
-// contiguous eighth of the work.  A wavefront always owns 64 consecutive slices
-// (1 KiB per row).  The wavefronts of workgroup `tile` sit 2^stripe_log2 KiB apart
-// and consecutive workgroups fill the gaps, so that a workgroup's simultaneous
-// requests to one row hit addresses one stripe apart (stripe_log2 = 0: the plain
+// Which group and which 16-byte column slice does this lane own?  Workgroups are handed to
+// the 8 XCDs round-robin (workgroup b runs on XCD b mod 8) and walk the column tiles of one
+// group before the next group's (the chip sweeps one group's rows at a time).  A wavefront
+// always owns 64 consecutive slices (1 KiB per row).  The wavefronts of workgroup `tile` sit
+// 2^stripe_log2 KiB apart and consecutive workgroups fill the gaps, so that a workgroup's
+// simultaneous requests to one row hit addresses one stripe apart (stripe_log2 = 0: the plain
 // contiguous tile).  Returns false for lanes and workgroups beyond the end.
-template <int BLOCK>
+constexpr int kBlock = 256;  // threads per workgroup of every step kernel
+
 __device__ __forceinline__ bool decode_block(const StepParams& p, int64_t& group, int64_t& col)
 {
-    int64_t b = blockIdx.x;
-    if (p.swizzle) {
-        const int64_t per_xcd = (p.blocks + kNumXcd - 1) / kNumXcd;
-        b = (b % kNumXcd) * per_xcd + b / kNumXcd;
-    }
+    const int64_t b = blockIdx.x;
     if (b >= p.blocks)
         return false;
-    int64_t tile;
-    if (p.tile_major) {
-        const int64_t groups = p.blocks / p.tiles;
-        group = b % groups;
-        tile = b / groups;
-    } else {
-        group = b / p.tiles;
-        tile = b % p.tiles;
-    }
+    group = b / p.tiles;
+    int64_t tile = b % p.tiles;
     if (p.xcd_chunk_log2 > 0) {
-        // Workgroup b runs on XCD b % 8.  Give each XCD runs of 2^xcd_chunk_log2 consecutive
-        // tiles: the XCD number moves from tile bits [0,3) up to bits [j, j+3).
+        // Give each XCD runs of 2^xcd_chunk_log2 consecutive tiles: the XCD number moves from
+        // tile bits [0,3) up to bits [j, j+3).
         const int j = p.xcd_chunk_log2;
         const int64_t xcd = tile & (kNumXcd - 1);
         const int64_t hi = tile >> 3;
         tile = ((hi >> j) << (j + 3)) | (xcd << j) | (hi & ((int64_t(1) << j) - 1));
     }
-    constexpr int kWavesPerBlock = BLOCK / 64;
+    constexpr int kWavesPerBlock = kBlock / 64;
     const int64_t wave = threadIdx.x >> 6;
     const int64_t lane = threadIdx.x & 63;
     const int64_t super = tile >> p.stripe_log2;
@@ -332,21 +333,23 @@ __device__ __forceinline__ bool decode_block(const StepParams& p, int64_t& group
     return col < p.nvec;
 }
 
-template <int S, bool NT, bool LAG, int BLOCK, int WAVES>
-__global__ void __launch_bounds__(BLOCK, WAVES) step_rows_in_registers(const StepParams p)
+// Resident wavefronts per SIMD the register allocation must allow: the S = 8 body holds 32
+// 128-bit values per lane (131 registers: 3 wavefronts), the smaller ones fit 4 and more.
+template <int S, bool NT, bool LAG>
+__global__ void __launch_bounds__(kBlock, S == 8 ? 2 : 4) step_rows_in_registers(const StepParams p)
 {
     int64_t group, col;
-    if (!decode_block<BLOCK>(p, group, col))
+    if (!decode_block(p, group, col))
         return;
     const FlatAddr at{p, (uint32_t)col * 4u};
     registers_body<S, NT, LAG, v4f>(p, p.table + group * S, at);
 }
 
-template <bool NT, bool LAG, int BLOCK, int WAVES>
-__global__ void __launch_bounds__(BLOCK, WAVES) step_rows_streamed(const StepParams p)
+template <bool NT, bool LAG>
+__global__ void __launch_bounds__(kBlock, 2) step_rows_streamed(const StepParams p)
 {
     int64_t group, col;
-    if (!decode_block<BLOCK>(p, group, col))
+    if (!decode_block(p, group, col))
         return;
     const FlatAddr at{p, (uint32_t)col * 4u};
     streamed_body<NT, LAG, v4f>(p, p.table + group * p.members, at);
@@ -356,8 +359,8 @@ __global__ void __launch_bounds__(BLOCK, WAVES) step_rows_streamed(const StepPar
 // names the tensor and the tile's first 16-byte slice inside it.  A lane whose slice is
 // cut off by the end of the tensor does the remaining 1..3 elements one by one; nothing
 // beyond a tensor's last element is touched.
-template <int S, bool NT, bool LAG, int BLOCK>
-__global__ void __launch_bounds__(BLOCK, 2) step_tensors_in_registers(const StepParams p)
+template <int S, bool NT, bool LAG>
+__global__ void __launch_bounds__(kBlock, 2) step_tensors_in_registers(const StepParams p)
 {
     const int64_t group = blockIdx.x / p.tiles;
     const TileRef ref = p.tile_ref[blockIdx.x % p.tiles];
@@ -377,8 +380,8 @@ __global__ void __launch_bounds__(BLOCK, 2) step_tensors_in_registers(const Step
     }
 }
 
-template <bool NT, bool LAG, int BLOCK>
-__global__ void __launch_bounds__(BLOCK, 2) step_tensors_streamed(const StepParams p)
+template <bool NT, bool LAG>
+__global__ void __launch_bounds__(kBlock, 2) step_tensors_streamed(const StepParams p)
 {
     const int64_t group = blockIdx.x / p.tiles;
     const TileRef ref = p.tile_ref[blockIdx.x % p.tiles];

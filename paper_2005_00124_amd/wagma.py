@@ -18,10 +18,11 @@ LIB_PATH = os.path.join(_PKG, "libwagma.so")
 
 WAGMA_OK, WAGMA_EINVAL, WAGMA_EHIP, WAGMA_ENOMEM = 0, -1, -2, -3
 WAGMA_MAX_P = 1024
+WAGMA_STATIC_TABLE_BYTES = 45056
 WAGMA_GROUPING_DYNAMIC, WAGMA_GROUPING_FIXED = 0, 1
-WAGMA_OPT_BLOCK, WAGMA_OPT_NONTEMPORAL, WAGMA_OPT_FORCE_STREAM = 1, 2, 3
-WAGMA_OPT_XCD_SWIZZLE, WAGMA_OPT_TILE_MAJOR, WAGMA_OPT_WAVES, WAGMA_OPT_STRIPE_LOG2 = 4, 5, 6, 7
-WAGMA_OPT_XCD_CHUNK_LOG2, WAGMA_OPT_PLACEMENT = 8, 9
+WAGMA_OPT_NONTEMPORAL, WAGMA_OPT_PLACEMENT = 2, 9
+# launch-shape switches outside the public header (csrc/wagma_internal.h): tests and measurements only
+WAGMA_DEBUG_FORCE_STREAM, WAGMA_DEBUG_STRIPE_LOG2, WAGMA_DEBUG_XCD_CHUNK_LOG2 = 3, 7, 8
 WAGMA_PLACE_PLAIN, WAGMA_PLACE_ARRAYS, WAGMA_PLACE_CHUNKS, WAGMA_PLACE_AUTO, WAGMA_PLACE_SEARCH = 0, 1, 2, 3, 4
 
 # name -> (restype, argtypes): every symbol include/wagma.h declares
@@ -70,6 +71,12 @@ SYMBOLS = {
     "wagma_last_hip_error": (ctypes.c_int, []),
 }
 
+# exported, but not declared in include/wagma.h (csrc/wagma_internal.h): tests and measurements only
+DEBUG_SYMBOLS = {
+    "wagma_debug_set_option": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64]),
+    "wagma_debug_get_option": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_int64)]),
+}
+
 _lib = None
 
 
@@ -93,7 +100,7 @@ def load() -> ctypes.CDLL:
         # library binds to the runtime that owns the tensors and streams it is handed.
         import torch  # noqa: F401
         lib = ctypes.CDLL(LIB_PATH)
-        for name, (restype, argtypes) in SYMBOLS.items():
+        for name, (restype, argtypes) in {**SYMBOLS, **DEBUG_SYMBOLS}.items():
             fn = getattr(lib, name)
             fn.restype, fn.argtypes = restype, argtypes
         _lib = lib
@@ -309,6 +316,17 @@ def wagma_set_option(ctx: int, option: int, value: int) -> None:
     _check(load().wagma_set_option(ctx, option, value), "wagma_set_option")
 
 
+def wagma_debug_set_option(ctx: int, option: int, value: int) -> None:
+    """Launch-shape switches outside the public header; also takes the public options."""
+    _check(load().wagma_debug_set_option(ctx, option, value), "wagma_debug_set_option")
+
+
+def wagma_debug_get_option(ctx: int, option: int) -> int:
+    value = ctypes.c_int64()
+    _check(load().wagma_debug_get_option(ctx, option, ctypes.byref(value)), "wagma_debug_get_option")
+    return int(value.value)
+
+
 # ---- convenience wrapper ------------------------------------------------------
 
 class Wagma:
@@ -330,6 +348,12 @@ class Wagma:
 
     def set_option(self, option: int, value: int) -> None:
         wagma_set_option(self.ctx, option, value)
+
+    def debug_set_option(self, option: int, value: int) -> None:
+        wagma_debug_set_option(self.ctx, option, value)
+
+    def debug_get_option(self, option: int) -> int:
+        return wagma_debug_get_option(self.ctx, option)
 
     @property
     def period(self) -> int:

@@ -222,17 +222,28 @@ def fill_gradients(wl: Workload, t: int, g: torch.Tensor) -> None:
         g[p, :n].normal_(0.0, wl.grad_std, generator=gen)
 
 
-def sample_columns(n: int, count: int, seed: int, tile: int = 4096) -> torch.Tensor:
-    """A sorted int64 column set for sampled parity: both ends of the row (with the
-    ragged tail), columns on each side of multiples of ``tile``, and a seeded random rest."""
-    cols = set(range(min(n, 256)))
-    cols.update(range(max(0, n - 256), n))
+def sample_columns(n: int, count: int, seed: int, tile: int = 4096, tensor_sizes=None,
+                   ends: int = 256) -> torch.Tensor:
+    """A sorted int64 column set for sampled parity: ``ends`` columns at both ends of the row
+    (with the ragged tail), columns on each side of multiples of ``tile``, the first and last
+    four columns of every tensor of the flattened model (``tensor_sizes``: their lengths in
+    row order), and a seeded random rest up to ``count`` columns."""
+    cols = set(range(min(n, ends)))
+    cols.update(range(max(0, n - ends), n))
     gen = torch.Generator()
     gen.manual_seed(seed)
     if n > tile:
         edges = torch.randint(1, max(2, n // tile), (32,), generator=gen) * tile
         for e in edges.tolist():
             cols.update(c for c in range(e - 4, e + 4) if 0 <= c < n)
+    if tensor_sizes is not None:
+        at = 0
+        for size in tensor_sizes:
+            cols.update(c for c in range(at, min(at + 4, at + size)))
+            cols.update(c for c in range(max(at, at + size - 4), at + size))
+            at += size
+        if at != n:
+            raise ValueError("tensor sizes do not add up to n")
     need = max(0, count - len(cols))
     if need:
         cols.update(torch.randint(0, n, (need,), generator=gen).tolist())

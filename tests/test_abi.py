@@ -36,12 +36,23 @@ def test_every_declared_symbol_is_exported_and_bound(lib):
 def test_header_constants_match_binding():
     text = open(os.path.join(ROOT, "include", "wagma.h")).read()
     for name in ("WAGMA_OK", "WAGMA_EINVAL", "WAGMA_EHIP", "WAGMA_ENOMEM", "WAGMA_MAX_P",
-                 "WAGMA_GROUPING_DYNAMIC", "WAGMA_GROUPING_FIXED", "WAGMA_OPT_BLOCK", "WAGMA_OPT_NONTEMPORAL", "WAGMA_OPT_FORCE_STREAM",
-                 "WAGMA_OPT_XCD_SWIZZLE", "WAGMA_OPT_TILE_MAJOR", "WAGMA_OPT_WAVES",
-                 "WAGMA_OPT_STRIPE_LOG2", "WAGMA_OPT_XCD_CHUNK_LOG2", "WAGMA_OPT_PLACEMENT",
+                 "WAGMA_GROUPING_DYNAMIC", "WAGMA_GROUPING_FIXED", "WAGMA_OPT_NONTEMPORAL", "WAGMA_OPT_PLACEMENT",
+                 "WAGMA_STATIC_TABLE_BYTES",
                  "WAGMA_PLACE_PLAIN", "WAGMA_PLACE_ARRAYS", "WAGMA_PLACE_CHUNKS", "WAGMA_PLACE_AUTO", "WAGMA_PLACE_SEARCH"):
         value = re.search(r"#define\s+%s\s+\(?(-?\d+)\)?" % name, text).group(1)
         assert int(value) == getattr(libwagma, name), name
+
+
+def test_debug_switches_are_exported_but_not_in_the_public_header(lib):
+    text = open(os.path.join(ROOT, "include", "wagma.h")).read()
+    internal = open(os.path.join(ROOT, "paper_2005_00124_amd", "csrc", "wagma_internal.h")).read()
+    for name in libwagma.DEBUG_SYMBOLS:
+        assert hasattr(lib, name) and name not in text and name in internal
+    for name in ("WAGMA_DEBUG_FORCE_STREAM", "WAGMA_DEBUG_STRIPE_LOG2", "WAGMA_DEBUG_XCD_CHUNK_LOG2"):
+        value = re.search(r"#define\s+%s\s+(\d+)" % name, internal).group(1)
+        assert int(value) == getattr(libwagma, name) and name not in text
+    assert lib.wagma_debug_set_option(None, 3, 1) == libwagma.WAGMA_EINVAL
+    assert lib.wagma_debug_get_option(None, 3, None) == libwagma.WAGMA_EINVAL
 
 
 def test_host_side_argument_checks(lib):
@@ -57,7 +68,8 @@ def test_host_side_argument_checks(lib):
     assert lib.wagma_schedule_period(None) == libwagma.WAGMA_EINVAL
     assert lib.wagma_is_global_iteration(None, 0) == libwagma.WAGMA_EINVAL
     assert lib.wagma_step(None, None, None, None, None, None, 0.1, 0.9, 0, None) == libwagma.WAGMA_EINVAL
-    assert lib.wagma_set_option(None, 1, 256) == libwagma.WAGMA_EINVAL
+    assert lib.wagma_set_option(None, 2, 1) == libwagma.WAGMA_EINVAL
+    assert lib.wagma_step_static(4, 2, 16, 0, 16, None, None, None, None, None, 0.1, 0.9, 0, None) == libwagma.WAGMA_EINVAL
     assert lib.wagma_set_grouping(None, 0) == libwagma.WAGMA_EINVAL
     assert lib.wagma_tensors_create(None, None, 1, None, None, None, None, None) == libwagma.WAGMA_EINVAL
     assert lib.wagma_tensors_destroy(None) == libwagma.WAGMA_OK

@@ -12,7 +12,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def run_bench(*extra):
     out = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--workload", "1", "--steps", "10",
-                          "--warmup", "2", "--cpu-columns", "4096", *extra],
+                          "--warmup", "2", "--cpu-columns", "8192", "--cpu-workers", "2", *extra],
                          capture_output=True, text=True, cwd=ROOT, timeout=600)
     assert out.returncode == 0, out.stderr[-2000:]
     lines = [l for l in out.stdout.splitlines() if l.strip()]
@@ -33,4 +33,7 @@ def test_bench_json_contract():
     assert r["bound"] == "hbm" and r["peak"] == 8000.0 and r["unit"] == "GB/s"
     assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-9
     c = d["cpu_baseline"]
-    assert c["kind"] == "oracle" and c["cores"] == 1 and c["value"] > 0 and c["sample"]
+    assert c["kind"] == "oracle" and c["cores"] == 1 and c["value"] > 0 and c["sample"] and c["cpu_model"]
+    a = c["all_cores"]
+    assert a["cores"] == 2 and a["value"] > 0 and a["sample"] and a["cpu_model"]
+    assert r["traffic"] is None and r["traffic_source"] is None      # no counter run stored for workload 1

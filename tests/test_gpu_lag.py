@@ -61,10 +61,9 @@ def test_step_lag_random_masks(P, S, n, tau):
 
 
 @pytest.mark.parametrize("options", [
-    ((lw.WAGMA_OPT_BLOCK, 256), (lw.WAGMA_OPT_WAVES, 4)),
-    ((lw.WAGMA_OPT_BLOCK, 512), (lw.WAGMA_OPT_WAVES, 2)),
-    ((lw.WAGMA_OPT_NONTEMPORAL, 0), (lw.WAGMA_OPT_STRIPE_LOG2, 0), (lw.WAGMA_OPT_XCD_CHUNK_LOG2, 0)),
-    ((lw.WAGMA_OPT_FORCE_STREAM, 1), (lw.WAGMA_OPT_WAVES, 3)),
+    ((lw.WAGMA_OPT_NONTEMPORAL, 1),),
+    ((lw.WAGMA_OPT_NONTEMPORAL, 0), (lw.WAGMA_DEBUG_STRIPE_LOG2, 0), (lw.WAGMA_DEBUG_XCD_CHUNK_LOG2, 0)),
+    ((lw.WAGMA_DEBUG_FORCE_STREAM, 1), (lw.WAGMA_DEBUG_STRIPE_LOG2, 3)),
 ])
 def test_step_lag_launch_options(options):
     """The other launch shapes of the same kernels, S = 8 (in registers and streamed)."""
@@ -73,7 +72,7 @@ def test_step_lag_launch_options(options):
     rng = np.random.default_rng(17)
     with lw.Wagma(P, S, n, tau) as ctx:
         for opt, val in options:
-            ctx.set_option(opt, val)
+            ctx.debug_set_option(opt, val)
         w, g, m, pub, gen = random_state(P, ctx.ld, n, 5)
         ow, om, opub = (x.cpu().numpy().copy() for x in (w, m, pub))
         for t in range(7):
@@ -205,17 +204,13 @@ def test_seeded_random_configurations():
         fixed = bool(rng.integers(0, 2))
         options = []
         if rng.integers(0, 2):
-            options.append((lw.WAGMA_OPT_BLOCK, int(rng.choice([256, 512]))))
-        if rng.integers(0, 2):
-            options.append((lw.WAGMA_OPT_WAVES, int(rng.choice([2, 3, 4]))))
-        if rng.integers(0, 2):
             options.append((lw.WAGMA_OPT_NONTEMPORAL, int(rng.integers(0, 2))))
         if rng.integers(0, 2):
-            options.append((lw.WAGMA_OPT_STRIPE_LOG2, int(rng.integers(0, 5))))
+            options.append((lw.WAGMA_DEBUG_STRIPE_LOG2, int(rng.integers(0, 5))))
         if rng.integers(0, 2):
-            options.append((lw.WAGMA_OPT_XCD_CHUNK_LOG2, int(rng.integers(0, 5))))
+            options.append((lw.WAGMA_DEBUG_XCD_CHUNK_LOG2, int(rng.integers(0, 5))))
         if rng.integers(0, 3) == 0:
-            options.append((lw.WAGMA_OPT_FORCE_STREAM, 1))
+            options.append((lw.WAGMA_DEBUG_FORCE_STREAM, 1))
         pad = int(rng.integers(0, 3)) * 4
         say("random case %d: P=%d S=%d n=%d tau=%d fixed=%s pad=%d options=%s"
             % (case, P, S, n, tau, fixed, pad, options))
@@ -223,7 +218,7 @@ def test_seeded_random_configurations():
             if pad:
                 ctx.set_row_stride((n + 3) // 4 * 4 + pad)
             for opt, val in options:
-                ctx.set_option(opt, val)
+                ctx.debug_set_option(opt, val)
             if fixed:
                 ctx.set_grouping(lw.WAGMA_GROUPING_FIXED)
             w, g, m, pub, gen = random_state(P, ctx.ld, n, 1000 + case)

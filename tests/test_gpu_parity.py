@@ -52,7 +52,7 @@ def run_case(P, S, n, tau, iters, q, seed, options=(), ld=None, t0=0, fixed_grou
         if ld is not None:
             ctx.set_row_stride(ld)
         for opt, val in options:
-            ctx.set_option(opt, val)
+            ctx.debug_set_option(opt, val)
         if fixed_groups:
             ctx.set_grouping(lw.WAGMA_GROUPING_FIXED)
         ld = ctx.ld
@@ -169,22 +169,17 @@ def test_step_row_stride_variants():
 
 
 OPTION_SETS = [
-    ((lw.WAGMA_OPT_BLOCK, 512),),
-    ((lw.WAGMA_OPT_BLOCK, 256),),
     ((lw.WAGMA_OPT_NONTEMPORAL, 0),),
-    ((lw.WAGMA_OPT_FORCE_STREAM, 1),),
-    ((lw.WAGMA_OPT_XCD_SWIZZLE, 1),),
-    ((lw.WAGMA_OPT_TILE_MAJOR, 1),),
-    ((lw.WAGMA_OPT_WAVES, 2),),
-    ((lw.WAGMA_OPT_WAVES, 4),),
-    ((lw.WAGMA_OPT_STRIPE_LOG2, 3),),
-    ((lw.WAGMA_OPT_XCD_CHUNK_LOG2, 1),),
-    ((lw.WAGMA_OPT_XCD_CHUNK_LOG2, 8), (lw.WAGMA_OPT_STRIPE_LOG2, 2), (lw.WAGMA_OPT_BLOCK, 512)),
-    ((lw.WAGMA_OPT_XCD_CHUNK_LOG2, 13), (lw.WAGMA_OPT_FORCE_STREAM, 1)),
-    ((lw.WAGMA_OPT_STRIPE_LOG2, 6), (lw.WAGMA_OPT_BLOCK, 512)),
-    ((lw.WAGMA_OPT_STRIPE_LOG2, 16), (lw.WAGMA_OPT_XCD_SWIZZLE, 1)),
-    ((lw.WAGMA_OPT_BLOCK, 512), (lw.WAGMA_OPT_XCD_SWIZZLE, 1), (lw.WAGMA_OPT_TILE_MAJOR, 1),
-     (lw.WAGMA_OPT_FORCE_STREAM, 1), (lw.WAGMA_OPT_WAVES, 4), (lw.WAGMA_OPT_NONTEMPORAL, 0)),
+    ((lw.WAGMA_OPT_NONTEMPORAL, 1),),
+    ((lw.WAGMA_DEBUG_FORCE_STREAM, 1),),
+    ((lw.WAGMA_DEBUG_STRIPE_LOG2, 0), (lw.WAGMA_DEBUG_XCD_CHUNK_LOG2, 0)),
+    ((lw.WAGMA_DEBUG_STRIPE_LOG2, 3),),
+    ((lw.WAGMA_DEBUG_XCD_CHUNK_LOG2, 1),),
+    ((lw.WAGMA_DEBUG_XCD_CHUNK_LOG2, 8), (lw.WAGMA_DEBUG_STRIPE_LOG2, 2)),
+    ((lw.WAGMA_DEBUG_XCD_CHUNK_LOG2, 13), (lw.WAGMA_DEBUG_FORCE_STREAM, 1)),
+    ((lw.WAGMA_DEBUG_STRIPE_LOG2, 6),),
+    ((lw.WAGMA_DEBUG_STRIPE_LOG2, 16), (lw.WAGMA_DEBUG_XCD_CHUNK_LOG2, 3)),
+    ((lw.WAGMA_DEBUG_FORCE_STREAM, 1), (lw.WAGMA_OPT_NONTEMPORAL, 0), (lw.WAGMA_DEBUG_STRIPE_LOG2, 1)),
 ]
 
 
@@ -274,12 +269,18 @@ def test_errors_leave_buffers_alone():
         assert lib.wagma_step(ctx.ctx, ptrs[0] + 4, ptrs[1], ptrs[2], ptrs[3], None, LR, MU, 0, None) == lw.WAGMA_EINVAL
         assert lib.wagma_step(ctx.ctx, ptrs[0], None, ptrs[2], ptrs[3], None, LR, MU, 0, None) == lw.WAGMA_EINVAL
         assert lib.wagma_step(ctx.ctx, ptrs[0], ptrs[1], ptrs[2], ptrs[3], None, LR, MU, -1, None) == lw.WAGMA_EINVAL
+        # arrays that overlap: the same array twice, and an array that begins inside another
+        assert lib.wagma_step(ctx.ctx, ptrs[0], ptrs[1], ptrs[0], ptrs[3], None, LR, MU, 0, None) == lw.WAGMA_EINVAL
+        assert lib.wagma_step(ctx.ctx, ptrs[0], ptrs[0] + 16 * ctx.ld, ptrs[2], ptrs[3], None, LR, MU, 0, None) == lw.WAGMA_EINVAL
+        assert lib.wagma_step_static(P, S, n, 3, ctx.ld, ptrs[0], ptrs[1], ptrs[2], ptrs[2], None, LR, MU, 0, None) == lw.WAGMA_EINVAL
         with pytest.raises(lw.WagmaError):
             ctx.set_row_stride(n - 4)
         with pytest.raises(lw.WagmaError):
             ctx.set_row_stride(n + 1)
         with pytest.raises(lw.WagmaError):
-            ctx.set_option(lw.WAGMA_OPT_BLOCK, 100)
+            ctx.set_option(lw.WAGMA_DEBUG_STRIPE_LOG2, 1)      # not a public option
+        with pytest.raises(lw.WagmaError):
+            ctx.debug_set_option(lw.WAGMA_DEBUG_STRIPE_LOG2, 17)
         with pytest.raises(ValueError):
             ctx.step(w[:, :-4], g, m, pub, None, LR, MU, 0)
         torch.cuda.synchronize()
@@ -371,13 +372,54 @@ def test_workload_1_full_tensors():
                     assert torch.equal(w[int(grp[0]), :n], w[int(grp[1]), :n])
 
 
-def sampled_parity(index, iters=None, count=40000, placed=False):
+ORACLE_THREADS = 8      # the sample is cut into column shards (columns are independent of one
+                        # another); the single-threaded oracle runs on the shards side by side
+
+
+def same_bits_on_device(a, b):
+    return torch.equal(a.view(torch.int32), b.view(torch.int32))
+
+
+def whole_tensor_group_checks(ctx, wl, t, mask, w, g, m, pub, m_before, pub_before):
+    """Properties that hold for the whole tensors after a group iteration, checked on the device:
+    members of a group that were in time hold bit-identical rows (everyone of them received
+    sum * 1/S: Algorithm 2 lines 10-11); and no 16-byte slice of the momentum or of the send
+    buffer of any row kept its old bits where the gradient is not zero (a slice the kernel had
+    skipped would)."""
+    P, S, n = wl.P, wl.S, wl.n
+    _, host = ctx.group_schedule(t)
+    late = [bool((int(mask[r >> 6]) >> (r & 63)) & 1) for r in range(P)]
+    for grp in host.reshape(-1, S):
+        in_time = [int(r) for r in grp if not late[int(r)]]
+        for r in in_time[1:]:
+            assert same_bits_on_device(w[r, :n], w[in_time[0], :n]), \
+                "members %d and %d of a group differ after iteration %d" % (in_time[0], r, t)
+    n4 = n // 4 * 4
+    for new, old, what in ((m, m_before, "momentum"), (pub, pub_before, "send buffer")):
+        stale = ((new[:, :n4].view(torch.int32) == old[:, :n4].view(torch.int32)) & (g[:, :n4] != 0))
+        whole = stale.view(P, n4 // 4, 4).all(dim=2)
+        assert not bool(whole.any()), "%s: a 16-byte slice kept its old bits in iteration %d" % (what, t)
+        # single elements may keep their bits: an update below half an ulp of the value is
+        # rounded away (about one element in 10^4 at these scales)
+        assert int(stale.sum()) <= 1e-3 * P * n, what
+
+
+def sampled_parity(index, iters=None, count=40000, placed=False, whole_tensor=False):
     """Full-size run in bench.py's launch configuration; the oracle follows a column sample
-    (columns are independent of one another) through every iteration."""
+    (columns are independent of one another) through every iteration: both ends of the row,
+    tile edges, the first and last columns of every tensor of the model, a seeded random rest.
+    whole_tensor: also the on-device properties of whole_tensor_group_checks after every group
+    iteration."""
+    import math
+    from concurrent.futures import ThreadPoolExecutor
     wl = wk.workload(index)
     iters = wl.iters if iters is None else iters
-    say("workload %d sampled: %s, %d iterations, %d columns" % (index, wl.name, iters, count))
     P, S, n = wl.P, wl.S, wl.n
+    sizes = [math.prod(shape) for _, shape, *_ in wl.tensors()]
+    cols = wk.sample_columns(n, count, wl.seed, tensor_sizes=sizes, ends=4096)
+    say("workload %d sampled: %s, %d iterations, %d columns (%d tensors)"
+        % (index, wl.name, iters, cols.numel(), len(sizes)))
+    pool = ThreadPoolExecutor(max_workers=ORACLE_THREADS)
     with lw.Wagma(P, S, n, wl.tau) as ctx:
         if placed:
             w, g, m, pub = ctx.alloc_placed()
@@ -387,51 +429,73 @@ def sampled_parity(index, iters=None, count=40000, placed=False):
         else:
             w, g, m, pub = ctx.alloc()
         wk.fill_initial_state(wl, w, m, pub)
-        cols = wk.sample_columns(n, count, wl.seed).cuda()
-        ow, om, opub = (np.ascontiguousarray(x[:, cols].cpu().numpy()) for x in (w, m, pub))
-        w64, m64, pub64 = (x.astype(np.float64) for x in (ow, om, opub))
+        cols = cols.cuda()
+        cuts = np.linspace(0, cols.numel(), ORACLE_THREADS + 1).astype(int)
+        parts = [slice(int(a), int(b)) for a, b in zip(cuts[:-1], cuts[1:]) if b > a]
+
+        def shards(x):
+            host = x[:, cols].cpu().numpy()
+            return [np.ascontiguousarray(host[:, part]) for part in parts]
+        ow, om, opub = shards(w), shards(m), shards(pub)
+        # the fp64 shadow follows the first shard (both ends of the row are spread over the shards)
+        w64, m64, pub64 = (x[0].astype(np.float64) for x in (ow, om, opub))
         worst = 0.0
         for t in range(iters):
             wk.fill_gradients(wl, t, g)
-            og = np.ascontiguousarray(g[:, cols].cpu().numpy())
+            og = shards(g)
             mask = ctx.stale_mask(wl.seed, t, wl.stale_threshold)
             assert np.array_equal(mask, orc.stale_mask(wl.seed, t, P, wl.stale_threshold))
             _, host = ctx.group_schedule(t)
             if not ctx.is_global(t):
                 assert np.array_equal(host, orc.member_table(P, S, t).ravel())
+            check_whole = whole_tensor and not ctx.is_global(t)
+            if check_whole:
+                m_before, pub_before = m.clone(), pub.clone()
             ctx.step(w, g, m, pub, mask, wl.lr, wl.mu, t)
-            orc.step_f32(P, S, wl.tau, t, ow, og, om, opub, mask, wl.lr, wl.mu)
-            orc.step_f64(P, S, wl.tau, t, w64, og.astype(np.float64), m64, pub64, mask,
-                         float(np.float32(wl.lr)), float(np.float32(wl.mu)))
+
+            def follow(k):
+                orc.step_f32(P, S, wl.tau, t, ow[k], og[k], om[k], opub[k], mask, wl.lr, wl.mu)
+                if k == 0:
+                    orc.step_f64(P, S, wl.tau, t, w64, og[0].astype(np.float64), m64, pub64, mask,
+                                 float(np.float32(wl.lr)), float(np.float32(wl.mu)))
+            list(pool.map(follow, range(len(parts))))
             torch.cuda.synchronize()
             for have, want, what in ((w, ow, "w"), (m, om, "m"), (pub, opub, "pub")):
-                assert_same_bits(have[:, cols].cpu().numpy(), want, "%s at t=%d" % (what, t))
-            worst = max(worst, float(np.abs(ow - w64).max() / np.abs(w64).max()))
+                got = have[:, cols].cpu().numpy()
+                for k, part in enumerate(parts):
+                    assert_same_bits(got[:, part], want[k], "%s at t=%d (column shard %d)" % (what, t, k))
+            worst = max(worst, float(np.abs(ow[0] - w64).max() / np.abs(w64).max()))
             # properties of the whole tensors
             if ctx.is_global(t):
                 assert bool((w[:, :n] == w[:1, :n]).all()), "replicas differ after a global average"
+            if check_whole:
+                whole_tensor_group_checks(ctx, wl, t, mask, w, g, m, pub, m_before, pub_before)
+                del m_before, pub_before
         say("workload %d: bit-exact on %d columns x %d iterations; |f32-f64|/max|w| <= %.2e"
             % (index, cols.numel(), iters, worst))
         assert worst <= 1e-6
         del w, g, m, pub
+    pool.shutdown()
     torch.cuda.empty_cache()
 
 
 def test_workload_2_sampled():
-    sampled_parity(2)
+    sampled_parity(2, count=200000, whole_tensor=True)
 
 
 def test_workload_3_sampled():
-    sampled_parity(3)
+    sampled_parity(3, count=200000, whole_tensor=True)
 
 
 def test_workload_4_sampled():
-    sampled_parity(4)
+    """The headline workload on caller-owned (torch) arrays: about a million columns, and the
+    whole-tensor properties after every group iteration (the S = 8 kernel in registers)."""
+    sampled_parity(4, count=1 << 20, whole_tensor=True)
 
 
 def test_workload_4_sampled_library_allocator():
     """The configuration bench.py times: arrays placed by wagma_alloc_buffers."""
-    sampled_parity(4, placed=True)
+    sampled_parity(4, count=1 << 20, placed=True, whole_tensor=True)
 
 
 @pytest.mark.parametrize("mode", [lw.WAGMA_PLACE_CHUNKS, lw.WAGMA_PLACE_ARRAYS, lw.WAGMA_PLACE_SEARCH,
@@ -464,7 +528,7 @@ def test_every_placement_mode_gives_the_same_bits(mode):
 
 
 def test_workload_5_sampled():
-    sampled_parity(5, count=20000)
+    sampled_parity(5, count=200000, whole_tensor=True)
 
 
 def test_longest_row():

@@ -77,3 +77,24 @@ def test_lateness_masks_of_the_workloads_are_frozen():
     spec.loader.exec_module(mod)
     stored = open(os.path.join(here, "golden", "lateness_masks.txt")).read().split("\n")
     assert [x for x in stored if x] == list(mod.lines())
+
+
+def test_stored_traffic_figures_are_those_of_the_profiles():
+    """bench.py's roofline.traffic constants are copies of figures under profiles/: each must
+    equal the number its file states, and the launch options they were taken with likewise."""
+    import os
+    import re
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    sys.path.insert(0, root)
+    import bench
+    for table in (bench.MEASURED_TRAFFIC, bench.MEASURED_TRAFFIC_PER_TENSOR):
+        for index, (nbytes, name) in table.items():
+            text = open(os.path.join(root, "profiles", name)).read()
+            stated = re.search(r"traffic_bytes_per_launch = ([0-9.e+]+)", text)
+            assert stated and float(stated.group(1)) == nbytes, name
+            options = re.search(r"launch options of these runs: ([a-z0-9_= ]+)\)", text)
+            assert options, name
+            have = dict(kv.split("=") for kv in options.group(1).split())
+            assert {k: int(v) for k, v in have.items()} == bench.PROFILE_OPTIONS, name
+            assert set(bench.PROFILE_OPTIONS) <= set(bench.OPTS)
