@@ -354,8 +354,7 @@ def main() -> int:
         # HBM bytes of such a launch as the counters measured them in the profiled run; stale
         # (hence left out) as soon as the library's launch defaults differ from that run's
         roofline["traffic"] = stored[0]
-        roofline["traffic_source"] = "profiles/" + stored[1]
-        roofline["traffic_gbs"] = stored[0] / (roofline["avg_launch_ms"] * 1e-3) / 1e9
+        roofline["traffic_source"] = "profiles/" + stored[1] + " (counter runs of that file, not of this run)"
     out = {
         "metric": "replica-params averaged/sec", "value": P * n * K / wall, "unit": "replica-params/s",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": wall * 1e3 / K,
