@@ -10,9 +10,10 @@ the timed region.  Prints ONE JSON line on stdout; progress goes to stderr.
 
 The default run times the headline workload (4: P=64, S=8, 25.6M parameters) on arrays placed by
 the library's allocator, then the same steps on ordinary torch allocations ("plain_alloc": what
-a caller who brings its own buffers gets), then the other four seeded workloads in child
-processes ("workloads"), then the CPU oracle on the host cores ("cpu_baseline").  --no-extras
-stops after the headline run.
+a caller who brings its own buffers gets), then measures the HBM traffic of the group launches
+with the counters (two child runs under rocprofv3: "roofline.traffic"), then the other four
+seeded workloads in child processes ("workloads"), then the CPU oracle on the host cores
+("cpu_baseline").  --no-extras stops after the headline run.
 """
 from __future__ import annotations
 
@@ -158,6 +159,54 @@ def cpu_baseline(wl, columns: int, iters: int, workers: int):
     return out
 
 
+# ---------------------------------------------------------------- HBM traffic from the counters
+
+def measure_traffic(workload: int, K: int, W: int, array_bytes: int):
+    """HBM bytes per group launch of this very command, measured now: two child runs of the
+    headline part of this script under `rocprofv3 --pmc` (FETCH_SIZE, then WRITE_SIZE, each in a
+    run of its own), each counter scaled by what it reads for the plain device copy of one whole
+    array (`array_bytes`) in the same run.  Returns a dict, or None if the profiler is not there
+    or a run fails."""
+    import csv
+    import glob
+    import shutil
+    import tempfile
+    if shutil.which("rocprofv3") is None:
+        return None
+    per_launch, factors = {}, {}
+    for counter in ("FETCH_SIZE", "WRITE_SIZE"):
+        out_dir = tempfile.mkdtemp(prefix="wagma_pmc_", dir="/tmp")
+        cmd = ["rocprofv3", "--kernel-trace", "--pmc", counter, "--output-format", "csv", "-d", out_dir, "--",
+               sys.executable, os.path.abspath(__file__), "--workload", str(workload), "--no-extras",
+               "--no-cpu-baseline", "--steps", str(K), "--warmup", str(W)]
+        try:
+            run = subprocess.run(cmd, cwd="/tmp", env=dict(os.environ, TMPDIR="/tmp"), capture_output=True,
+                                 text=True, timeout=300)
+            files = glob.glob(os.path.join(out_dir, "**", "*_counter_collection.csv"), recursive=True)
+            if run.returncode != 0 or not files:
+                return None
+            steps, copies = [], []
+            for row in csv.DictReader(open(files[0])):
+                if row["Counter_Name"] != counter:
+                    continue
+                nbytes = float(row["Counter_Value"]) * 1024.0          # the counters are in KiB
+                if "step_rows" in row["Kernel_Name"] or "step_tensors" in row["Kernel_Name"]:
+                    steps.append((row["Kernel_Name"], nbytes))
+                elif "copyBuffer" in row["Kernel_Name"]:
+                    copies.append(nbytes)
+            timed = [b for name, b in steps[-K:] if "in_registers" in name]      # the group launches
+            if not timed or not copies or max(copies) <= 0:
+                return None
+            factors[counter] = array_bytes / max(copies)
+            per_launch[counter] = sum(timed) / len(timed)
+        except (OSError, subprocess.TimeoutExpired, KeyError, ValueError):
+            return None
+        finally:
+            shutil.rmtree(out_dir, ignore_errors=True)
+    return {"bytes": factors["FETCH_SIZE"] * per_launch["FETCH_SIZE"] + factors["WRITE_SIZE"] * per_launch["WRITE_SIZE"],
+            "fetch_factor": factors["FETCH_SIZE"], "write_factor": factors["WRITE_SIZE"]}
+
+
 # ---------------------------------------------------------------- GPU timing
 
 def time_steps(step, stream, K, graph=False):
@@ -218,6 +267,9 @@ def main() -> int:
                          "wagma_step_lag instead of the workload's Bernoulli mask")
     ap.add_argument("--no-extras", action="store_true",
                     help="the headline run only: no plain-allocation leg, no other workloads")
+    ap.add_argument("--no-counters", action="store_true",
+                    help="do not run the two rocprofv3 child runs that measure roofline.traffic (the figure "
+                         "stored under profiles/ is reported instead)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-columns", type=int, default=1048576)
     ap.add_argument("--cpu-workers", type=int, default=None,
@@ -394,6 +446,18 @@ def main() -> int:
                               "frac": p_gbs / HBM_PEAK_GBS, "launches": len(dom_ts)}
     ctx.destroy()
     torch.cuda.empty_cache()
+
+    if extras and not args.no_counters:
+        log("HBM traffic of the group launches from the counters (two profiler runs of this command) ...")
+        measured = measure_traffic(wl.index, K, W, P * ld * 4)
+        if measured is not None:
+            roofline["traffic"] = measured["bytes"]
+            roofline["traffic_source"] = (
+                "measured now: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, each in a child run of this command "
+                "(--no-extras), average over its %d group launches, scaled by %.3f and %.3f (what each counter "
+                "reads for the device copy of one %d-byte array in the same run)"
+                % (len(dom_ts), measured["fetch_factor"], measured["write_factor"], P * ld * 4))
+            roofline["traffic_gbs"] = measured["bytes"] / (roofline["avg_launch_ms"] * 1e-3) / 1e9
 
     if extras:
         summary = {wl.index: {"workload": wl.name, "value": out["value"], "ms_per_step": out["ms_per_step"],
