@@ -13,13 +13,16 @@
 // wavefront's accesses are 1 KiB contiguous per row.  The step is bound by HBM
 // bandwidth (about 0.25 flop per byte): no matrix cores are involved.
 //
-// Two kernels cover all group sizes:
-//   step_rows_in_registers<S>  S <= 8 member rows are held in registers
+// Three kernels cover all group sizes:
+//   step_rows_in_registers<S>  S <= 8 member rows are held in registers by one wavefront
 //                              (3*S independent 128-bit loads in flight per lane).
-//   step_rows_streamed         any S >= 8: member rows are streamed 8 at a time (4 when
-//                              some processes are still computing), the partial sums
-//                              kept on a pairwise stack; late members re-read their own
-//                              W' from the send buffer they just wrote (an L2 hit).
+//   step_rows_cooperative      S = 16, 32, 64: the S/8 wavefronts of a workgroup hold 8 rows
+//                              each in the same way; the octets' sums meet in LDS.
+//   step_rows_streamed         larger S (and the per-tensor layout from S = 16): member rows
+//                              are streamed 8 at a time (4 when some processes are still
+//                              computing), the partial sums kept on a pairwise stack; late
+//                              members re-read their own W' from the send buffer they just
+//                              wrote (an L2 hit).
 // The global average (Algorithm 2 lines 15-16) is the same computation with
 // one group of all P ranks in natural order and nobody late.  The same bodies serve the
 // per-tensor layout (step_tensors_*) through an address functor, and each kernel has a
@@ -127,12 +130,22 @@ void set_defaults(wagma_ctx* ctx, int P, int S, int G, int g, int64_t n, int tau
 }
 
 // LAG: the kernels that also look at the busy mask (chosen only when a bit of it is set).
+enum class FlatKernel { in_registers, cooperative, streamed };
+
 template <bool NT, bool LAG>
-void launch_flat(const StepParams& p, bool streamed, unsigned grid, hipStream_t stream)
+void launch_flat(const StepParams& p, FlatKernel kind, unsigned grid, hipStream_t stream)
 {
     const dim3 g(grid), b(kBlock);
-    if (streamed) {
+    if (kind == FlatKernel::streamed) {
         hipLaunchKernelGGL((step_rows_streamed<NT, LAG>), g, b, 0, stream, p);
+        return;
+    }
+    if (kind == FlatKernel::cooperative) {
+        switch (p.members) {
+        case 16: hipLaunchKernelGGL((step_rows_cooperative<2, NT, LAG>), g, dim3(128), 0, stream, p); break;
+        case 32: hipLaunchKernelGGL((step_rows_cooperative<4, NT, LAG>), g, dim3(256), 0, stream, p); break;
+        default: hipLaunchKernelGGL((step_rows_cooperative<8, NT, LAG>), g, dim3(512), 0, stream, p); break;
+        }
         return;
     }
     switch (p.members) {
@@ -249,8 +262,12 @@ int step_flat(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub, co
     p.ld = ctx->ld;
     p.nvec = (ctx->n + 3) / 4;
 
-    const bool streamed = p.members > kRegisterRows || (ctx->opt_force_stream && p.members == kRegisterRows);
-    p.log2_chunks = streamed ? exact_log2(p.members / streamed_chunk(lag)) : 0;
+    FlatKernel kind = FlatKernel::in_registers;
+    if (p.members > kCooperativeRows || (ctx->opt_force_stream && p.members >= kRegisterRows))
+        kind = FlatKernel::streamed;
+    else if (p.members > kRegisterRows)
+        kind = FlatKernel::cooperative;
+    p.log2_chunks = kind == FlatKernel::streamed ? exact_log2(p.members / streamed_chunk(lag)) : 0;
     p.stripe_log2 = ctx->opt_stripe_log2;
     p.xcd_chunk_log2 = ctx->opt_xcd_chunk_log2;
     // tiles is rounded up to whole stripes and whole XCD rounds (the surplus lanes find col >= nvec)
@@ -258,8 +275,12 @@ int step_flat(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub, co
     int round_log2 = p.stripe_log2;
     if (p.xcd_chunk_log2 > 0 && p.xcd_chunk_log2 + 3 > round_log2)
         round_log2 = p.xcd_chunk_log2 + 3;
+    if (kind == FlatKernel::cooperative && round_log2 < 3)
+        round_log2 = 3;  // its workgroups take the tiles in rounds of 8
     p.tiles = ((p.tiles + (int64_t(1) << round_log2) - 1) >> round_log2) << round_log2;
     p.blocks = (int64_t)(ctx->P / p.members) * p.tiles;
+    if (kind == FlatKernel::cooperative)
+        p.blocks *= 4;  // one workgroup per 1 KiB piece of a row instead of per 4 KiB tile
     const int64_t grid = p.blocks;
     if (grid > 0x7fffffff)
         return WAGMA_EINVAL;
@@ -267,14 +288,14 @@ int step_flat(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub, co
     const hipStream_t on = (hipStream_t)stream;
     if (ctx->opt_nontemporal) {
         if (lag)
-            launch_flat<true, true>(p, streamed, (unsigned)grid, on);
+            launch_flat<true, true>(p, kind, (unsigned)grid, on);
         else
-            launch_flat<true, false>(p, streamed, (unsigned)grid, on);
+            launch_flat<true, false>(p, kind, (unsigned)grid, on);
     } else {
         if (lag)
-            launch_flat<false, true>(p, streamed, (unsigned)grid, on);
+            launch_flat<false, true>(p, kind, (unsigned)grid, on);
         else
-            launch_flat<false, false>(p, streamed, (unsigned)grid, on);
+            launch_flat<false, false>(p, kind, (unsigned)grid, on);
     }
     e = hipGetLastError();
     if (e != hipSuccess)

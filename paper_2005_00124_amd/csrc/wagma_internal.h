@@ -33,7 +33,7 @@ struct wagma_ctx {
 
 // Launch-shape switches that are not part of the public header: exported for the tests and for
 // measurements only.  wagma_debug_set_option also accepts the public WAGMA_OPT_* values.
-#define WAGMA_DEBUG_FORCE_STREAM 3   /* 0/1: the row-streaming kernel also for S = 8 */
+#define WAGMA_DEBUG_FORCE_STREAM 3   /* 0/1: the row-streaming kernel for every S >= 8 */
 #define WAGMA_DEBUG_STRIPE_LOG2 7    /* 0..16: the wavefronts of a workgroup work 2^v KiB apart in every row */
 #define WAGMA_DEBUG_XCD_CHUNK_LOG2 8 /* 0..13: each XCD works on runs of 2^v consecutive column tiles of a row;
                                         a per-tensor plan takes the value at wagma_tensors_create (its tiles are

@@ -14,7 +14,8 @@ namespace {
 typedef float v4f __attribute__((ext_vector_type(4)));
 
 constexpr int kMaskWords = WAGMA_MAX_P / 64;
-constexpr int kRegisterRows = 8;  // groups up to this size are held in registers, larger ones streamed
+constexpr int kRegisterRows = 8;      // groups up to this size are held in registers by one wavefront,
+constexpr int kCooperativeRows = 64;  // up to this size by the wavefronts of a workgroup, larger ones streamed
 // Rows per chunk of the streaming kernels.  Without busy processes 8 rows (24 loads in flight
 // per lane, 2 wavefronts per SIMD) are best; with them a chunk of 8 often holds only two or
 // three rows that are loaded at all, and 4 rows with twice the wavefronts hide the latency
@@ -145,6 +146,74 @@ struct TensorAddr {
     __device__ __forceinline__ float* m(int rank) const { return p.tm[slot(rank)] + lane_at; }
     __device__ __forceinline__ float* pub(int rank) const { return p.tpub[slot(rank)] + lane_at; }
 };
+
+// The work of registers_body (below) in two stages, for the kernel that deals a large group's rows
+// out to several wavefronts: the local update of S <= 8 rows with the stores of momentum and send
+// buffer, which yields W' of every row and the sum of the rows' contributions; and, once the sum
+// over the whole group is known, the stores of W.  (Only W' is handed from one stage to the other:
+// with the ranks and the late/busy flags handed over as well the compiler keeps 120 registers more
+// alive and spills.  registers_body is not built from the two stages: that form of the S = 8
+// kernel measured 0.75 % slower, same arrays, side by side.)
+template <int S, bool NT, bool LAG, typename V, typename Addr>
+__device__ __forceinline__ V rows_update(const StepParams& p, const int32_t* member, const Addr& at,
+                                         V (&w_prime)[S])
+{
+    // Measured, same arrays, variants side by side: with 8 rows an ordinary load of W (the other
+    // loads non-temporal) is 0.8-1 % faster than all loads non-temporal (workloads 4 and 5);
+    // with 4 rows it is 0.5 % slower (workloads 2 and 3).
+    constexpr bool kNontemporalW = NT && S < 8;
+    V gv[S], mv[S], contrib[S];
+    bool late[S], busy[S];
+    int rank[S];
+#pragma unroll
+    for (int e = 0; e < S; ++e) {
+        rank[e] = member[e];
+        late[e] = is_late(p, rank[e]);
+        busy[e] = LAG && is_busy(p, rank[e]);
+        if (!busy[e]) {
+            w_prime[e] = load_v<kNontemporalW, V>(at.w(rank[e]));
+            gv[e] = load_v<NT, V>(at.g(rank[e]));
+            mv[e] = load_v<NT, V>(at.m(rank[e]));
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < S; ++e)
+        if (late[e])
+            contrib[e] = load_v<NT, V>(at.pub(rank[e]));  // the send buffer of a late process
+
+    // (Issuing the loads and stores one array at a time instead of row by row was measured:
+    // no difference.)
+#pragma unroll
+    for (int e = 0; e < S; ++e) {
+        if (busy[e])
+            continue;
+        const V m_new = fma_v(p.mu, mv[e], gv[e]);
+        w_prime[e] = fma_v(-p.lr, m_new, w_prime[e]);  // W'
+        store_v<NT, V>(at.m(rank[e]), m_new);
+        store_v<NT, V>(at.pub(rank[e]), w_prime[e]);
+        if (!late[e])
+            contrib[e] = w_prime[e];
+    }
+    return tree_sum<S, V>(contrib);
+}
+
+template <int S, bool NT, bool LAG, typename V, typename Addr>
+__device__ __forceinline__ void rows_average(const StepParams& p, const int32_t* member, const Addr& at,
+                                             const V (&w_prime)[S], V w_sum)
+{
+#pragma unroll
+    for (int e = 0; e < S; ++e) {
+        const int rank = member[e];
+        if (LAG && is_busy(p, rank))
+            continue;  // the sum would wait in its receive buffer, unread
+        V out;
+        if (is_late(p, rank))
+            out = (w_sum + w_prime[e]) / p.members_plus_1;
+        else
+            out = w_sum * p.inv_members;
+        store_v<NT, V>(at.w(rank), out);
+    }
+}
 
 // One group of S <= 8 members, all member rows held in registers.  LAG: some members may
 // be still computing (is_busy); without it the busy mask is not looked at.
@@ -353,6 +422,57 @@ __global__ void __launch_bounds__(kBlock, 2) step_rows_streamed(const StepParams
         return;
     const FlatAddr at{p, (uint32_t)col * 4u};
     streamed_body<NT, LAG, v4f>(p, p.table + group * p.members, at);
+}
+
+// One group of 16, 32 or 64 members, its rows dealt out to the OCTETS = S/8 wavefronts of a
+// workgroup, 8 consecutive members each: every wavefront holds its 8 rows in registers exactly as
+// the S = 8 kernel does, the sums of the octets meet in LDS and every wavefront adds them up in
+// the same order (the pairwise tree over the group is the pairwise tree over its octets' trees),
+// so that a late member's W' is still in registers when W is stored.  All wavefronts of a
+// workgroup work on the same 64 column slices (1 KiB of every row).  Workgroups b, b+8, b+16, b+24
+// (the same XCD) take the four 1 KiB pieces that one workgroup of the other kernels takes.
+template <int OCTETS, bool NT, bool LAG>
+__global__ void __launch_bounds__(64 * OCTETS, OCTETS <= 4 ? 2 : 1) step_rows_cooperative(const StepParams p)
+{
+    __shared__ v4f octet_sum[OCTETS][64];
+    const int64_t b = blockIdx.x;  // p.blocks = groups * tiles * 4, tiles a multiple of 32
+    if (b >= p.blocks)
+        return;
+    const int64_t per_group = p.tiles * 4;
+    const int64_t group = b / per_group;
+    const int64_t piece = b % per_group;
+    int64_t tile = ((piece >> 5) << 3) | (piece & 7);
+    const int64_t wave_of_tile = (piece >> 3) & 3;
+    if (p.xcd_chunk_log2 > 0) {
+        const int j = p.xcd_chunk_log2;
+        const int64_t xcd = tile & (kNumXcd - 1);
+        const int64_t hi = tile >> 3;
+        tile = ((hi >> j) << (j + 3)) | (xcd << j) | (hi & ((int64_t(1) << j) - 1));
+    }
+    const int64_t super = tile >> p.stripe_log2;
+    const int64_t within = tile & ((int64_t(1) << p.stripe_log2) - 1);
+    const int64_t chunk = ((super * 4 + wave_of_tile) << p.stripe_log2) + within;
+    if (chunk * 64 >= p.nvec)
+        return;  // the whole workgroup: padding of the tile count
+    const int octet = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t col = chunk * 64 + lane;
+    const bool valid = col < p.nvec;  // the same lanes in every wavefront of the workgroup
+    const FlatAddr at{p, (uint32_t)col * 4u};
+    const int32_t* member = p.table + group * p.members + octet * 8;
+
+    v4f w_prime[8];
+    v4f mine = {0.f, 0.f, 0.f, 0.f};
+    if (valid)
+        mine = rows_update<8, NT, LAG, v4f>(p, member, at, w_prime);
+    octet_sum[octet][lane] = mine;
+    __syncthreads();  // reached by every wavefront of the workgroup, outside the lanes' branch
+    if (!valid)
+        return;
+    v4f sums[OCTETS];
+#pragma unroll
+    for (int o = 0; o < OCTETS; ++o)
+        sums[o] = octet_sum[o][lane];
+    rows_average<8, NT, LAG, v4f>(p, member, at, w_prime, tree_sum<OCTETS, v4f>(sums));
 }
 
 // Per-tensor layout.  Workgroup b owns tile b % tiles of group b / tiles; the tile table
