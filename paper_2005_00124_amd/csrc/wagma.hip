@@ -18,7 +18,7 @@
 //                              (3*S independent 128-bit loads in flight per lane).
 //   step_rows_cooperative      S = 16, 32, 64: the S/8 wavefronts of a workgroup hold 8 rows
 //                              each in the same way; the octets' sums meet in LDS.
-//   step_rows_streamed         larger S (and the per-tensor layout from S = 16): member rows
+//   step_rows_streamed         larger S (and the per-tensor layout from S = 32): member rows
 //                              are streamed 8 at a time (4 when some processes are still
 //                              computing), the partial sums kept on a pairwise stack; late
 //                              members re-read their own W' from the send buffer they just
@@ -167,7 +167,6 @@ struct wagma_tensors {
     const float* const* tg;
     float* const* tm;
     float* const* tpub;
-    const int64_t* tensor_size;
     const TileRef* tile_ref;
 };
 
@@ -175,9 +174,13 @@ namespace {
 constexpr int kTensorBlock = kBlock;  // threads per workgroup of the per-tensor kernels
 
 template <bool NT, bool LAG>
-void launch_tensors(const StepParams& p, unsigned grid, hipStream_t stream)
+void launch_tensors(const StepParams& p, bool cooperative, unsigned grid, hipStream_t stream)
 {
     const dim3 g(grid), b(kTensorBlock);
+    if (cooperative) {  // groups of 16: two wavefronts per group
+        hipLaunchKernelGGL((step_tensors_cooperative<2, NT, LAG>), g, dim3(128), 0, stream, p);
+        return;
+    }
     switch (p.members) {
     case 1: hipLaunchKernelGGL((step_tensors_in_registers<1, NT, LAG>), g, b, 0, stream, p); break;
     case 2: hipLaunchKernelGGL((step_tensors_in_registers<2, NT, LAG>), g, b, 0, stream, p); break;
@@ -544,11 +547,10 @@ int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64
     if (device != ctx->device)
         return WAGMA_EINVAL;
 
-    // blob layout: [4 pointer tables][T sizes][tiles tile refs]; every part 16-byte aligned
+    // blob layout: [4 pointer tables][tiles tile refs]; every part 16-byte aligned
     const size_t table_bytes = (slots * sizeof(void*) + 15) / 16 * 16;
-    const size_t sizes_bytes = ((size_t)T * sizeof(int64_t) + 15) / 16 * 16;
     const size_t refs_bytes = (size_t)tiles * sizeof(TileRef);
-    const size_t blob_bytes = 4 * table_bytes + sizes_bytes + refs_bytes;
+    const size_t blob_bytes = 4 * table_bytes + refs_bytes;
     char* host = (char*)std::malloc(blob_bytes);
     wagma_tensors* plan = new (std::nothrow) wagma_tensors();
     if (!host || !plan) {
@@ -557,12 +559,18 @@ int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64
         return WAGMA_ENOMEM;
     }
     std::memset(host, 0, blob_bytes);
-    std::memcpy(host + 0 * table_bytes, w, slots * sizeof(void*));
-    std::memcpy(host + 1 * table_bytes, g, slots * sizeof(void*));
-    std::memcpy(host + 2 * table_bytes, m, slots * sizeof(void*));
-    std::memcpy(host + 3 * table_bytes, pub, slots * sizeof(void*));
-    std::memcpy(host + 4 * table_bytes, sizes, (size_t)T * sizeof(int64_t));
-    TileRef* refs = (TileRef*)(host + 4 * table_bytes + sizes_bytes);
+    {
+        // the caller's tables are [P][T]; the device tables are [T][P]
+        const void* const* from[4] = {(const void* const*)w, (const void* const*)g, (const void* const*)m,
+                                      (const void* const*)pub};
+        for (int a = 0; a < 4; ++a) {
+            const void** to = (const void**)(host + (size_t)a * table_bytes);
+            for (int r = 0; r < ctx->P; ++r)
+                for (int k = 0; k < T; ++k)
+                    to[(size_t)k * ctx->P + r] = from[a][(size_t)r * T + k];
+        }
+    }
+    TileRef* refs = (TileRef*)(host + 4 * table_bytes);
     {
         // slot i of the table (the tile of workgroups i, i + tiles, ...) holds tile number
         // `linear` of the walk through the tensors: the XCD number i mod 8 moves from bits [0,3)
@@ -578,12 +586,11 @@ int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64
         for (int k = 0; k < T; ++k) {
             const int64_t slices = (sizes[k] + 3) / 4;
             for (int64_t first = 0; first < slices; first += kTensorBlock)
-                in_order.push_back(TileRef{k, 0, first});
+                in_order.push_back(TileRef{k, (uint32_t)sizes[k], first});
         }
-        // an empty tile: its first slice lies beyond tensor 0, so every lane of it returns at once
-        const int64_t beyond = ((sizes[0] + 3) / 4 + kTensorBlock - 1) / kTensorBlock * kTensorBlock;
+        // an empty tile has size 0: every lane of it returns at once
         while ((int64_t)in_order.size() < tiles)
-            in_order.push_back(TileRef{0, 0, beyond});
+            in_order.push_back(TileRef{0, 0u, 0});
         for (int64_t i = 0; i < tiles; ++i) {
             const int64_t xcd = i & (kNumXcd - 1), hi = i >> 3;
             const int64_t linear =
@@ -611,8 +618,7 @@ int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64
     plan->tg = (const float* const*)(dev + 1 * table_bytes);
     plan->tm = (float* const*)(dev + 2 * table_bytes);
     plan->tpub = (float* const*)(dev + 3 * table_bytes);
-    plan->tensor_size = (const int64_t*)(dev + 4 * table_bytes);
-    plan->tile_ref = (const TileRef*)(dev + 4 * table_bytes + sizes_bytes);
+    plan->tile_ref = (const TileRef*)(dev + 4 * table_bytes);
     *out = plan;
     return WAGMA_OK;
 }
@@ -656,23 +662,31 @@ int wagma_step_tensors_lag(wagma_ctx* ctx, const wagma_tensors* plan, const uint
     p.tg = plan->tg;
     p.tm = plan->tm;
     p.tpub = plan->tpub;
-    p.tensor_size = plan->tensor_size;
     p.tile_ref = plan->tile_ref;
-    p.num_tensors = plan->T;
-    p.tiles = plan->tiles;
+    p.num_ranks = ctx->P;
+    p.tiles = plan->tiles;  // a multiple of 8 (whole XCD rounds)
     p.blocks = (int64_t)(ctx->P / p.members) * p.tiles;
-    p.log2_chunks = p.members > kRegisterRows ? exact_log2(p.members / streamed_chunk(lag)) : 0;
+    // Measured (bench.py --tensors --S k --tau 0): with 2 wavefronts per group the cooperative kernel
+    // beats the row-streaming one (6093 against 5916 GB/s); with 4 and 8 it loses (5157 against 5689,
+    // 4539 against 5617): a workgroup looks up its tile and its base pointers before its first
+    // load, and with one or three large workgroups per compute unit nothing covers that wait.
+    const bool cooperative = p.members == 2 * kRegisterRows && !ctx->opt_force_stream;
+    if (cooperative)
+        p.blocks *= 4;  // one workgroup per quarter tile
+    if (p.blocks > 0x7fffffff)
+        return WAGMA_EINVAL;
+    p.log2_chunks = p.members > kRegisterRows && !cooperative ? exact_log2(p.members / streamed_chunk(lag)) : 0;
     const hipStream_t on = (hipStream_t)stream;
     if (ctx->opt_nontemporal) {
         if (lag)
-            launch_tensors<true, true>(p, (unsigned)p.blocks, on);
+            launch_tensors<true, true>(p, cooperative, (unsigned)p.blocks, on);
         else
-            launch_tensors<true, false>(p, (unsigned)p.blocks, on);
+            launch_tensors<true, false>(p, cooperative, (unsigned)p.blocks, on);
     } else {
         if (lag)
-            launch_tensors<false, true>(p, (unsigned)p.blocks, on);
+            launch_tensors<false, true>(p, cooperative, (unsigned)p.blocks, on);
         else
-            launch_tensors<false, false>(p, (unsigned)p.blocks, on);
+            launch_tensors<false, false>(p, cooperative, (unsigned)p.blocks, on);
     }
     e = hipGetLastError();
     if (e != hipSuccess)

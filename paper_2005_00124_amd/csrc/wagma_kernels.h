@@ -27,7 +27,7 @@ constexpr int64_t kMaxN = int64_t(1) << 31;
 
 struct TileRef {
     int32_t tensor;       // which tensor a tile of the per-tensor layout belongs to
-    int32_t reserved;
+    uint32_t size;        // floats in that tensor (0: an empty tile that pads the table)
     int64_t first_slice;  // first 16-byte slice of the tile inside that tensor
 };
 
@@ -52,13 +52,12 @@ struct StepParams {
     int stripe_log2;       // log2 of the distance, in KiB, between a workgroup's wavefronts
     int xcd_chunk_log2;    // log2 of the run of consecutive tiles one XCD works on (0: 1 tile)
     // per-tensor layout only (device tables)
-    float* const* tw;            // [P][T] base pointers, index rank * T + tensor
+    float* const* tw;            // [T][P] base pointers, index tensor * P + rank
     const float* const* tg;
     float* const* tm;
     float* const* tpub;
     const TileRef* tile_ref;     // [tiles]
-    const int64_t* tensor_size;  // [T] floats
-    int num_tensors;
+    int num_ranks;               // P: the device tables hold tensor k of all ranks side by side
 };
 
 // Element types of the kernel bodies: v4f (one 16-byte column slice) and float
@@ -134,13 +133,14 @@ struct FlatAddr {
     __device__ __forceinline__ float* pub(int rank) const { return p.pub + (int64_t)rank * p.ld + lane_at; }
 };
 
-// Per-tensor layout: a table of P x T base pointers per array; the lane adds its
-// float index inside the tensor.
+// Per-tensor layout: a table of T x P base pointers per array (the P pointers of one tensor side
+// by side: a workgroup works on one tensor and looks up its members' ranks there, a few cache
+// lines that its wavefronts and its neighbours share); the lane adds its float index inside the tensor.
 struct TensorAddr {
     const StepParams& p;
     int tensor;
     uint32_t lane_at;
-    __device__ __forceinline__ int64_t slot(int rank) const { return (int64_t)rank * p.num_tensors + tensor; }
+    __device__ __forceinline__ int64_t slot(int rank) const { return (int64_t)tensor * p.num_ranks + rank; }
     __device__ __forceinline__ float* w(int rank) const { return p.tw[slot(rank)] + lane_at; }
     __device__ __forceinline__ const float* g(int rank) const { return p.tg[slot(rank)] + lane_at; }
     __device__ __forceinline__ float* m(int rank) const { return p.tm[slot(rank)] + lane_at; }
@@ -476,7 +476,7 @@ __global__ void __launch_bounds__(64 * OCTETS, OCTETS <= 4 ? 2 : 1) step_rows_co
 }
 
 // Per-tensor layout.  Workgroup b owns tile b % tiles of group b / tiles; the tile table
-// names the tensor and the tile's first 16-byte slice inside it.  A lane whose slice is
+// names the tensor, its size and the tile's first 16-byte slice inside it.  A lane whose slice is
 // cut off by the end of the tensor does the remaining 1..3 elements one by one; nothing
 // beyond a tensor's last element is touched.
 template <int S, bool NT, bool LAG>
@@ -484,7 +484,7 @@ __global__ void __launch_bounds__(kBlock, 2) step_tensors_in_registers(const Ste
 {
     const int64_t group = blockIdx.x / p.tiles;
     const TileRef ref = p.tile_ref[blockIdx.x % p.tiles];
-    const int64_t size = p.tensor_size[ref.tensor];
+    const int64_t size = ref.size;
     const int64_t first = (ref.first_slice + threadIdx.x) * 4;
     if (first >= size)
         return;
@@ -505,7 +505,7 @@ __global__ void __launch_bounds__(kBlock, 2) step_tensors_streamed(const StepPar
 {
     const int64_t group = blockIdx.x / p.tiles;
     const TileRef ref = p.tile_ref[blockIdx.x % p.tiles];
-    const int64_t size = p.tensor_size[ref.tensor];
+    const int64_t size = ref.size;
     const int64_t first = (ref.first_slice + threadIdx.x) * 4;
     if (first >= size)
         return;
@@ -518,6 +518,70 @@ __global__ void __launch_bounds__(kBlock, 2) step_tensors_streamed(const StepPar
             at.lane_at = (uint32_t)k;
             streamed_body<NT, LAG, float>(p, member, at);
         }
+    }
+}
+
+// The per-tensor form of step_rows_cooperative: workgroup b takes one quarter (64 slices, 1 KiB per
+// row) of a tile of the tile table; workgroups b, b+8, b+16, b+24 (the same XCD) take the four
+// quarters of one tile.  The slice that a tensor's end cuts off is done element by element in up
+// to three more rounds; the number of rounds is the same for every wavefront of the workgroup
+// (they all work on the same slices), so every wavefront meets every barrier.
+template <int OCTETS, bool NT, bool LAG>
+__global__ void __launch_bounds__(64 * OCTETS, OCTETS <= 4 ? 2 : 1) step_tensors_cooperative(const StepParams p)
+{
+    __shared__ v4f octet_sum[OCTETS][64];
+    __shared__ float octet_sum_1[OCTETS][64];
+    const int64_t b = blockIdx.x;  // p.blocks = groups * tiles * 4, tiles a multiple of 8
+    if (b >= p.blocks)
+        return;
+    const int64_t per_group = p.tiles * 4;
+    const int64_t group = b / per_group;
+    const int64_t piece = b % per_group;
+    const TileRef ref = p.tile_ref[((piece >> 5) << 3) | (piece & 7)];
+    const int64_t size = ref.size;
+    const int64_t first_slice = ref.first_slice + ((piece >> 3) & 3) * 64;
+    if (first_slice * 4 >= size)
+        return;  // the whole workgroup: this quarter lies beyond the tensor (or the tile is padding)
+    const int octet = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t first = (first_slice + lane) * 4;
+    const bool whole = first + 4 <= size;      // the same lanes in every wavefront of the workgroup
+    const bool cut = !whole && first < size;   // at most one lane, and only in the tensor's last quarter
+    const int32_t* member = p.table + group * p.members + octet * 8;
+    {
+        const TensorAddr at{p, ref.tensor, (uint32_t)first};
+        v4f w_prime[8];
+        v4f mine = {0.f, 0.f, 0.f, 0.f};
+        if (whole)
+            mine = rows_update<8, NT, LAG, v4f>(p, member, at, w_prime);
+        octet_sum[octet][lane] = mine;
+        __syncthreads();
+        if (whole) {
+            v4f sums[OCTETS];
+#pragma unroll
+            for (int o = 0; o < OCTETS; ++o)
+                sums[o] = octet_sum[o][lane];
+            rows_average<8, NT, LAG, v4f>(p, member, at, w_prime, tree_sum<OCTETS, v4f>(sums));
+        }
+    }
+    // the elements of a slice cut off by the tensor's end, if that slice is in this quarter
+    const int64_t cut_slice = size / 4;
+    const int rounds = (size % 4 != 0 && cut_slice >= first_slice && cut_slice < first_slice + 64) ? (int)(size % 4) : 0;
+    for (int k = 0; k < rounds; ++k) {
+        const TensorAddr at{p, ref.tensor, (uint32_t)(first + k)};
+        float w_prime[8];
+        float mine = 0.f;
+        if (cut)
+            mine = rows_update<8, NT, LAG, float>(p, member, at, w_prime);
+        octet_sum_1[octet][lane] = mine;
+        __syncthreads();
+        if (cut) {
+            float sums[OCTETS];
+#pragma unroll
+            for (int o = 0; o < OCTETS; ++o)
+                sums[o] = octet_sum_1[o][lane];
+            rows_average<8, NT, LAG, float>(p, member, at, w_prime, tree_sum<OCTETS, float>(sums));
+        }
+        __syncthreads();  // before the next round writes the sums again
     }
 }
 
