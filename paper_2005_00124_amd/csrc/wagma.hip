@@ -129,9 +129,9 @@ void set_defaults(wagma_ctx* ctx, int P, int S, int G, int g, int64_t n, int tau
     ctx->place_split_gbs = 0.0;
 }
 
-// LAG: the kernels that also look at the busy mask (chosen only when a bit of it is set).
 enum class FlatKernel { in_registers, cooperative, streamed };
 
+// LAG: the kernels that also look at the busy mask (chosen only when a bit of it is set).
 template <bool NT, bool LAG>
 void launch_flat(const StepParams& p, FlatKernel kind, unsigned grid, hipStream_t stream)
 {
@@ -162,7 +162,7 @@ struct wagma_tensors {
     wagma_ctx* ctx;
     int T;
     int64_t tiles;      // workgroups per group
-    void* d_blob;       // one device allocation: four pointer tables, the sizes, the tile table
+    void* d_blob;       // one device allocation: four pointer tables ([T][P]), the tile table
     float* const* tw;
     const float* const* tg;
     float* const* tm;
