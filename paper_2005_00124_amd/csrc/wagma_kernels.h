@@ -158,10 +158,6 @@ template <int S, bool NT, bool LAG, typename V, typename Addr>
 __device__ __forceinline__ V rows_update(const StepParams& p, const int32_t* member, const Addr& at,
                                          V (&w_prime)[S])
 {
-    // Measured, same arrays, variants side by side: with 8 rows an ordinary load of W (the other
-    // loads non-temporal) is 0.8-1 % faster than all loads non-temporal (workloads 4 and 5);
-    // with 4 rows it is 0.5 % slower (workloads 2 and 3).
-    constexpr bool kNontemporalW = NT && S < 8;
     V gv[S], mv[S], contrib[S];
     bool late[S], busy[S];
     int rank[S];
@@ -171,7 +167,7 @@ __device__ __forceinline__ V rows_update(const StepParams& p, const int32_t* mem
         late[e] = is_late(p, rank[e]);
         busy[e] = LAG && is_busy(p, rank[e]);
         if (!busy[e]) {
-            w_prime[e] = load_v<kNontemporalW, V>(at.w(rank[e]));
+            w_prime[e] = load_v<NT, V>(at.w(rank[e]));
             gv[e] = load_v<NT, V>(at.g(rank[e]));
             mv[e] = load_v<NT, V>(at.m(rank[e]));
         }
@@ -220,10 +216,6 @@ __device__ __forceinline__ void rows_average(const StepParams& p, const int32_t*
 template <int S, bool NT, bool LAG, typename V, typename Addr>
 __device__ __forceinline__ void registers_body(const StepParams& p, const int32_t* member, const Addr& at)
 {
-    // Measured, same arrays, variants side by side: with 8 rows an ordinary load of W (the other
-    // loads non-temporal) is 0.8-1 % faster than all loads non-temporal (workloads 4 and 5);
-    // with 4 rows it is 0.5 % slower (workloads 2 and 3).
-    constexpr bool kNontemporalW = NT && S < 8;
     bool late[S], busy[S];
     int rank[S];
     V wv[S], gv[S], mv[S], contrib[S];
@@ -233,7 +225,7 @@ __device__ __forceinline__ void registers_body(const StepParams& p, const int32_
         late[e] = is_late(p, rank[e]);
         busy[e] = LAG && is_busy(p, rank[e]);
         if (!busy[e]) {
-            wv[e] = load_v<kNontemporalW, V>(at.w(rank[e]));
+            wv[e] = load_v<NT, V>(at.w(rank[e]));
             gv[e] = load_v<NT, V>(at.g(rank[e]));
             mv[e] = load_v<NT, V>(at.m(rank[e]));
         }
