@@ -31,14 +31,14 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 # over the group launches of the profiled command; valid for the launch options of PROFILE_OPTIONS
 # only.  workload -> (bytes per launch, the file under profiles/ that holds the figure).
 MEASURED_TRAFFIC = {
-    2: (10.116e9, "group_step_S4__resnet50-25.6M_P16_S4.md"),
-    3: (24.015e9, "group_step_S4__transformer-base-61.4M_P16_S4.md"),
+    2: (10.115e9, "group_step_S4__resnet50-25.6M_P16_S4.md"),
+    3: (24.016e9, "group_step_S4__transformer-base-61.4M_P16_S4.md"),
     4: (40.93e9, "group_step_S8__resnet50-25.6M_P64_S8.md"),
-    5: (166.31e9, "group_step_S8__transformer-big-210.8M_P32_S8.md"),
+    5: (166.36e9, "group_step_S8__transformer-big-210.8M_P32_S8.md"),
 }
-MEASURED_TRAFFIC_PER_TENSOR = {4: (40.965e9, "group_step_S8_per_tensor__resnet50-25.6M_P64_S8.md")}
+MEASURED_TRAFFIC_PER_TENSOR = {4: (40.938e9, "group_step_S8_per_tensor__resnet50-25.6M_P64_S8.md")}
 # option number -> value the profiles were taken with (the library's defaults at that time)
-PROFILE_OPTIONS = {"nontemporal": 1, "force_stream": 0, "stripe_log2": 2, "xcd_chunk_log2": 2}
+PROFILE_OPTIONS = {"nontemporal": 1, "force_stream": 0, "stripe_log2": 2, "xcd_chunk_log2": -1}
 
 OPTS = {"nontemporal": 2, "force_stream": 3, "stripe_log2": 7, "xcd_chunk_log2": 8, "placement": 9}
 
@@ -383,6 +383,8 @@ def main() -> int:
         bufs = ctx.alloc_placed()     # w, m, pub in different HBM regions
         info = ctx.placement_info()
         placement = "wagma_alloc_buffers: %(mode)s placement, %(candidates)d memory blocks examined" % info
+        placement += ", runs of %d tile(s) per XCD measured best on them" % (
+            1 << ctx.debug_get_option(lw.WAGMA_DEBUG_PLACED_XCD_CHUNK_LOG2))
         log("placement:", info)
     ms, wall = run_on(*bufs, K)
     grp_ms = sum(ms[t] for t in grp)
@@ -390,9 +392,10 @@ def main() -> int:
 
     if grp:
         dom, dom_ts = "group step (S=%d member rows %s%s)" % (
-            S, "in registers" if S <= 8 else "streamed", ", per-tensor layout" if args.tensors else ""), grp
+            S, "in registers" if S <= 8 else "dealt out to the wavefronts of a workgroup" if S <= 64 else "streamed",
+            ", per-tensor layout" if args.tensors else ""), grp
     else:
-        dom, dom_ts = "global step (rows streamed)", glb
+        dom, dom_ts = "global step (all P rows one group)", glb
     dom_ms = sum(ms[t] for t in dom_ts)
     achieved = sum(bytes_of[t] for t in dom_ts) / (dom_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS,

@@ -109,10 +109,11 @@ void set_defaults(wagma_ctx* ctx, int P, int S, int G, int g, int64_t n, int tau
     ctx->opt_nontemporal = (size_t)4 * (size_t)P * (size_t)ctx->ld * sizeof(float) > (size_t(256) << 20) ? 1 : 0;
     ctx->opt_force_stream = 0;
     // Measured best on MI355X (workgroups of 256 threads: three of them fit a compute unit with
-    // the S = 8 kernel's registers): the wavefronts of a workgroup 4 KiB apart, runs of 4
-    // consecutive tiles per XCD.
+    // the S = 8 kernel's registers): the wavefronts of a workgroup 4 KiB apart; how many
+    // consecutive tiles an XCD takes is chosen per launch (step_flat).
     ctx->opt_stripe_log2 = 2;
-    ctx->opt_xcd_chunk_log2 = 2;
+    ctx->opt_xcd_chunk_log2 = -1;
+    ctx->placed_xcd_chunk_log2 = 2;
     ctx->fixed_groups = 0;
     ctx->d_table = nullptr;
     ctx->h_table = nullptr;
@@ -273,6 +274,23 @@ int step_flat(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub, co
     p.log2_chunks = kind == FlatKernel::streamed ? exact_log2(p.members / streamed_chunk(lag)) : 0;
     p.stripe_log2 = ctx->opt_stripe_log2;
     p.xcd_chunk_log2 = ctx->opt_xcd_chunk_log2;
+    if (p.xcd_chunk_log2 < 0) {
+        // Runs of consecutive tiles per XCD, measured on MI355X (the results do not depend on it).
+        // The kernels whose workgroups share a group's rows: runs of 8 (4 in the row-streaming
+        // one) wherever the arrays lie.  The kernel that holds a group in registers: on arrays
+        // whose writes all go to one HBM region (ordinary allocations on a GPU whose memory is
+        // otherwise unused) tile by tile round the XCDs is 7-9 % faster than runs of 4, and 1-4 %
+        // on ordinary allocations in memory that has been in use; on arrays with w, m and pub in
+        // three regions the two are within 0.4 % of each other, either way round.  So: tile by
+        // tile for a caller's arrays, and for the library's own arrays what wagma_alloc_buffers
+        // measured on them (group_only: that measurement itself).
+        const bool own = group_only || (ctx->placed[0] && w == ctx->placed[0] && g == ctx->placed[1] &&
+                                        m == ctx->placed[2] && pub == ctx->placed[3]);
+        if (kind == FlatKernel::in_registers)
+            p.xcd_chunk_log2 = own ? ctx->placed_xcd_chunk_log2 : 0;
+        else
+            p.xcd_chunk_log2 = kind == FlatKernel::cooperative ? 3 : 2;
+    }
     // tiles is rounded up to whole stripes and whole XCD rounds (the surplus lanes find col >= nvec)
     p.tiles = (p.nvec + kBlock - 1) / kBlock;
     int round_log2 = p.stripe_log2;
@@ -526,9 +544,11 @@ int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64
         tiles += ((sizes[k] + 3) / 4 + kTensorBlock - 1) / kTensorBlock;
     }
     // Workgroup b of a launch runs on XCD b mod 8.  As in the flat layout, each XCD gets runs of
-    // consecutive tiles (here of 4 KiB per row, so twice as many as there for the same run
-    // length): the table is padded with empty tiles to whole rounds of 8 runs and permuted below.
-    const int run_log2 = ctx->opt_xcd_chunk_log2 > 0 ? (ctx->opt_xcd_chunk_log2 < 7 ? ctx->opt_xcd_chunk_log2 + 1 : 8) : 0;
+    // consecutive 4 KiB tiles (measured best here: runs of 8, twice the flat layout's value; tile
+    // by tile is 2-5 % slower on every kind of array): the table is padded with empty tiles to
+    // whole rounds of 8 runs and permuted below.
+    const int xcd_chunk_log2 = ctx->opt_xcd_chunk_log2 < 0 ? 2 : ctx->opt_xcd_chunk_log2;
+    const int run_log2 = xcd_chunk_log2 > 0 ? (xcd_chunk_log2 < 7 ? xcd_chunk_log2 + 1 : 8) : 0;
     const int64_t round_tiles = int64_t(kNumXcd) << run_log2;
     tiles = (tiles + round_tiles - 1) / round_tiles * round_tiles;
     if (total != ctx->n || tiles * (int64_t)ctx->P > 0x7fffffff)
@@ -773,9 +793,14 @@ int wagma_debug_set_option(wagma_ctx* ctx, int option, int64_t value)
         ctx->opt_stripe_log2 = (int)value;
         return WAGMA_OK;
     case WAGMA_DEBUG_XCD_CHUNK_LOG2:
-        if (value < 0 || value > 13)
+        if (value < -1 || value > 13)
             return WAGMA_EINVAL;
         ctx->opt_xcd_chunk_log2 = (int)value;
+        return WAGMA_OK;
+    case WAGMA_DEBUG_PLACED_XCD_CHUNK_LOG2:
+        if (value < 0 || value > 13)
+            return WAGMA_EINVAL;
+        ctx->placed_xcd_chunk_log2 = (int)value;
         return WAGMA_OK;
     default:
         return wagma_set_option(ctx, option, value);
@@ -792,6 +817,7 @@ int wagma_debug_get_option(const wagma_ctx* ctx, int option, int64_t* value)
     case WAGMA_DEBUG_FORCE_STREAM: *value = ctx->opt_force_stream; return WAGMA_OK;
     case WAGMA_DEBUG_STRIPE_LOG2: *value = ctx->opt_stripe_log2; return WAGMA_OK;
     case WAGMA_DEBUG_XCD_CHUNK_LOG2: *value = ctx->opt_xcd_chunk_log2; return WAGMA_OK;
+    case WAGMA_DEBUG_PLACED_XCD_CHUNK_LOG2: *value = ctx->placed_xcd_chunk_log2; return WAGMA_OK;
     default: return WAGMA_EINVAL;
     }
 }

@@ -627,6 +627,27 @@ int wagma_alloc_buffers(wagma_ctx* ctx, float** w, float** g, float** m, float**
     ctx->placed[1] = *g = best.ptr[1];
     ctx->placed[2] = *m = best.ptr[2];
     ctx->placed[3] = *pub = best.ptr[3];
+    // How many consecutive tiles an XCD takes is measured on the chosen arrays as well (the
+    // kernel that holds a group in registers; step_flat says what is known about it): runs of 4,
+    // with which the placements above were timed, against tile by tile, twice each in turn.
+    ctx->placed_xcd_chunk_log2 = 2;
+    if (bytes >= wagma_placement::kPlacementMinBytes && ctx->S <= 8) {
+        const int choice[2] = {2, 0};
+        double ms[2] = {0.0, 0.0};
+        for (int round = 0; round < 2; ++round) {
+            for (int c = 0; c < 2; ++c) {
+                ctx->placed_xcd_chunk_log2 = choice[c];
+                const double t = time_steps(ctx, best);
+                if (t > 0.0 && (ms[c] == 0.0 || t < ms[c]))
+                    ms[c] = t;
+            }
+        }
+        ctx->placed_xcd_chunk_log2 = ms[1] > 0.0 && ms[0] > 0.0 && ms[1] < ms[0] ? choice[1] : choice[0];
+        if (debug)
+            std::fprintf(stderr, "wagma placement: runs of 4 tiles per XCD %.3f ms, tile by tile %.3f ms\n", ms[0],
+                         ms[1]);
+        (void)hipGetLastError();
+    }
     return WAGMA_OK;
 }
 

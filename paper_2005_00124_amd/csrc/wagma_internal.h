@@ -18,8 +18,10 @@ struct wagma_ctx {
     int64_t n, ld;
     int32_t* d_table;  // (period + 1) * P, device
     int32_t* h_table;  // host mirror
-    int opt_nontemporal, opt_force_stream, opt_stripe_log2, opt_xcd_chunk_log2;
+    int opt_nontemporal, opt_force_stream, opt_stripe_log2;
+    int opt_xcd_chunk_log2;  // -1: chosen per launch (see step_flat); >= 0: this value for every launch
     float* placed[4];        // w, g, m, pub handed out by wagma_alloc_buffers (or all NULL)
+    int placed_xcd_chunk_log2;  // what wagma_alloc_buffers measured as best for steps on those arrays
     int64_t placed_ld;       // the row stride those arrays were sized for
     VmmArrays* vmm;          // not NULL: the four arrays are chunk-mapped, not hipMalloc'ed
     int opt_placement;       // WAGMA_PLACE_*
@@ -36,8 +38,12 @@ struct wagma_ctx {
 #define WAGMA_DEBUG_FORCE_STREAM 3   /* 0/1: the row-streaming kernel for every S >= 8 */
 #define WAGMA_DEBUG_STRIPE_LOG2 7    /* 0..16: the wavefronts of a workgroup work 2^v KiB apart in every row */
 #define WAGMA_DEBUG_XCD_CHUNK_LOG2 8 /* 0..13: each XCD works on runs of 2^v consecutive column tiles of a row;
-                                        a per-tensor plan takes the value at wagma_tensors_create (its tiles are
-                                        half as long: runs of 2^(v+1), at most 256, tiles) */
+                                        -1 (the default): chosen per launch, by kernel and by whose arrays they
+                                        are.  A per-tensor plan takes the value at wagma_tensors_create (-1
+                                        counts as 2) and uses runs twice as long: 2^(v+1), at most 256, tiles */
+#define WAGMA_DEBUG_PLACED_XCD_CHUNK_LOG2 10 /* 0..13: the run length (as above) for steps of the kernel that
+                                        holds a group in registers on the arrays of wagma_alloc_buffers, which
+                                        measures it; read it back after that call */
 extern "C" int wagma_debug_set_option(wagma_ctx* ctx, int option, int64_t value);
 extern "C" int wagma_debug_get_option(const wagma_ctx* ctx, int option, int64_t* value);
 

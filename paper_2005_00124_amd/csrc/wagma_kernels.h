@@ -395,7 +395,7 @@ __device__ __forceinline__ bool decode_block(const StepParams& p, int64_t& group
 }
 
 // Resident wavefronts per SIMD the register allocation must allow: the S = 8 body holds 32
-// 128-bit values per lane (131 registers: 3 wavefronts), the smaller ones fit 4 and more.
+// 128-bit values per lane (136 registers: 3 wavefronts), the smaller ones fit 4 and more.
 template <int S, bool NT, bool LAG>
 __global__ void __launch_bounds__(kBlock, S == 8 ? 2 : 4) step_rows_in_registers(const StepParams p)
 {

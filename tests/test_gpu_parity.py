@@ -175,6 +175,7 @@ OPTION_SETS = [
     ((lw.WAGMA_DEBUG_STRIPE_LOG2, 0), (lw.WAGMA_DEBUG_XCD_CHUNK_LOG2, 0)),
     ((lw.WAGMA_DEBUG_STRIPE_LOG2, 3),),
     ((lw.WAGMA_DEBUG_XCD_CHUNK_LOG2, 1),),
+    ((lw.WAGMA_DEBUG_XCD_CHUNK_LOG2, 2),),
     ((lw.WAGMA_DEBUG_XCD_CHUNK_LOG2, 8), (lw.WAGMA_DEBUG_STRIPE_LOG2, 2)),
     ((lw.WAGMA_DEBUG_XCD_CHUNK_LOG2, 13), (lw.WAGMA_DEBUG_FORCE_STREAM, 1)),
     ((lw.WAGMA_DEBUG_STRIPE_LOG2, 6),),

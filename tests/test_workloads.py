@@ -93,7 +93,7 @@ def test_stored_traffic_figures_are_those_of_the_profiles():
             text = open(os.path.join(root, "profiles", name)).read()
             stated = re.search(r"traffic_bytes_per_launch = ([0-9.e+]+)", text)
             assert stated and float(stated.group(1)) == nbytes, name
-            options = re.search(r"launch options of these runs: ([a-z0-9_= ]+)\)", text)
+            options = re.search(r"launch options of these runs: ([a-z0-9_= -]+)\)", text)
             assert options, name
             have = dict(kv.split("=") for kv in options.group(1).split())
             assert {k: int(v) for k, v in have.items()} == bench.PROFILE_OPTIONS, name
