@@ -509,7 +509,11 @@ def test_every_placement_mode_gives_the_same_bits(mode):
     with lw.Wagma(P, S, n, wl.tau) as ctx:
         ctx.set_option(lw.WAGMA_OPT_PLACEMENT, mode)
         w, g, m, pub = ctx.alloc_placed()
-        say("placement:", ctx.placement_info())
+        measured = ctx.debug_get_option(lw.WAGMA_DEBUG_PLACED_XCD_CHUNK_LOG2)
+        say("placement:", ctx.placement_info(), "runs of %d tiles per XCD" % (1 << measured))
+        assert measured in (0, 2)        # the allocator timed both on these arrays and kept one
+        # the other one for the second half of the run: the bits must not depend on it
+        other = 2 - measured
         wk.fill_initial_state(wl, w, m, pub)
         cols = wk.sample_columns(n, 20000, wl.seed).cuda()
         ow, om, opub = (np.ascontiguousarray(x[:, cols].cpu().numpy()) for x in (w, m, pub))
@@ -517,6 +521,8 @@ def test_every_placement_mode_gives_the_same_bits(mode):
             wk.fill_gradients(wl, t, g)
             og = np.ascontiguousarray(g[:, cols].cpu().numpy())
             mask = ctx.stale_mask(wl.seed, t, wl.stale_threshold)
+            if t == 6:
+                ctx.debug_set_option(lw.WAGMA_DEBUG_PLACED_XCD_CHUNK_LOG2, other)
             ctx.step(w, g, m, pub, mask, wl.lr, wl.mu, t)
             orc.step_f32(P, S, wl.tau, t, ow, og, om, opub, mask, wl.lr, wl.mu)
             torch.cuda.synchronize()
