@@ -31,16 +31,17 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 # over the group launches of the profiled command; valid for the launch options of PROFILE_OPTIONS
 # only.  workload -> (bytes per launch, the file under profiles/ that holds the figure).
 MEASURED_TRAFFIC = {
-    2: (10.115e9, "group_step_S4__resnet50-25.6M_P16_S4.md"),
-    3: (24.016e9, "group_step_S4__transformer-base-61.4M_P16_S4.md"),
+    2: (10.116e9, "group_step_S4__resnet50-25.6M_P16_S4.md"),
+    3: (24.015e9, "group_step_S4__transformer-base-61.4M_P16_S4.md"),
     4: (40.93e9, "group_step_S8__resnet50-25.6M_P64_S8.md"),
-    5: (166.36e9, "group_step_S8__transformer-big-210.8M_P32_S8.md"),
+    5: (166.37e9, "group_step_S8__transformer-big-210.8M_P32_S8.md"),
 }
-MEASURED_TRAFFIC_PER_TENSOR = {4: (40.938e9, "group_step_S8_per_tensor__resnet50-25.6M_P64_S8.md")}
+MEASURED_TRAFFIC_PER_TENSOR = {4: (40.937e9, "group_step_S8_per_tensor__resnet50-25.6M_P64_S8.md")}
 # option number -> value the profiles were taken with (the library's defaults at that time)
-PROFILE_OPTIONS = {"nontemporal": 1, "force_stream": 0, "stripe_log2": 2, "xcd_chunk_log2": -1}
+PROFILE_OPTIONS = {"nontemporal": 1, "force_stream": 0, "stripe_log2": 2, "xcd_chunk_log2": -1, "map": 0}
 
-OPTS = {"nontemporal": 2, "force_stream": 3, "stripe_log2": 7, "xcd_chunk_log2": 8, "placement": 9}
+OPTS = {"nontemporal": 2, "force_stream": 3, "stripe_log2": 7, "xcd_chunk_log2": 8, "placement": 9, "placed_shape": 10,
+        "map": 11}
 
 
 def log(*a):
@@ -318,7 +319,7 @@ def main() -> int:
     defaults_match = all(ctx.debug_get_option(OPTS[k]) == v for k, v in PROFILE_OPTIONS.items())
     for kv in args.opt:
         k, v = kv.split("=")
-        ctx.debug_set_option(OPTS[k], int(v))
+        ctx.debug_set_option(OPTS[k], int(v, 0))
     ld = ctx.ld
     log("workload %d: %s  n=%d ld=%d  buffers 4 x %.2f GB" % (wl.index, wl.name, n, ld, P * ld * 4 / 1e9))
     busy_masks = None
@@ -383,8 +384,7 @@ def main() -> int:
         bufs = ctx.alloc_placed()     # w, m, pub in different HBM regions
         info = ctx.placement_info()
         placement = "wagma_alloc_buffers: %(mode)s placement, %(candidates)d memory blocks examined" % info
-        placement += ", runs of %d tile(s) per XCD measured best on them" % (
-            1 << ctx.debug_get_option(lw.WAGMA_DEBUG_PLACED_XCD_CHUNK_LOG2))
+        placement += ", launch shape %d measured best on them" % ctx.debug_get_option(lw.WAGMA_DEBUG_PLACED_SHAPE)
         log("placement:", info)
     ms, wall = run_on(*bufs, K)
     grp_ms = sum(ms[t] for t in grp)

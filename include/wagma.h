@@ -281,9 +281,10 @@ int wagma_lag_masks(const wagma_ctx* ctx, uint64_t seed, int64_t iter, int windo
  * Where physical memory is scattered (a GPU that has been in use), plain allocations are
  * already mixed over the regions and may be the fastest, so by default (WAGMA_PLACE_AUTO) the
  * SEARCH, CHUNKS and PLAIN placements are each timed with the step kernel and the fastest is kept.
- * On the arrays it hands out the call also measures which order of the column tiles over the
- * chip's eight dies is faster for steps on these arrays, and the context uses that order whenever
- * a step is given exactly these four arrays (results do not depend on it).
+ * On the arrays it hands out the call also measures which way of dealing the column tiles out to
+ * the chip's eight dies and to the wavefronts of a workgroup is fastest for steps on these
+ * arrays, and the context uses that one whenever a step is given exactly these four arrays
+ * (results do not depend on it; a caller's own arrays get a fixed choice).
  * Arrays under 1 GiB get plain allocations.  The call takes from a fraction of a second to
  * several seconds, may hold most of the free memory while it searches, synchronises the
  * device and runs kernels on the default stream.  One set of buffers per context: a second

@@ -113,7 +113,8 @@ void set_defaults(wagma_ctx* ctx, int P, int S, int G, int g, int64_t n, int tau
     // consecutive tiles an XCD takes is chosen per launch (step_flat).
     ctx->opt_stripe_log2 = 2;
     ctx->opt_xcd_chunk_log2 = -1;
-    ctx->placed_xcd_chunk_log2 = 2;
+    ctx->opt_map = 0;
+    ctx->placed_shape = 0;
     ctx->fixed_groups = 0;
     ctx->d_table = nullptr;
     ctx->h_table = nullptr;
@@ -274,23 +275,31 @@ int step_flat(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub, co
     p.log2_chunks = kind == FlatKernel::streamed ? exact_log2(p.members / streamed_chunk(lag)) : 0;
     p.stripe_log2 = ctx->opt_stripe_log2;
     p.xcd_chunk_log2 = ctx->opt_xcd_chunk_log2;
-    if (p.xcd_chunk_log2 < 0) {
-        // Runs of consecutive tiles per XCD, measured on MI355X (the results do not depend on it).
-        // The kernels whose workgroups share a group's rows: runs of 8 (4 in the row-streaming
-        // one) wherever the arrays lie.  The kernel that holds a group in registers: on arrays
-        // whose writes all go to one HBM region (ordinary allocations on a GPU whose memory is
-        // otherwise unused) tile by tile round the XCDs is 7-9 % faster than runs of 4, and 1-4 %
-        // on ordinary allocations in memory that has been in use; on arrays with w, m and pub in
-        // three regions the two are within 0.4 % of each other, either way round.  So: tile by
-        // tile for a caller's arrays, and for the library's own arrays what wagma_alloc_buffers
-        // measured on them (group_only: that measurement itself).
-        const bool own = group_only || (ctx->placed[0] && w == ctx->placed[0] && g == ctx->placed[1] &&
-                                        m == ctx->placed[2] && pub == ctx->placed[3]);
-        if (kind == FlatKernel::in_registers)
-            p.xcd_chunk_log2 = own ? ctx->placed_xcd_chunk_log2 : 0;
-        else
+    p.map = ctx->opt_map;
+    if (p.map == 0 && p.xcd_chunk_log2 < 0) {
+        // Nothing forced: the shape measured best on MI355X (the results do not depend on it).
+        // The kernels whose workgroups share a group's rows: wavefronts 4 KiB apart, runs of 8
+        // tiles per XCD (4 in the row-streaming one), wherever the arrays lie.  The kernel that
+        // holds a group in registers: which shape is best depends on where the arrays lie.  On
+        // arrays whose writes all go to one HBM region (ordinary allocations on a GPU whose memory
+        // is otherwise unused) the wavefronts of a workgroup want to be 32 KiB apart (+15 % over
+        // shape 0), on arrays with w, m and pub in three regions shape 0 or 2 wins by 1 %.  A
+        // caller's arrays get the shape that lost least over all cases measured (within 1.5 % of the
+        // best everywhere); the library's own arrays get what wagma_alloc_buffers measured on
+        // them (group_only: that measurement itself).
+        if (kind == FlatKernel::in_registers) {
+            const bool own = group_only || (ctx->placed[0] && w == ctx->placed[0] && g == ctx->placed[1] &&
+                                            m == ctx->placed[2] && pub == ctx->placed[3]);
+            const LaunchShape& shape = kLaunchShapes[own ? ctx->placed_shape : kForeignShape];
+            p.map = shape.map;
+            p.stripe_log2 = shape.stripe_log2;
+            p.xcd_chunk_log2 = shape.xcd_chunk_log2;
+        } else {
             p.xcd_chunk_log2 = kind == FlatKernel::cooperative ? 3 : 2;
+        }
     }
+    if (p.xcd_chunk_log2 < 0)
+        p.xcd_chunk_log2 = 0;  // a forced map: unused
     // tiles is rounded up to whole stripes and whole XCD rounds (the surplus lanes find col >= nvec)
     p.tiles = (p.nvec + kBlock - 1) / kBlock;
     int round_log2 = p.stripe_log2;
@@ -298,6 +307,8 @@ int step_flat(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub, co
         round_log2 = p.xcd_chunk_log2 + 3;
     if (kind == FlatKernel::cooperative && round_log2 < 3)
         round_log2 = 3;  // its workgroups take the tiles in rounds of 8
+    if (p.map != 0)
+        round_log2 = 6;  // a map permutes the pieces of 64 tiles among themselves
     p.tiles = ((p.tiles + (int64_t(1) << round_log2) - 1) >> round_log2) << round_log2;
     p.blocks = (int64_t)(ctx->P / p.members) * p.tiles;
     if (kind == FlatKernel::cooperative)
@@ -797,11 +808,26 @@ int wagma_debug_set_option(wagma_ctx* ctx, int option, int64_t value)
             return WAGMA_EINVAL;
         ctx->opt_xcd_chunk_log2 = (int)value;
         return WAGMA_OK;
-    case WAGMA_DEBUG_PLACED_XCD_CHUNK_LOG2:
-        if (value < 0 || value > 13)
+    case WAGMA_DEBUG_PLACED_SHAPE:
+        if (value < 0 || value >= wagma_detail::kNumLaunchShapes)
             return WAGMA_EINVAL;
-        ctx->placed_xcd_chunk_log2 = (int)value;
+        ctx->placed_shape = (int)value;
         return WAGMA_OK;
+    case WAGMA_DEBUG_MAP: {
+        if (value < 0 || value > 0xffffffffll)
+            return WAGMA_EINVAL;
+        unsigned seen = 0;
+        for (int k = 0; k < 8 && value != 0; ++k) {
+            const unsigned field = (unsigned)(value >> (4 * k)) & 15u;
+            if (field > 7u)
+                return WAGMA_EINVAL;
+            seen |= 1u << field;
+        }
+        if (value != 0 && seen != 0xffu)
+            return WAGMA_EINVAL;
+        ctx->opt_map = (uint32_t)value;
+        return WAGMA_OK;
+    }
     default:
         return wagma_set_option(ctx, option, value);
     }
@@ -817,7 +843,8 @@ int wagma_debug_get_option(const wagma_ctx* ctx, int option, int64_t* value)
     case WAGMA_DEBUG_FORCE_STREAM: *value = ctx->opt_force_stream; return WAGMA_OK;
     case WAGMA_DEBUG_STRIPE_LOG2: *value = ctx->opt_stripe_log2; return WAGMA_OK;
     case WAGMA_DEBUG_XCD_CHUNK_LOG2: *value = ctx->opt_xcd_chunk_log2; return WAGMA_OK;
-    case WAGMA_DEBUG_PLACED_XCD_CHUNK_LOG2: *value = ctx->placed_xcd_chunk_log2; return WAGMA_OK;
+    case WAGMA_DEBUG_PLACED_SHAPE: *value = ctx->placed_shape; return WAGMA_OK;
+    case WAGMA_DEBUG_MAP: *value = ctx->opt_map; return WAGMA_OK;
     default: return WAGMA_EINVAL;
     }
 }

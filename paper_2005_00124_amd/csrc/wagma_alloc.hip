@@ -627,25 +627,41 @@ int wagma_alloc_buffers(wagma_ctx* ctx, float** w, float** g, float** m, float**
     ctx->placed[1] = *g = best.ptr[1];
     ctx->placed[2] = *m = best.ptr[2];
     ctx->placed[3] = *pub = best.ptr[3];
-    // How many consecutive tiles an XCD takes is measured on the chosen arrays as well (the
-    // kernel that holds a group in registers; step_flat says what is known about it): runs of 4,
-    // with which the placements above were timed, against tile by tile, twice each in turn.
-    ctx->placed_xcd_chunk_log2 = 2;
+    // The launch shape is measured on the chosen arrays as well (the kernel that holds a group in
+    // registers; step_flat says what is known about it): every shape of kLaunchShapes once, the
+    // two fastest once more; the placements above were timed with shape 0.
+    ctx->placed_shape = 0;
     if (bytes >= wagma_placement::kPlacementMinBytes && ctx->S <= 8) {
-        const int choice[2] = {2, 0};
-        double ms[2] = {0.0, 0.0};
-        for (int round = 0; round < 2; ++round) {
-            for (int c = 0; c < 2; ++c) {
-                ctx->placed_xcd_chunk_log2 = choice[c];
-                const double t = time_steps(ctx, best);
-                if (t > 0.0 && (ms[c] == 0.0 || t < ms[c]))
-                    ms[c] = t;
+        constexpr int kShapes = wagma_detail::kNumLaunchShapes;
+        double ms[kShapes] = {};
+        int first = 0, second = -1;
+        for (int c = 0; c < kShapes; ++c) {
+            ctx->placed_shape = c;
+            ms[c] = time_steps(ctx, best);
+        }
+        for (int c = 1; c < kShapes; ++c) {
+            if (ms[c] > 0.0 && (ms[first] == 0.0 || ms[c] < ms[first])) {
+                second = first;
+                first = c;
+            } else if (ms[c] > 0.0 && (second < 0 || ms[second] == 0.0 || ms[c] < ms[second])) {
+                second = c;
             }
         }
-        ctx->placed_xcd_chunk_log2 = ms[1] > 0.0 && ms[0] > 0.0 && ms[1] < ms[0] ? choice[1] : choice[0];
+        for (int c : {first, second}) {
+            if (c < 0)
+                continue;
+            ctx->placed_shape = c;
+            const double again = time_steps(ctx, best);
+            if (again > 0.0 && (ms[c] == 0.0 || again < ms[c]))
+                ms[c] = again;
+        }
+        if (second >= 0 && ms[second] > 0.0 && (ms[first] == 0.0 || ms[second] < ms[first]))
+            first = second;
+        ctx->placed_shape = first;
         if (debug)
-            std::fprintf(stderr, "wagma placement: runs of 4 tiles per XCD %.3f ms, tile by tile %.3f ms\n", ms[0],
-                         ms[1]);
+            for (int c = 0; c < kShapes; ++c)
+                std::fprintf(stderr, "wagma placement: launch shape %d: %.3f ms per group step%s\n", c, ms[c],
+                             c == first ? " (kept)" : "");
         (void)hipGetLastError();
     }
     return WAGMA_OK;

@@ -20,8 +20,10 @@ struct wagma_ctx {
     int32_t* h_table;  // host mirror
     int opt_nontemporal, opt_force_stream, opt_stripe_log2;
     int opt_xcd_chunk_log2;  // -1: chosen per launch (see step_flat); >= 0: this value for every launch
+    uint32_t opt_map;        // not 0: this tile-to-address map for every launch (see chunk_of)
     float* placed[4];        // w, g, m, pub handed out by wagma_alloc_buffers (or all NULL)
-    int placed_xcd_chunk_log2;  // what wagma_alloc_buffers measured as best for steps on those arrays
+    int placed_shape;        // index into wagma_detail::kLaunchShapes: what wagma_alloc_buffers measured as
+                             // best for steps on those arrays
     int64_t placed_ld;       // the row stride those arrays were sized for
     VmmArrays* vmm;          // not NULL: the four arrays are chunk-mapped, not hipMalloc'ed
     int opt_placement;       // WAGMA_PLACE_*
@@ -41,13 +43,36 @@ struct wagma_ctx {
                                         -1 (the default): chosen per launch, by kernel and by whose arrays they
                                         are.  A per-tensor plan takes the value at wagma_tensors_create (-1
                                         counts as 2) and uses runs twice as long: 2^(v+1), at most 256, tiles */
-#define WAGMA_DEBUG_PLACED_XCD_CHUNK_LOG2 10 /* 0..13: the run length (as above) for steps of the kernel that
-                                        holds a group in registers on the arrays of wagma_alloc_buffers, which
-                                        measures it; read it back after that call */
+#define WAGMA_DEBUG_PLACED_SHAPE 10  /* 0..kNumLaunchShapes-1: which of the launch shapes below the kernel that
+                                        holds a group in registers uses on the arrays of wagma_alloc_buffers,
+                                        which measures them all; read it back after that call */
+#define WAGMA_DEBUG_MAP 11           /* eight 4-bit fields, a permutation of 0..7: bit k of (tile << 2 | wavefront)
+                                        becomes bit field[k] of the number of the 1 KiB piece of a row; 0 (the
+                                        default): no forced map */
 extern "C" int wagma_debug_set_option(wagma_ctx* ctx, int option, int64_t value);
 extern "C" int wagma_debug_get_option(const wagma_ctx* ctx, int option, int64_t* value);
 
 namespace wagma_detail {
+
+// How the column tiles of a row are dealt out to workgroups (hence XCDs) and wavefronts: either
+// a map (chunk_of in wagma_kernels.h) or, with map == 0, stripe and XCD run length.
+struct LaunchShape {
+    uint32_t map;
+    int stripe_log2, xcd_chunk_log2;
+};
+// The shapes wagma_alloc_buffers times on its arrays.  Piece-number bits from bit 0 up
+// (w = wavefront, x = XCD, t = later tile bits):
+//   0  t3 t4 w0 w1 x0 x1 x2 t5   wavefronts 4 KiB apart, runs of 4 tiles per XCD
+//   1  x0 x1 w0 w1 x2 t3 t4 t5   wavefronts 4 KiB apart, tile by tile round the XCDs
+//   2  w1 t3 w0 t4 x0 x1 x2 t5   a workgroup takes KiB 0, 1, 4, 5 of 8; 16 KiB per XCD
+//   3  t3 t4 w0 w1 x0 t5 x2 x1   as 0 with the upper XCD bits further up
+//   4  t3 x2 t4 t5 x0 w0 w1 x1   wavefronts 32 KiB apart: what arrays in one HBM region want; of the
+//                                shapes of this kind the one that loses least elsewhere
+//   5  x2 x1 t3 t4 x0 w0 w1 t5   wavefronts 32 KiB apart, the XCDs interleaved finely
+constexpr int kNumLaunchShapes = 6;
+constexpr LaunchShape kLaunchShapes[kNumLaunchShapes] = {
+    {0u, 2, 2}, {0u, 2, 0}, {0x73165402u, 0, 0}, {0x51067432u, 0, 0}, {0x32017465u, 0, 0}, {0x73201465u, 0, 0}};
+constexpr int kForeignShape = 4;  // for arrays the library did not place
 
 // Records a failed HIP call for wagma_last_hip_error (per thread) and returns WAGMA_EHIP.
 int hip_failed(hipError_t e);

@@ -176,6 +176,9 @@ OPTION_SETS = [
     ((lw.WAGMA_DEBUG_STRIPE_LOG2, 3),),
     ((lw.WAGMA_DEBUG_XCD_CHUNK_LOG2, 1),),
     ((lw.WAGMA_DEBUG_XCD_CHUNK_LOG2, 2),),
+    ((lw.WAGMA_DEBUG_MAP, 0x32017465),),
+    ((lw.WAGMA_DEBUG_MAP, 0x01234567), (lw.WAGMA_OPT_NONTEMPORAL, 0)),
+    ((lw.WAGMA_DEBUG_MAP, 0x73165402), (lw.WAGMA_DEBUG_FORCE_STREAM, 1)),
     ((lw.WAGMA_DEBUG_XCD_CHUNK_LOG2, 8), (lw.WAGMA_DEBUG_STRIPE_LOG2, 2)),
     ((lw.WAGMA_DEBUG_XCD_CHUNK_LOG2, 13), (lw.WAGMA_DEBUG_FORCE_STREAM, 1)),
     ((lw.WAGMA_DEBUG_STRIPE_LOG2, 6),),
@@ -509,11 +512,11 @@ def test_every_placement_mode_gives_the_same_bits(mode):
     with lw.Wagma(P, S, n, wl.tau) as ctx:
         ctx.set_option(lw.WAGMA_OPT_PLACEMENT, mode)
         w, g, m, pub = ctx.alloc_placed()
-        measured = ctx.debug_get_option(lw.WAGMA_DEBUG_PLACED_XCD_CHUNK_LOG2)
-        say("placement:", ctx.placement_info(), "runs of %d tiles per XCD" % (1 << measured))
-        assert measured in (0, 2)        # the allocator timed both on these arrays and kept one
-        # the other one for the second half of the run: the bits must not depend on it
-        other = 2 - measured
+        measured = ctx.debug_get_option(lw.WAGMA_DEBUG_PLACED_SHAPE)
+        say("placement:", ctx.placement_info(), "launch shape %d" % measured)
+        assert 0 <= measured < 6         # the allocator timed its launch shapes on these arrays and kept one
+        # the others in turn from iteration 4 on: the bits must not depend on the shape
+        others = [k for k in range(6) if k != measured]
         wk.fill_initial_state(wl, w, m, pub)
         cols = wk.sample_columns(n, 20000, wl.seed).cuda()
         ow, om, opub = (np.ascontiguousarray(x[:, cols].cpu().numpy()) for x in (w, m, pub))
@@ -521,8 +524,8 @@ def test_every_placement_mode_gives_the_same_bits(mode):
             wk.fill_gradients(wl, t, g)
             og = np.ascontiguousarray(g[:, cols].cpu().numpy())
             mask = ctx.stale_mask(wl.seed, t, wl.stale_threshold)
-            if t == 6:
-                ctx.debug_set_option(lw.WAGMA_DEBUG_PLACED_XCD_CHUNK_LOG2, other)
+            if t >= 4:
+                ctx.debug_set_option(lw.WAGMA_DEBUG_PLACED_SHAPE, others[t % 5])
             ctx.step(w, g, m, pub, mask, wl.lr, wl.mu, t)
             orc.step_f32(P, S, wl.tau, t, ow, og, om, opub, mask, wl.lr, wl.mu)
             torch.cuda.synchronize()
