@@ -41,7 +41,7 @@ MEASURED_TRAFFIC_PER_TENSOR = {4: (40.937e9, "group_step_S8_per_tensor__resnet50
 PROFILE_OPTIONS = {"nontemporal": 1, "force_stream": 0, "stripe_log2": 2, "xcd_chunk_log2": -1, "map": 0}
 
 OPTS = {"nontemporal": 2, "force_stream": 3, "stripe_log2": 7, "xcd_chunk_log2": 8, "placement": 9, "placed_shape": 10,
-        "map": 11}
+        "map": 11, "placed_coop_shape": 12}
 
 
 def log(*a):
@@ -384,7 +384,8 @@ def main() -> int:
         bufs = ctx.alloc_placed()     # w, m, pub in different HBM regions
         info = ctx.placement_info()
         placement = "wagma_alloc_buffers: %(mode)s placement, %(candidates)d memory blocks examined" % info
-        placement += ", launch shape %d measured best on them" % ctx.debug_get_option(lw.WAGMA_DEBUG_PLACED_SHAPE)
+        placement += ", launch shapes %d (group rows in registers) and %d (rows over a workgroup) measured best on them" % (
+            ctx.debug_get_option(lw.WAGMA_DEBUG_PLACED_SHAPE), ctx.debug_get_option(lw.WAGMA_DEBUG_PLACED_COOP_SHAPE))
         log("placement:", info)
     ms, wall = run_on(*bufs, K)
     grp_ms = sum(ms[t] for t in grp)

@@ -112,9 +112,11 @@ void set_defaults(wagma_ctx* ctx, int P, int S, int G, int g, int64_t n, int tau
     // the S = 8 kernel's registers): the wavefronts of a workgroup 4 KiB apart; how many
     // consecutive tiles an XCD takes is chosen per launch (step_flat).
     ctx->opt_stripe_log2 = 2;
+    ctx->stripe_forced = 0;
     ctx->opt_xcd_chunk_log2 = -1;
     ctx->opt_map = 0;
     ctx->placed_shape = 0;
+    ctx->placed_coop_shape = 0;
     ctx->fixed_groups = 0;
     ctx->d_table = nullptr;
     ctx->h_table = nullptr;
@@ -228,13 +230,13 @@ bool fill_common(const wagma_ctx* ctx, StepParams& p, bool global, const uint64_
 namespace wagma_detail {
 
 int step_flat(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub, const uint64_t* stale_mask,
-              const uint64_t* busy_mask, float lr, float mu, int64_t iter, void* stream, bool group_only)
+              const uint64_t* busy_mask, float lr, float mu, int64_t iter, void* stream, Force force)
 {
     int global = wagma_is_global_iteration(ctx, iter);
     if (global < 0)
         return global;
-    if (group_only)
-        global = 0;
+    if (force != Force::none)
+        global = force == Force::global ? 1 : 0;
     if (!w || !g || !m || !pub)
         return WAGMA_EINVAL;
     if ((((uintptr_t)w) | ((uintptr_t)g) | ((uintptr_t)m) | ((uintptr_t)pub)) & 15u)
@@ -258,7 +260,7 @@ int step_flat(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub, co
 
     StepParams p;
     const bool lag = fill_common(ctx, p, global != 0, stale_mask, busy_mask, lr, mu, iter);
-    if (group_only)
+    if (force == Force::group)
         p.table = ctx->d_table + (ctx->fixed_groups ? 0 : iter % ctx->period) * ctx->P;
     p.w = w;
     p.g = g;
@@ -276,27 +278,35 @@ int step_flat(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub, co
     p.stripe_log2 = ctx->opt_stripe_log2;
     p.xcd_chunk_log2 = ctx->opt_xcd_chunk_log2;
     p.map = ctx->opt_map;
+    if (p.map == 0 && p.xcd_chunk_log2 < 0 && ctx->stripe_forced) {
+        // only the stripe is forced: tile by tile for the kernel that holds a group in registers,
+        // the other kernels' usual runs
+        p.xcd_chunk_log2 = kind == FlatKernel::in_registers ? 0 : kind == FlatKernel::cooperative ? 3 : 2;
+    }
     if (p.map == 0 && p.xcd_chunk_log2 < 0) {
         // Nothing forced: the shape measured best on MI355X (the results do not depend on it).
-        // The kernels whose workgroups share a group's rows: wavefronts 4 KiB apart, runs of 8
-        // tiles per XCD (4 in the row-streaming one), wherever the arrays lie.  The kernel that
-        // holds a group in registers: which shape is best depends on where the arrays lie.  On
-        // arrays whose writes all go to one HBM region (ordinary allocations on a GPU whose memory
-        // is otherwise unused) the wavefronts of a workgroup want to be 32 KiB apart (+15 % over
-        // shape 0), on arrays with w, m and pub in three regions shape 0 or 2 wins by 1 %.  A
-        // caller's arrays get the shape that lost least over all cases measured (within 1.5 % of the
-        // best everywhere); the library's own arrays get what wagma_alloc_buffers measured on
-        // them (group_only: that measurement itself).
-        if (kind == FlatKernel::in_registers) {
-            const bool own = group_only || (ctx->placed[0] && w == ctx->placed[0] && g == ctx->placed[1] &&
-                                            m == ctx->placed[2] && pub == ctx->placed[3]);
-            const LaunchShape& shape = kLaunchShapes[own ? ctx->placed_shape : kForeignShape];
-            p.map = shape.map;
-            p.stripe_log2 = shape.stripe_log2;
-            p.xcd_chunk_log2 = shape.xcd_chunk_log2;
-        } else {
-            p.xcd_chunk_log2 = kind == FlatKernel::cooperative ? 3 : 2;
-        }
+        // Which shape is best depends on where the arrays lie.  The kernel that holds a group in
+        // registers: on arrays whose writes all go to one HBM region (ordinary allocations on a GPU
+        // whose memory is otherwise unused) shape 0 runs at 66 % of the peak and the shapes whose
+        // wavefronts take 512 B here and 512 B 32 KiB further on at 82 %; on arrays with w, m and
+        // pub in three regions all shapes are within 1 % of each other, in an order that changes
+        // with the box and the workload.  A caller's arrays get shape 3, within 0.6 % of the best
+        // in every case measured; the library's own arrays get what wagma_alloc_buffers measured on
+        // them (a forced iteration is that measurement itself).  The kernel that deals a group's
+        // rows out to the wavefronts of a workgroup: with two wavefronts the split shape gains up to
+        // 24 % on arrays in one region and stays within 3 % elsewhere, with four or eight it loses
+        // 12 % on arrays in three regions: a caller's arrays get it for groups of 16 only.  The
+        // row-streaming kernel keeps the 4 KiB stripe with runs of 4 tiles per XCD.
+        const bool own = force != Force::none || (ctx->placed[0] && w == ctx->placed[0] && g == ctx->placed[1] &&
+                                                  m == ctx->placed[2] && pub == ctx->placed[3]);
+        LaunchShape shape = {0u, ctx->opt_stripe_log2, 2};
+        if (kind == FlatKernel::in_registers)
+            shape = kLaunchShapes[own ? ctx->placed_shape : kForeignShape];
+        else if (kind == FlatKernel::cooperative)
+            shape = kCoopShapes[own ? ctx->placed_coop_shape : (p.members == 16 ? 1 : 0)];
+        p.map = shape.map;
+        p.stripe_log2 = shape.stripe_log2;
+        p.xcd_chunk_log2 = shape.xcd_chunk_log2;
     }
     if (p.xcd_chunk_log2 < 0)
         p.xcd_chunk_log2 = 0;  // a forced map: unused
@@ -308,7 +318,7 @@ int step_flat(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub, co
     if (kind == FlatKernel::cooperative && round_log2 < 3)
         round_log2 = 3;  // its workgroups take the tiles in rounds of 8
     if (p.map != 0)
-        round_log2 = 6;  // a map permutes the pieces of 64 tiles among themselves
+        round_log2 = 6;  // a map permutes the slices of 64 tiles among themselves
     p.tiles = ((p.tiles + (int64_t(1) << round_log2) - 1) >> round_log2) << round_log2;
     p.blocks = (int64_t)(ctx->P / p.members) * p.tiles;
     if (kind == FlatKernel::cooperative)
@@ -458,14 +468,14 @@ int wagma_group_schedule(const wagma_ctx* ctx, int64_t iter, const int32_t** dev
 int wagma_step(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub,
                const uint64_t* stale_mask, float lr, float mu, int64_t iter, void* stream)
 {
-    return step_flat(ctx, w, g, m, pub, stale_mask, nullptr, lr, mu, iter, stream, false);
+    return step_flat(ctx, w, g, m, pub, stale_mask, nullptr, lr, mu, iter, stream, wagma_detail::Force::none);
 }
 
 int wagma_step_lag(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub,
                    const uint64_t* late_mask, const uint64_t* busy_mask, float lr, float mu, int64_t iter,
                    void* stream)
 {
-    return step_flat(ctx, w, g, m, pub, late_mask, busy_mask, lr, mu, iter, stream, false);
+    return step_flat(ctx, w, g, m, pub, late_mask, busy_mask, lr, mu, iter, stream, wagma_detail::Force::none);
 }
 
 // ---- wagma_step without a context: the schedule table lives in a static device array ------
@@ -534,7 +544,7 @@ int wagma_step_static(int P, int S, int64_t n, int tau, int64_t ld, float* w, co
     e = hipGetLastError();
     if (e != hipSuccess)
         return hip_failed(e);
-    return step_flat(&ctx, w, g, m, pub, stale_mask, nullptr, lr, mu, iter, stream, false);
+    return step_flat(&ctx, w, g, m, pub, stale_mask, nullptr, lr, mu, iter, stream, wagma_detail::Force::none);
 }
 
 // ---- per-tensor layout ------------------------------------------------------------------
@@ -802,6 +812,7 @@ int wagma_debug_set_option(wagma_ctx* ctx, int option, int64_t value)
         if (value < 0 || value > 16)
             return WAGMA_EINVAL;
         ctx->opt_stripe_log2 = (int)value;
+        ctx->stripe_forced = 1;
         return WAGMA_OK;
     case WAGMA_DEBUG_XCD_CHUNK_LOG2:
         if (value < -1 || value > 13)
@@ -813,19 +824,24 @@ int wagma_debug_set_option(wagma_ctx* ctx, int option, int64_t value)
             return WAGMA_EINVAL;
         ctx->placed_shape = (int)value;
         return WAGMA_OK;
+    case WAGMA_DEBUG_PLACED_COOP_SHAPE:
+        if (value < 0 || value >= wagma_detail::kNumCoopShapes)
+            return WAGMA_EINVAL;
+        ctx->placed_coop_shape = (int)value;
+        return WAGMA_OK;
     case WAGMA_DEBUG_MAP: {
-        if (value < 0 || value > 0xffffffffll)
+        if (value < 0 || value > 0xffffffffffll)
             return WAGMA_EINVAL;
         unsigned seen = 0;
-        for (int k = 0; k < 8 && value != 0; ++k) {
+        for (int k = 0; k < 10 && value != 0; ++k) {
             const unsigned field = (unsigned)(value >> (4 * k)) & 15u;
-            if (field > 7u)
+            if (field > 9u)
                 return WAGMA_EINVAL;
             seen |= 1u << field;
         }
-        if (value != 0 && seen != 0xffu)
+        if (value != 0 && seen != 0x3ffu)
             return WAGMA_EINVAL;
-        ctx->opt_map = (uint32_t)value;
+        ctx->opt_map = (uint64_t)value;
         return WAGMA_OK;
     }
     default:
@@ -844,7 +860,8 @@ int wagma_debug_get_option(const wagma_ctx* ctx, int option, int64_t* value)
     case WAGMA_DEBUG_STRIPE_LOG2: *value = ctx->opt_stripe_log2; return WAGMA_OK;
     case WAGMA_DEBUG_XCD_CHUNK_LOG2: *value = ctx->opt_xcd_chunk_log2; return WAGMA_OK;
     case WAGMA_DEBUG_PLACED_SHAPE: *value = ctx->placed_shape; return WAGMA_OK;
-    case WAGMA_DEBUG_MAP: *value = ctx->opt_map; return WAGMA_OK;
+    case WAGMA_DEBUG_PLACED_COOP_SHAPE: *value = ctx->placed_coop_shape; return WAGMA_OK;
+    case WAGMA_DEBUG_MAP: *value = (int64_t)ctx->opt_map; return WAGMA_OK;
     default: return WAGMA_EINVAL;
     }
 }

@@ -426,8 +426,9 @@ bool place_plain(size_t bytes, ArraySet& out)
 }
 
 // Milliseconds per group step of `ctx` on the (uninitialised) arrays of `set`: every distinct
-// group schedule once, after one untimed pass.  0 on failure.
-double time_steps(wagma_ctx* ctx, const ArraySet& set)
+// group schedule once, after one untimed pass; with `global`, of a global iteration (twice, after
+// one untimed one).  0 on failure.
+double time_steps(wagma_ctx* ctx, const ArraySet& set, bool global = false)
 {
     hipEvent_t start = nullptr, stop = nullptr;
     if (hipEventCreate(&start) != hipSuccess || hipEventCreate(&stop) != hipSuccess) {
@@ -443,11 +444,11 @@ double time_steps(wagma_ctx* ctx, const ArraySet& set)
     double ms_per_step = 0.0;
     bool ok = true;
     for (int pass = 0; pass < 2 && ok; ++pass) {
-        const int steps = ctx->period;
+        const int steps = global ? 2 : ctx->period;
         ok = hipEventRecord(start, nullptr) == hipSuccess;
         for (int t = 0; t < steps && ok; ++t)
             ok = step_flat(ctx, set.ptr[0], set.ptr[1], set.ptr[2], set.ptr[3], late, nullptr, 0.0f, 0.0f, t, nullptr,
-                           true) == WAGMA_OK;
+                           global ? wagma_detail::Force::global : wagma_detail::Force::group) == WAGMA_OK;
         ok = ok && hipEventRecord(stop, nullptr) == hipSuccess && hipEventSynchronize(stop) == hipSuccess;
         float ms = 0.0f;
         if (ok && pass == 1 && hipEventElapsedTime(&ms, start, stop) == hipSuccess)
@@ -456,6 +457,58 @@ double time_steps(wagma_ctx* ctx, const ArraySet& set)
     (void)hipEventDestroy(start);
     (void)hipEventDestroy(stop);
     return ok ? ms_per_step : 0.0;
+}
+
+// Which launch-shape setting of the context a group (or global) iteration uses: placed_shape for
+// the kernel that holds a group in registers, placed_coop_shape for the one that deals a group's
+// rows out to the wavefronts of a workgroup, none (nullptr) for the row-streaming kernel.
+int* shape_setting(wagma_ctx* ctx, bool global, int* count)
+{
+    const int members = global ? ctx->P : ctx->S;
+    if (members <= 8) {
+        *count = wagma_detail::kNumLaunchShapes;
+        return &ctx->placed_shape;
+    }
+    if (members <= 64) {
+        *count = wagma_detail::kNumCoopShapes;
+        return &ctx->placed_coop_shape;
+    }
+    *count = 0;
+    return nullptr;
+}
+
+// What a placement is judged by: milliseconds per iteration over a period of tau iterations,
+// every kernel with the better of its first and of its caller-array launch shape (which of the
+// two wins depends on the placement, so a placement is not judged with one of them alone).
+// 0 on failure.
+double time_placement(wagma_ctx* ctx, const ArraySet& set)
+{
+    const int kept = ctx->placed_shape, kept_coop = ctx->placed_coop_shape;
+    auto better_of_two = [&](bool global) {
+        int count = 0;
+        int* setting = shape_setting(ctx, global, &count);
+        if (!setting)
+            return time_steps(ctx, set, global);
+        double best = 0.0;
+        for (int shape : {0, count == wagma_detail::kNumLaunchShapes ? wagma_detail::kForeignShape : 1}) {
+            *setting = shape;
+            const double t = time_steps(ctx, set, global);
+            if (t > 0.0 && (best == 0.0 || t < best))
+                best = t;
+        }
+        return best;
+    };
+    const double group_ms = ctx->tau != 1 ? better_of_two(false) : 0.0;
+    const double global_ms = ctx->tau >= 1 ? better_of_two(true) : 0.0;
+    ctx->placed_shape = kept;
+    ctx->placed_coop_shape = kept_coop;
+    if (ctx->tau == 0)
+        return group_ms;
+    if (ctx->tau == 1)
+        return global_ms;
+    if (group_ms == 0.0 || global_ms == 0.0)
+        return 0.0;
+    return ((ctx->tau - 1) * group_ms + global_ms) / ctx->tau;
 }
 
 // Placement by measurement alone: candidate arrays spread over the free memory, then a
@@ -592,10 +645,10 @@ int wagma_alloc_buffers(wagma_ctx* ctx, float** w, float** g, float** m, float**
             (void)hipGetLastError();
             continue;
         }
-        if (mode == WAGMA_PLACE_AUTO && trial.step_ms == 0.0)
-            trial.step_ms = time_steps(ctx, trial);
+        if (mode == WAGMA_PLACE_AUTO)
+            trial.step_ms = time_placement(ctx, trial);
         if (debug)
-            std::fprintf(stderr, "wagma placement: mode %d regions %d: %.3f ms per group step\n", trial.mode,
+            std::fprintf(stderr, "wagma placement: mode %d regions %d: %.3f ms per iteration\n", trial.mode,
                          trial.regions, trial.step_ms);
         // step_ms == 0: the timing failed, the placement's speed is unknown; any placement with
         // a known time replaces such a one, and a later one must be 1 % faster to replace a known one
@@ -627,41 +680,54 @@ int wagma_alloc_buffers(wagma_ctx* ctx, float** w, float** g, float** m, float**
     ctx->placed[1] = *g = best.ptr[1];
     ctx->placed[2] = *m = best.ptr[2];
     ctx->placed[3] = *pub = best.ptr[3];
-    // The launch shape is measured on the chosen arrays as well (the kernel that holds a group in
-    // registers; step_flat says what is known about it): every shape of kLaunchShapes once, the
-    // two fastest once more; the placements above were timed with shape 0.
+    // The launch shapes are measured on the chosen arrays as well (step_flat says what is known
+    // about them): every shape once, the two fastest once more; the group iterations first, then
+    // the global one if it runs another kernel.
     ctx->placed_shape = 0;
-    if (bytes >= wagma_placement::kPlacementMinBytes && ctx->S <= 8) {
-        constexpr int kShapes = wagma_detail::kNumLaunchShapes;
-        double ms[kShapes] = {};
-        int first = 0, second = -1;
-        for (int c = 0; c < kShapes; ++c) {
-            ctx->placed_shape = c;
-            ms[c] = time_steps(ctx, best);
-        }
-        for (int c = 1; c < kShapes; ++c) {
-            if (ms[c] > 0.0 && (ms[first] == 0.0 || ms[c] < ms[first])) {
-                second = first;
-                first = c;
-            } else if (ms[c] > 0.0 && (second < 0 || ms[second] == 0.0 || ms[c] < ms[second])) {
-                second = c;
+    ctx->placed_coop_shape = 0;
+    if (bytes >= wagma_placement::kPlacementMinBytes) {
+        auto keep_fastest = [&](bool global) {
+            int count = 0;
+            int* setting = shape_setting(ctx, global, &count);
+            if (!setting)
+                return;
+            double ms[8] = {};
+            int first = 0, second = -1;
+            for (int c = 0; c < count; ++c) {
+                *setting = c;
+                ms[c] = time_steps(ctx, best, global);
             }
-        }
-        for (int c : {first, second}) {
-            if (c < 0)
-                continue;
-            ctx->placed_shape = c;
-            const double again = time_steps(ctx, best);
-            if (again > 0.0 && (ms[c] == 0.0 || again < ms[c]))
-                ms[c] = again;
-        }
-        if (second >= 0 && ms[second] > 0.0 && (ms[first] == 0.0 || ms[second] < ms[first]))
-            first = second;
-        ctx->placed_shape = first;
-        if (debug)
-            for (int c = 0; c < kShapes; ++c)
-                std::fprintf(stderr, "wagma placement: launch shape %d: %.3f ms per group step%s\n", c, ms[c],
-                             c == first ? " (kept)" : "");
+            for (int c = 1; c < count; ++c) {
+                if (ms[c] > 0.0 && (ms[first] == 0.0 || ms[c] < ms[first])) {
+                    second = first;
+                    first = c;
+                } else if (ms[c] > 0.0 && (second < 0 || ms[second] == 0.0 || ms[c] < ms[second])) {
+                    second = c;
+                }
+            }
+            for (int c : {first, second}) {
+                if (c < 0)
+                    continue;
+                *setting = c;
+                const double again = time_steps(ctx, best, global);
+                if (again > 0.0 && (ms[c] == 0.0 || again < ms[c]))
+                    ms[c] = again;
+            }
+            if (second >= 0 && ms[second] > 0.0 && (ms[first] == 0.0 || ms[second] < ms[first]))
+                first = second;
+            *setting = first;
+            if (debug)
+                for (int c = 0; c < count; ++c)
+                    std::fprintf(stderr, "wagma placement: %s step, launch shape %d: %.3f ms%s\n", global ? "global" : "group", c,
+                                 ms[c], c == first ? " (kept)" : "");
+        };
+        static_assert(wagma_detail::kNumLaunchShapes <= 8 && wagma_detail::kNumCoopShapes <= 8, "ms[] above");
+        int count = 0;
+        const bool has_group = ctx->tau != 1, has_global = ctx->tau >= 1;
+        if (has_group)
+            keep_fastest(false);
+        if (has_global && !(has_group && shape_setting(ctx, true, &count) == shape_setting(ctx, false, &count)))
+            keep_fastest(true);
         (void)hipGetLastError();
     }
     return WAGMA_OK;

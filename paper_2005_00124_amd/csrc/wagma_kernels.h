@@ -51,7 +51,7 @@ struct StepParams {
     int log2_chunks;       // log2(members / streamed_chunk(lag)) for the streaming kernels
     int stripe_log2;       // log2 of the distance, in KiB, between a workgroup's wavefronts
     int xcd_chunk_log2;    // log2 of the run of consecutive tiles one XCD works on (0: 1 tile)
-    uint32_t map;          // not 0: replaces the two fields above, see chunk_of()
+    uint64_t map;          // not 0: replaces the two fields above, see slice_of()
     // per-tensor layout only (device tables)
     float* const* tw;            // [T][P] base pointers, index tensor * P + rank
     const float* const* tg;
@@ -370,22 +370,25 @@ __device__ __forceinline__ void streamed_body(const StepParams& p, const int32_t
 // contiguous tile).  Returns false for lanes and workgroups beyond the end.
 constexpr int kBlock = 256;  // threads per workgroup of every step kernel
 
-// Which 1 KiB piece (64 column slices) of a row wavefront `wave` of the workgroup for column tile
-// `tile` takes.  Workgroup b runs on XCD b mod 8, so bits [0,3) of `tile` are the XCD.
-//   map == 0: each XCD takes runs of 2^xcd_chunk_log2 consecutive tiles (the XCD number moves from
-//     tile bits [0,3) up to bits [j, j+3)), and the four wavefronts of a workgroup work
-//     2^stripe_log2 KiB apart inside 4 << stripe_log2 KiB.
-//   map != 0: eight 4-bit fields; bit k of x = (tile << 2 | wave) becomes bit (map >> 4k & 15) of the
-//     piece number, the higher bits of x stay (the fields are a permutation of 0..7).
-__device__ __forceinline__ int64_t chunk_of(const StepParams& p, int64_t tile, int64_t wave)
+// Which 16-byte column slice of a row lane `lane` of wavefront `wave` of the workgroup for column
+// tile `tile` takes.  Workgroup b runs on XCD b mod 8, so bits [0,3) of `tile` are the XCD.
+//   map == 0: a wavefront takes 64 consecutive slices (1 KiB); each XCD takes runs of
+//     2^xcd_chunk_log2 consecutive tiles (the XCD number moves from tile bits [0,3) up to bits
+//     [j, j+3)), and the four wavefronts of a workgroup work 2^stripe_log2 KiB apart inside
+//     4 << stripe_log2 KiB.
+//   map != 0: ten 4-bit fields, a permutation of 0..9.  With y = (tile << 2 | wave) << 2 | lane >> 4,
+//     bit k of y becomes bit 4 + field[k] of the slice number and the higher bits of y stay; 16
+//     lanes always take 16 consecutive slices (256 B).  A field of the two lane bits that is not
+//     0 or 1 splits a wavefront's 1 KiB into pieces that lie apart.
+__device__ __forceinline__ int64_t slice_of(const StepParams& p, int64_t tile, int64_t wave, int64_t lane)
 {
     if (p.map != 0) {
-        const int64_t x = (tile << 2) | wave;
-        int64_t chunk = x & ~int64_t(0xff);
+        const int64_t y = (((tile << 2) | wave) << 2) | (lane >> 4);
+        int64_t upper = y & ~int64_t(0x3ff);
 #pragma unroll
-        for (int k = 0; k < 8; ++k)
-            chunk |= ((x >> k) & 1) << ((p.map >> (4 * k)) & 15u);
-        return chunk;
+        for (int k = 0; k < 10; ++k)
+            upper |= ((y >> k) & 1) << ((p.map >> (4 * k)) & 15u);
+        return (upper << 4) | (lane & 15);
     }
     if (p.xcd_chunk_log2 > 0) {
         const int j = p.xcd_chunk_log2;
@@ -395,7 +398,7 @@ __device__ __forceinline__ int64_t chunk_of(const StepParams& p, int64_t tile, i
     }
     const int64_t super = tile >> p.stripe_log2;
     const int64_t within = tile & ((int64_t(1) << p.stripe_log2) - 1);
-    return ((super * 4 + wave) << p.stripe_log2) + within;
+    return ((((super * 4 + wave) << p.stripe_log2) + within) << 6) | lane;
 }
 
 __device__ __forceinline__ bool decode_block(const StepParams& p, int64_t& group, int64_t& col)
@@ -404,8 +407,8 @@ __device__ __forceinline__ bool decode_block(const StepParams& p, int64_t& group
     if (b >= p.blocks)
         return false;
     group = b / p.tiles;
-    static_assert(kBlock == 256, "chunk_of deals a tile out to four wavefronts");
-    col = chunk_of(p, b % p.tiles, threadIdx.x >> 6) * 64 + (threadIdx.x & 63);
+    static_assert(kBlock == 256, "slice_of deals a tile out to four wavefronts");
+    col = slice_of(p, b % p.tiles, threadIdx.x >> 6, threadIdx.x & 63);
     return col < p.nvec;
 }
 
@@ -448,11 +451,8 @@ __global__ void __launch_bounds__(64 * OCTETS, OCTETS <= 4 ? 2 : 1) step_rows_co
     const int64_t per_group = p.tiles * 4;
     const int64_t group = b / per_group;
     const int64_t piece = b % per_group;
-    const int64_t chunk = chunk_of(p, ((piece >> 5) << 3) | (piece & 7), (piece >> 3) & 3);
-    if (chunk * 64 >= p.nvec)
-        return;  // the whole workgroup: padding of the tile count
     const int octet = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int64_t col = chunk * 64 + lane;
+    const int64_t col = slice_of(p, ((piece >> 5) << 3) | (piece & 7), (piece >> 3) & 3, lane);
     const bool valid = col < p.nvec;  // the same lanes in every wavefront of the workgroup
     const FlatAddr at{p, (uint32_t)col * 4u};
     const int32_t* member = p.table + group * p.members + octet * 8;

@@ -176,9 +176,10 @@ OPTION_SETS = [
     ((lw.WAGMA_DEBUG_STRIPE_LOG2, 3),),
     ((lw.WAGMA_DEBUG_XCD_CHUNK_LOG2, 1),),
     ((lw.WAGMA_DEBUG_XCD_CHUNK_LOG2, 2),),
-    ((lw.WAGMA_DEBUG_MAP, 0x32017465),),
-    ((lw.WAGMA_DEBUG_MAP, 0x01234567), (lw.WAGMA_OPT_NONTEMPORAL, 0)),
-    ((lw.WAGMA_DEBUG_MAP, 0x73165402), (lw.WAGMA_DEBUG_FORCE_STREAM, 1)),
+    ((lw.WAGMA_DEBUG_MAP, 0x5423968710),),
+    ((lw.WAGMA_DEBUG_MAP, 0x0123456789), (lw.WAGMA_OPT_NONTEMPORAL, 0)),
+    ((lw.WAGMA_DEBUG_MAP, 0x9542368170), (lw.WAGMA_DEBUG_FORCE_STREAM, 1)),
+    ((lw.WAGMA_DEBUG_MAP, 0x2349618570),),
     ((lw.WAGMA_DEBUG_XCD_CHUNK_LOG2, 8), (lw.WAGMA_DEBUG_STRIPE_LOG2, 2)),
     ((lw.WAGMA_DEBUG_XCD_CHUNK_LOG2, 13), (lw.WAGMA_DEBUG_FORCE_STREAM, 1)),
     ((lw.WAGMA_DEBUG_STRIPE_LOG2, 6),),
@@ -526,6 +527,7 @@ def test_every_placement_mode_gives_the_same_bits(mode):
             mask = ctx.stale_mask(wl.seed, t, wl.stale_threshold)
             if t >= 4:
                 ctx.debug_set_option(lw.WAGMA_DEBUG_PLACED_SHAPE, others[t % 5])
+                ctx.debug_set_option(lw.WAGMA_DEBUG_PLACED_COOP_SHAPE, t % 2)
             ctx.step(w, g, m, pub, mask, wl.lr, wl.mu, t)
             orc.step_f32(P, S, wl.tau, t, ow, og, om, opub, mask, wl.lr, wl.mu)
             torch.cuda.synchronize()
