@@ -172,6 +172,7 @@ struct wagma_tensors {
     float* const* tm;
     float* const* tpub;
     const TileRef* tile_ref;
+    uint64_t map;       // how the slices of the mapped blocks of the tile table are dealt out (0: no such blocks)
 };
 
 namespace {
@@ -557,21 +558,35 @@ int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64
     *out = nullptr;
     if (!ctx || T < 1 || T > (1 << 20) || !sizes || !w || !g || !m || !pub)
         return WAGMA_EINVAL;
-    int64_t total = 0, tiles = 0;
+    // Every whole 256 KiB of a tensor (64 tiles of whole slices) becomes a mapped block: its slices
+    // are dealt out to the lanes of 64 workgroups by the launch shape for a caller's arrays (a
+    // plan's tensors are always the caller's), as in the flat layout; what is left of a tensor is
+    // cut into contiguous 4 KiB tiles.  Forcing a stripe or an XCD run length switches the blocks
+    // off, forcing a map chooses theirs.
+    constexpr int64_t kBlockSlices = 64 * kTensorBlock;
+    const uint64_t block_map = ctx->opt_map != 0 ? ctx->opt_map
+                               : (ctx->opt_xcd_chunk_log2 >= 0 || ctx->stripe_forced)
+                                   ? 0
+                                   : wagma_detail::kLaunchShapes[wagma_detail::kForeignShape].map;
+    int64_t total = 0, mapped_tiles = 0, plain_tiles = 0;
     for (int k = 0; k < T; ++k) {
         if (sizes[k] < 1 || sizes[k] > kMaxN)
             return WAGMA_EINVAL;
         total += sizes[k];
-        tiles += ((sizes[k] + 3) / 4 + kTensorBlock - 1) / kTensorBlock;
+        const int64_t blocks = block_map != 0 ? sizes[k] / 4 / kBlockSlices : 0;
+        mapped_tiles += 64 * blocks;
+        plain_tiles += ((sizes[k] + 3) / 4 - blocks * kBlockSlices + kTensorBlock - 1) / kTensorBlock;
     }
-    // Workgroup b of a launch runs on XCD b mod 8.  As in the flat layout, each XCD gets runs of
-    // consecutive 4 KiB tiles (measured best here: runs of 8, twice the flat layout's value; tile
-    // by tile is 2-5 % slower on every kind of array): the table is padded with empty tiles to
-    // whole rounds of 8 runs and permuted below.
+    // Workgroup b of a launch runs on XCD b mod 8.  The mapped blocks come first in the table (64
+    // slots each, so that the low three bits of a tile's number in its block are its XCD); of the
+    // contiguous tiles each XCD gets runs of consecutive ones (measured best: runs of 8; tile by
+    // tile is 2-5 % slower on every kind of array): that part of the table is padded with empty
+    // tiles to whole rounds of 8 runs and permuted below.
     const int xcd_chunk_log2 = ctx->opt_xcd_chunk_log2 < 0 ? 2 : ctx->opt_xcd_chunk_log2;
     const int run_log2 = xcd_chunk_log2 > 0 ? (xcd_chunk_log2 < 7 ? xcd_chunk_log2 + 1 : 8) : 0;
     const int64_t round_tiles = int64_t(kNumXcd) << run_log2;
-    tiles = (tiles + round_tiles - 1) / round_tiles * round_tiles;
+    plain_tiles = (plain_tiles + round_tiles - 1) / round_tiles * round_tiles;
+    int64_t tiles = mapped_tiles + plain_tiles;
     if (total != ctx->n || tiles * (int64_t)ctx->P > 0x7fffffff)
         return WAGMA_EINVAL;
     const size_t slots = (size_t)ctx->P * (size_t)T;
@@ -613,30 +628,35 @@ int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64
     }
     TileRef* refs = (TileRef*)(host + 4 * table_bytes);
     {
-        // slot i of the table (the tile of workgroups i, i + tiles, ...) holds tile number
-        // `linear` of the walk through the tensors: the XCD number i mod 8 moves from bits [0,3)
-        // of the tile number up to bits [run_log2, run_log2 + 3)
-        std::vector<TileRef> in_order;
+        std::vector<TileRef> in_order;  // the contiguous tiles, tensor by tensor
         try {
-            in_order.reserve((size_t)tiles);
+            in_order.reserve((size_t)plain_tiles);
         } catch (const std::bad_alloc&) {
             std::free(host);
             delete plan;
             return WAGMA_ENOMEM;
         }
+        int64_t at = 0;
         for (int k = 0; k < T; ++k) {
             const int64_t slices = (sizes[k] + 3) / 4;
-            for (int64_t first = 0; first < slices; first += kTensorBlock)
-                in_order.push_back(TileRef{k, (uint32_t)sizes[k], first});
+            const int64_t blocks = block_map != 0 ? sizes[k] / 4 / kBlockSlices : 0;
+            for (int64_t b = 0; b < blocks; ++b)
+                for (uint32_t j = 0; j < 64; ++j)
+                    refs[at++] = TileRef{k, (uint32_t)sizes[k], (uint32_t)(b * kBlockSlices), j + 1};
+            for (int64_t first = blocks * kBlockSlices; first < slices; first += kTensorBlock)
+                in_order.push_back(TileRef{k, (uint32_t)sizes[k], (uint32_t)first, 0u});
         }
         // an empty tile has size 0: every lane of it returns at once
-        while ((int64_t)in_order.size() < tiles)
-            in_order.push_back(TileRef{0, 0u, 0});
-        for (int64_t i = 0; i < tiles; ++i) {
+        while ((int64_t)in_order.size() < plain_tiles)
+            in_order.push_back(TileRef{0, 0u, 0u, 0u});
+        // slot i of this part (the tile of workgroups mapped_tiles + i, + tiles, ...) holds tile
+        // number `linear` of the walk: the XCD number i mod 8 (mapped_tiles is a multiple of 64)
+        // moves from bits [0,3) of the tile number up to bits [run_log2, run_log2 + 3)
+        for (int64_t i = 0; i < plain_tiles; ++i) {
             const int64_t xcd = i & (kNumXcd - 1), hi = i >> 3;
             const int64_t linear =
                 ((hi >> run_log2) << (run_log2 + 3)) | (xcd << run_log2) | (hi & ((int64_t(1) << run_log2) - 1));
-            refs[i] = in_order[(size_t)linear];
+            refs[mapped_tiles + i] = in_order[(size_t)linear];
         }
     }
     char* dev = nullptr;
@@ -660,6 +680,7 @@ int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64
     plan->tm = (float* const*)(dev + 2 * table_bytes);
     plan->tpub = (float* const*)(dev + 3 * table_bytes);
     plan->tile_ref = (const TileRef*)(dev + 4 * table_bytes);
+    plan->map = block_map;
     *out = plan;
     return WAGMA_OK;
 }
@@ -704,6 +725,7 @@ int wagma_step_tensors_lag(wagma_ctx* ctx, const wagma_tensors* plan, const uint
     p.tm = plan->tm;
     p.tpub = plan->tpub;
     p.tile_ref = plan->tile_ref;
+    p.map = plan->map;
     p.num_ranks = ctx->P;
     p.tiles = plan->tiles;  // a multiple of 8 (whole XCD rounds)
     p.blocks = (int64_t)(ctx->P / p.members) * p.tiles;

@@ -26,9 +26,11 @@ constexpr int kNumXcd = 8;      // accelerator complex dies of an MI355X
 constexpr int64_t kMaxN = int64_t(1) << 31;
 
 struct TileRef {
-    int32_t tensor;       // which tensor a tile of the per-tensor layout belongs to
-    uint32_t size;        // floats in that tensor (0: an empty tile that pads the table)
-    int64_t first_slice;  // first 16-byte slice of the tile inside that tensor
+    int32_t tensor;         // which tensor a tile of the per-tensor layout belongs to
+    uint32_t size;          // floats in that tensor (0: an empty tile that pads the table)
+    uint32_t first_slice;   // first 16-byte slice of the tile inside that tensor, or of the block below
+    uint32_t tile_in_block; // 0: the tile is 256 consecutive slices.  k + 1: tile k of a block of 64 tiles
+                            // (256 KiB, whole slices only) whose slices are dealt out by the plan's map
 };
 
 struct StepParams {
@@ -380,16 +382,20 @@ constexpr int kBlock = 256;  // threads per workgroup of every step kernel
 //     bit k of y becomes bit 4 + field[k] of the slice number and the higher bits of y stay; 16
 //     lanes always take 16 consecutive slices (256 B).  A field of the two lane bits that is not
 //     0 or 1 splits a wavefront's 1 KiB into pieces that lie apart.
+__device__ __forceinline__ int64_t mapped_slice(uint64_t map, int64_t tile, int64_t wave, int64_t lane)
+{
+    const int64_t y = (((tile << 2) | wave) << 2) | (lane >> 4);
+    int64_t upper = y & ~int64_t(0x3ff);
+#pragma unroll
+    for (int k = 0; k < 10; ++k)
+        upper |= ((y >> k) & 1) << ((map >> (4 * k)) & 15u);
+    return (upper << 4) | (lane & 15);
+}
+
 __device__ __forceinline__ int64_t slice_of(const StepParams& p, int64_t tile, int64_t wave, int64_t lane)
 {
-    if (p.map != 0) {
-        const int64_t y = (((tile << 2) | wave) << 2) | (lane >> 4);
-        int64_t upper = y & ~int64_t(0x3ff);
-#pragma unroll
-        for (int k = 0; k < 10; ++k)
-            upper |= ((y >> k) & 1) << ((p.map >> (4 * k)) & 15u);
-        return (upper << 4) | (lane & 15);
-    }
+    if (p.map != 0)
+        return mapped_slice(p.map, tile, wave, lane);
     if (p.xcd_chunk_log2 > 0) {
         const int j = p.xcd_chunk_log2;
         const int64_t xcd = tile & (kNumXcd - 1);
@@ -472,6 +478,15 @@ __global__ void __launch_bounds__(64 * OCTETS, OCTETS <= 4 ? 2 : 1) step_rows_co
     rows_average<8, NT, LAG, v4f>(p, member, at, w_prime, tree_sum<OCTETS, v4f>(sums));
 }
 
+// The 16-byte slice, inside its tensor, that lane `lane` of wavefront (or quarter) `wave` of a tile of
+// the per-tensor layout takes.
+__device__ __forceinline__ int64_t tensor_slice(const StepParams& p, const TileRef& ref, int64_t wave, int64_t lane)
+{
+    if (ref.tile_in_block == 0)
+        return (int64_t)ref.first_slice + wave * 64 + lane;
+    return (int64_t)ref.first_slice + mapped_slice(p.map, ref.tile_in_block - 1, wave, lane);
+}
+
 // Per-tensor layout.  Workgroup b owns tile b % tiles of group b / tiles; the tile table
 // names the tensor, its size and the tile's first 16-byte slice inside it.  A lane whose slice is
 // cut off by the end of the tensor does the remaining 1..3 elements one by one; nothing
@@ -482,7 +497,7 @@ __global__ void __launch_bounds__(kBlock, 2) step_tensors_in_registers(const Ste
     const int64_t group = blockIdx.x / p.tiles;
     const TileRef ref = p.tile_ref[blockIdx.x % p.tiles];
     const int64_t size = ref.size;
-    const int64_t first = (ref.first_slice + threadIdx.x) * 4;
+    const int64_t first = tensor_slice(p, ref, threadIdx.x >> 6, threadIdx.x & 63) * 4;
     if (first >= size)
         return;
     const int32_t* member = p.table + group * S;
@@ -503,7 +518,7 @@ __global__ void __launch_bounds__(kBlock, 2) step_tensors_streamed(const StepPar
     const int64_t group = blockIdx.x / p.tiles;
     const TileRef ref = p.tile_ref[blockIdx.x % p.tiles];
     const int64_t size = ref.size;
-    const int64_t first = (ref.first_slice + threadIdx.x) * 4;
+    const int64_t first = tensor_slice(p, ref, threadIdx.x >> 6, threadIdx.x & 63) * 4;
     if (first >= size)
         return;
     const int32_t* member = p.table + group * p.members;
@@ -536,11 +551,14 @@ __global__ void __launch_bounds__(64 * OCTETS, OCTETS <= 4 ? 2 : 1) step_tensors
     const int64_t piece = b % per_group;
     const TileRef ref = p.tile_ref[((piece >> 5) << 3) | (piece & 7)];
     const int64_t size = ref.size;
-    const int64_t first_slice = ref.first_slice + ((piece >> 3) & 3) * 64;
-    if (first_slice * 4 >= size)
+    const int64_t quarter = (piece >> 3) & 3;
+    // where a contiguous tile's quarter begins; in a mapped block (whole slices only, nothing cut
+    // off) the lanes' slices lie apart and only `first` below matters
+    const int64_t first_slice = (int64_t)ref.first_slice + quarter * 64;
+    if (ref.tile_in_block == 0 && first_slice * 4 >= size)
         return;  // the whole workgroup: this quarter lies beyond the tensor (or the tile is padding)
     const int octet = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int64_t first = (first_slice + lane) * 4;
+    const int64_t first = tensor_slice(p, ref, quarter, lane) * 4;
     const bool whole = first + 4 <= size;      // the same lanes in every wavefront of the workgroup
     const bool cut = !whole && first < size;   // at most one lane, and only in the tensor's last quarter
     const int32_t* member = p.table + group * p.members + octet * 8;
@@ -562,7 +580,9 @@ __global__ void __launch_bounds__(64 * OCTETS, OCTETS <= 4 ? 2 : 1) step_tensors
     }
     // the elements of a slice cut off by the tensor's end, if that slice is in this quarter
     const int64_t cut_slice = size / 4;
-    const int rounds = (size % 4 != 0 && cut_slice >= first_slice && cut_slice < first_slice + 64) ? (int)(size % 4) : 0;
+    const int rounds = (ref.tile_in_block == 0 && size % 4 != 0 && cut_slice >= first_slice && cut_slice < first_slice + 64)
+                           ? (int)(size % 4)
+                           : 0;
     for (int k = 0; k < rounds; ++k) {
         const TensorAddr at{p, ref.tensor, (uint32_t)(first + k)};
         float w_prime[8];

@@ -41,7 +41,7 @@ def to_rows(arrays):
     return np.stack([torch.cat(t).cpu().numpy() for t in arrays])
 
 
-def run_tensor_case(P, S, sizes, tau, iters, q, seed, fixed_groups=False):
+def run_tensor_case(P, S, sizes, tau, iters, q, seed, fixed_groups=False, options=()):
     say("tensor case P=%d S=%d T=%d n=%d tau=%d iters=%d q=%.2f seed=%d" % (P, S, len(sizes), sum(sizes), tau, iters, q, seed))
     n = sum(sizes)
     gen = torch.Generator(device="cuda")
@@ -49,6 +49,8 @@ def run_tensor_case(P, S, sizes, tau, iters, q, seed, fixed_groups=False):
     with lw.Wagma(P, S, n, tau) as ctx:
         if fixed_groups:
             ctx.set_grouping(lw.WAGMA_GROUPING_FIXED)
+        for option, value in options:
+            ctx.debug_set_option(option, value)
         (w, gw), (g, gg), (m, gm), (pub, gp) = (make_arrays(P, sizes, gen, s) for s in (0.05, 0.01, 0.01, 0.05))
         ow, om, opub = to_rows(w), to_rows(m), to_rows(pub)
         thr = min(int(q * 2 ** 32), 2 ** 32 - 1)
@@ -87,6 +89,22 @@ def test_tensors_variants():
     run_tensor_case(16, 4, [33, 1024, 9], tau=1, iters=3, q=0.5, seed=8)            # always global
     run_tensor_case(32, 8, [4097, 130], tau=0, iters=6, q=0.3, seed=9, fixed_groups=True)
     run_tensor_case(8, 1, [17], tau=2, iters=4, q=0.5, seed=10)                     # one tensor, S = 1
+
+
+BLOCKS = [65536, 3, 65536 + 4 * 300 + 2, 2 * 65536 + 1, 65535, 5]   # whole 256 KiB blocks, with and without a rest
+
+
+@pytest.mark.parametrize("P,S", [(16, 4), (32, 8), (16, 16), (32, 32), (8, 1)])
+def test_tensors_with_mapped_blocks(P, S):
+    """Every whole 256 KiB of a tensor is dealt out by the launch shape's map, the rest in 4 KiB tiles."""
+    run_tensor_case(P, S, BLOCKS, tau=3, iters=4, q=0.3, seed=300 + P + S)
+
+
+def test_tensors_block_options():
+    run_tensor_case(32, 8, BLOCKS, tau=0, iters=3, q=0.3, seed=41, options=((lw.WAGMA_DEBUG_MAP, 0x5329618470),))
+    run_tensor_case(16, 16, BLOCKS, tau=0, iters=3, q=0.3, seed=42, options=((lw.WAGMA_DEBUG_MAP, 0x0123456789),))
+    run_tensor_case(32, 8, BLOCKS, tau=2, iters=3, q=0.3, seed=43, options=((lw.WAGMA_DEBUG_XCD_CHUNK_LOG2, 2),))   # no blocks
+    run_tensor_case(32, 32, BLOCKS, tau=2, iters=3, q=0.3, seed=44, options=((lw.WAGMA_DEBUG_STRIPE_LOG2, 2),))     # no blocks
 
 
 def test_plan_validation():
