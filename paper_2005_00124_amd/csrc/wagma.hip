@@ -96,14 +96,19 @@ void set_defaults(wagma_ctx* ctx, int P, int S, int G, int g, int64_t n, int tau
     ctx->tau = tau;
     ctx->n = n;
     ctx->period = (g == 0 || G == 0) ? 1 : G / gcd_int(g, G);
-    // Row stride.  Measured on MI355X: rows on 16 KiB boundaries run about 1% faster than rows
-    // on 256 B boundaries (and rows off a 128 B boundary up to 10% slower); strides that are a
-    // multiple of 1 MiB put all member rows of a group on the same memory channels (20% slower),
-    // so such a stride is skewed by a few row alignments.  Small models keep the padding small.
-    const int64_t row_align = n >= (int64_t(1) << 20) ? 4096 : 64;  // floats
+    // Row stride.  Measured on MI355X: the launch shapes that split a wavefront's 1 KiB into two
+    // pieces 32 KiB apart (kLaunchShapes) gain what they gain only where the two pieces differ in
+    // address bit 15 and nothing else, so rows must begin on 64 KiB boundaries of the arrays, which
+    // the allocators put on 2 MiB boundaries (workload with rows at odd multiples of 16 KiB: 6238
+    // GB/s, on 64 KiB boundaries: 6615).  With a wavefront's 1 KiB in one piece: rows on 16 KiB
+    // boundaries run about 1 % faster than rows on 256 B boundaries (and rows off a 128 B boundary
+    // up to 10 % slower), and strides that are a multiple of 1 MiB put all member rows of a group
+    // on the same memory channels (20 % slower), so such a stride is skewed by one row alignment.
+    // Small models keep the padding small.
+    const int64_t row_align = n >= (int64_t(1) << 18) ? 16384 : 64;  // floats
     ctx->ld = (n + row_align - 1) / row_align * row_align;
     if ((ctx->ld * 4) % (int64_t(1) << 20) == 0)
-        ctx->ld += 5 * row_align;
+        ctx->ld += row_align;
     // Streaming hints help only when the arrays stream from HBM: four arrays that fit in the
     // 256 MB Infinity Cache together run 6 % faster without them (P=4, n=2^20).
     ctx->opt_nontemporal = (size_t)4 * (size_t)P * (size_t)ctx->ld * sizeof(float) > (size_t(256) << 20) ? 1 : 0;
