@@ -563,24 +563,55 @@ int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64
     *out = nullptr;
     if (!ctx || T < 1 || T > (1 << 20) || !sizes || !w || !g || !m || !pub)
         return WAGMA_EINVAL;
+    const size_t slots = (size_t)ctx->P * (size_t)T;
+    for (size_t i = 0; i < slots; ++i) {
+        if (!w[i] || !g[i] || !m[i] || !pub[i])
+            return WAGMA_EINVAL;
+        if ((((uintptr_t)w[i]) | ((uintptr_t)g[i]) | ((uintptr_t)m[i]) | ((uintptr_t)pub[i])) & 15u)
+            return WAGMA_EINVAL;
+    }
     // Every whole 256 KiB of a tensor (64 tiles of whole slices) becomes a mapped block: its slices
     // are dealt out to the lanes of 64 workgroups by the launch shape for a caller's arrays (a
     // plan's tensors are always the caller's), as in the flat layout; what is left of a tensor is
-    // cut into contiguous 4 KiB tiles.  Forcing a stripe or an XCD run length switches the blocks
-    // off, forcing a map chooses theirs.
+    // cut into contiguous 4 KiB tiles.  That shape pairs pieces whose addresses differ in bit 15
+    // only, so the blocks begin on a 64 KiB boundary of the address space where the tensor crosses
+    // one at the same place in every process and array (`lead` slices into the tensor), else at
+    // the tensor's first element.  Forcing a stripe or an XCD run length switches the blocks off,
+    // forcing a map chooses theirs.
     constexpr int64_t kBlockSlices = 64 * kTensorBlock;
     const uint64_t block_map = ctx->opt_map != 0 ? ctx->opt_map
                                : (ctx->opt_xcd_chunk_log2 >= 0 || ctx->stripe_forced)
                                    ? 0
                                    : wagma_detail::kLaunchShapes[wagma_detail::kForeignShape].map;
+    auto blocks_of = [&](int k, int64_t& lead, int64_t& blocks) {
+        lead = 0;
+        blocks = 0;
+        if (block_map == 0)
+            return;
+        const uintptr_t phase = (uintptr_t)w[k] & 65535u;
+        bool same = true;
+        for (int r = 0; r < ctx->P && same; ++r) {
+            const size_t i = (size_t)r * T + k;
+            same = ((uintptr_t)w[i] & 65535u) == phase && ((uintptr_t)g[i] & 65535u) == phase &&
+                   ((uintptr_t)m[i] & 65535u) == phase && ((uintptr_t)pub[i] & 65535u) == phase;
+        }
+        const int64_t whole = sizes[k] / 4;
+        if (same)
+            lead = (int64_t)((65536u - phase) & 65535u) / 16;
+        if (whole - lead < kBlockSlices)
+            lead = 0;
+        blocks = (whole - lead) / kBlockSlices;
+    };
     int64_t total = 0, mapped_tiles = 0, plain_tiles = 0;
     for (int k = 0; k < T; ++k) {
         if (sizes[k] < 1 || sizes[k] > kMaxN)
             return WAGMA_EINVAL;
         total += sizes[k];
-        const int64_t blocks = block_map != 0 ? sizes[k] / 4 / kBlockSlices : 0;
+        int64_t lead, blocks;
+        blocks_of(k, lead, blocks);
         mapped_tiles += 64 * blocks;
-        plain_tiles += ((sizes[k] + 3) / 4 - blocks * kBlockSlices + kTensorBlock - 1) / kTensorBlock;
+        plain_tiles += (lead + kTensorBlock - 1) / kTensorBlock +
+                       ((sizes[k] + 3) / 4 - lead - blocks * kBlockSlices + kTensorBlock - 1) / kTensorBlock;
     }
     // Workgroup b of a launch runs on XCD b mod 8.  The mapped blocks come first in the table (64
     // slots each, so that the low three bits of a tile's number in its block are its XCD); of the
@@ -594,13 +625,6 @@ int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64
     int64_t tiles = mapped_tiles + plain_tiles;
     if (total != ctx->n || tiles * (int64_t)ctx->P > 0x7fffffff)
         return WAGMA_EINVAL;
-    const size_t slots = (size_t)ctx->P * (size_t)T;
-    for (size_t i = 0; i < slots; ++i) {
-        if (!w[i] || !g[i] || !m[i] || !pub[i])
-            return WAGMA_EINVAL;
-        if ((((uintptr_t)w[i]) | ((uintptr_t)g[i]) | ((uintptr_t)m[i]) | ((uintptr_t)pub[i])) & 15u)
-            return WAGMA_EINVAL;
-    }
     int device = -1;
     hipError_t e = hipGetDevice(&device);
     if (e != hipSuccess)
@@ -644,11 +668,15 @@ int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64
         int64_t at = 0;
         for (int k = 0; k < T; ++k) {
             const int64_t slices = (sizes[k] + 3) / 4;
-            const int64_t blocks = block_map != 0 ? sizes[k] / 4 / kBlockSlices : 0;
+            int64_t lead, blocks;
+            blocks_of(k, lead, blocks);
+            // the tiles before the first block end where it begins: to them the tensor is that short
+            for (int64_t first = 0; first < lead; first += kTensorBlock)
+                in_order.push_back(TileRef{k, (uint32_t)(lead * 4), (uint32_t)first, 0u});
             for (int64_t b = 0; b < blocks; ++b)
                 for (uint32_t j = 0; j < 64; ++j)
-                    refs[at++] = TileRef{k, (uint32_t)sizes[k], (uint32_t)(b * kBlockSlices), j + 1};
-            for (int64_t first = blocks * kBlockSlices; first < slices; first += kTensorBlock)
+                    refs[at++] = TileRef{k, (uint32_t)sizes[k], (uint32_t)(lead + b * kBlockSlices), j + 1};
+            for (int64_t first = lead + blocks * kBlockSlices; first < slices; first += kTensorBlock)
                 in_order.push_back(TileRef{k, (uint32_t)sizes[k], (uint32_t)first, 0u});
         }
         // an empty tile has size 0: every lane of it returns at once

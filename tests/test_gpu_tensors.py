@@ -21,9 +21,24 @@ def bits(a):
     return np.ascontiguousarray(a).view(np.uint32)
 
 
-def make_arrays(P, sizes, gen, scale):
-    """For every process a list of tensors, each inside its own guarded allocation."""
+def make_arrays(P, sizes, gen, scale, arena=False):
+    """For every process a list of tensors, each inside its own guarded allocation; with `arena`,
+    views into one row per process (rows 64 KiB-multiples apart: a tensor then crosses the 64 KiB
+    boundaries of the address space at the same place in every process), sentinels between them."""
     arrays, guards = [], []
+    if arena:
+        row = (sum(sizes) + (len(sizes) + 1) * GUARD + 16383) // 16384 * 16384
+        slab = torch.full((P, row), 777.0, device="cuda")
+        for p in range(P):
+            tensors, at = [], GUARD
+            for size in sizes:
+                t = slab[p, at:at + size]
+                t.normal_(0.0, scale, generator=gen)
+                tensors.append(t)
+                guards.append(slab[p, at - GUARD:at + size + GUARD])
+                at += size + GUARD + (-size) % 4
+            arrays.append(tensors)
+        return arrays, guards
     for _p in range(P):
         tensors = []
         for size in sizes:
@@ -41,7 +56,7 @@ def to_rows(arrays):
     return np.stack([torch.cat(t).cpu().numpy() for t in arrays])
 
 
-def run_tensor_case(P, S, sizes, tau, iters, q, seed, fixed_groups=False, options=()):
+def run_tensor_case(P, S, sizes, tau, iters, q, seed, fixed_groups=False, options=(), arena=False):
     say("tensor case P=%d S=%d T=%d n=%d tau=%d iters=%d q=%.2f seed=%d" % (P, S, len(sizes), sum(sizes), tau, iters, q, seed))
     n = sum(sizes)
     gen = torch.Generator(device="cuda")
@@ -51,7 +66,7 @@ def run_tensor_case(P, S, sizes, tau, iters, q, seed, fixed_groups=False, option
             ctx.set_grouping(lw.WAGMA_GROUPING_FIXED)
         for option, value in options:
             ctx.debug_set_option(option, value)
-        (w, gw), (g, gg), (m, gm), (pub, gp) = (make_arrays(P, sizes, gen, s) for s in (0.05, 0.01, 0.01, 0.05))
+        (w, gw), (g, gg), (m, gm), (pub, gp) = (make_arrays(P, sizes, gen, s, arena) for s in (0.05, 0.01, 0.01, 0.05))
         ow, om, opub = to_rows(w), to_rows(m), to_rows(pub)
         thr = min(int(q * 2 ** 32), 2 ** 32 - 1)
         with ctx.tensor_plan(w, g, m, pub) as plan:
@@ -98,6 +113,13 @@ BLOCKS = [65536, 3, 65536 + 4 * 300 + 2, 2 * 65536 + 1, 65535, 5]   # whole 256 
 def test_tensors_with_mapped_blocks(P, S):
     """Every whole 256 KiB of a tensor is dealt out by the launch shape's map, the rest in 4 KiB tiles."""
     run_tensor_case(P, S, BLOCKS, tau=3, iters=4, q=0.3, seed=300 + P + S)
+
+
+@pytest.mark.parametrize("P,S", [(16, 4), (32, 8), (16, 16), (32, 32)])
+def test_tensors_blocks_on_address_boundaries(P, S):
+    """Tensors that are views into rows 64 KiB-multiples apart: the mapped blocks begin on a 64 KiB
+    boundary of the address space, the slices before it are contiguous tiles."""
+    run_tensor_case(P, S, [70001, 65536 + 8, 3, 2 * 65536 + 20000, 1000], tau=3, iters=4, q=0.3, seed=500 + P + S, arena=True)
 
 
 def test_tensors_block_options():
