@@ -73,7 +73,7 @@ struct LaunchShape {
 //   3  l5 t3 x0 x1 t5 w0 x2 l4 w1 t4   a wavefront takes 512 B and the 512 B that lie 32 KiB further on,
 //                                      the wavefronts of a workgroup 8 KiB and 64 KiB apart
 //   4  l5 x0 x1 t3 w0 t5 x2 l4 w1 t4   as 3, other places for the XCD bits
-//   5  l4 x0 t3 t4 w0 t5 x1 l5 w1 x2   as 3 with 256 B pieces
+//   5  l4 x0 t3 t4 w0 t5 x1 l5 w1 x2   as 3, the other lane bit chooses the piece; other places for the rest
 constexpr int kNumLaunchShapes = 6;
 constexpr LaunchShape kLaunchShapes[kNumLaunchShapes] = {
     {0u, 2, 2}, {0u, 2, 0}, {0x7328965410ull, 0, 0}, {0x4916328507ull, 0, 0}, {0x5936218407ull, 0, 0},
@@ -81,7 +81,7 @@ constexpr LaunchShape kLaunchShapes[kNumLaunchShapes] = {
 constexpr int kForeignShape = 3;  // for arrays the library did not place
 // The kernel for groups of 16 to 64 rows:
 //   0  l4 l5 t3 t4 w0 w1 t5 x0 x1 x2   1 KiB per wavefront, 4 KiB stripe, runs of 8 tiles per XCD
-//   1  l4 x0 x1 t4 w0 t5 t3 l5 w1 x2   256 B pieces 32 KiB apart
+//   1  l4 x0 x1 t4 w0 t5 t3 l5 w1 x2   a wavefront takes 512 B and the 512 B that lie 32 KiB further on
 constexpr int kNumCoopShapes = 2;
 constexpr LaunchShape kCoopShapes[kNumCoopShapes] = {{0u, 2, 3}, {0x5369218470ull, 0, 0}};
 
