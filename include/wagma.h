@@ -283,8 +283,10 @@ int wagma_lag_masks(const wagma_ctx* ctx, uint64_t seed, int64_t iter, int windo
  *                       the step kernel itself (no assumption about regions);
  *   WAGMA_PLACE_PLAIN   four ordinary allocations.
  * Where physical memory is scattered (a GPU that has been in use), plain allocations are
- * already mixed over the regions and may be the fastest, so by default (WAGMA_PLACE_AUTO) the
- * SEARCH, CHUNKS and PLAIN placements are each timed with the step kernel and the fastest is kept.
+ * already mixed over the regions and may be the fastest, and with the launch shapes the step
+ * uses now arrays that lie in one region are the fastest for its main kernel, so by default
+ * (WAGMA_PLACE_AUTO) the PLAIN, SEARCH and CHUNKS placements are each timed with the step kernels
+ * and the fastest is kept.
  * On the arrays it hands out the call also measures which way of dealing the column tiles out to
  * the chip's eight dies and to the wavefronts of a workgroup is fastest for steps on these
  * arrays, and the context uses that one whenever a step is given exactly these four arrays

@@ -614,25 +614,25 @@ int wagma_alloc_buffers(wagma_ctx* ctx, float** w, float** g, float** m, float**
     const size_t bytes = (size_t)ctx->P * (size_t)ctx->ld * sizeof(float);
     const bool debug = std::getenv("WAGMA_DEBUG_PLACEMENT") != nullptr;
 
-    // Candidate placements in the order timed search, chunks, whole arrays, plain.  With
-    // WAGMA_PLACE_AUTO each one that can be had (whole arrays excepted, see below) is timed with
-    // the step kernel itself and the fastest is kept (at most two sets of arrays exist at a
-    // time); a fixed mode takes the first that works.
+    // With WAGMA_PLACE_AUTO: four ordinary allocations first, while the memory is as the caller
+    // left it (on a GPU with untouched memory they lie in one HBM region, which the kernel that
+    // holds a group in registers likes best), then the timed search, then the arrays built from
+    // chunks (placement by whole arrays is left out: the timed search covers what it finds).  Each
+    // is judged with the step kernels themselves and must be 1 % faster than what is kept to
+    // replace it; at most two sets of arrays exist at a time.  A fixed mode takes that mode if it
+    // can be had, else ordinary allocations.
     const int mode = bytes >= wagma_placement::kPlacementMinBytes ? ctx->opt_placement : WAGMA_PLACE_PLAIN;
-    const int order[4] = {WAGMA_PLACE_SEARCH, WAGMA_PLACE_CHUNKS, WAGMA_PLACE_ARRAYS, WAGMA_PLACE_PLAIN};
+    const int auto_order[3] = {WAGMA_PLACE_PLAIN, WAGMA_PLACE_SEARCH, WAGMA_PLACE_CHUNKS};
+    const int fixed_order[3] = {mode, WAGMA_PLACE_PLAIN, -1};
     ArraySet best;
-    for (int candidate : order) {
-        if (mode != WAGMA_PLACE_AUTO && candidate != mode && candidate != WAGMA_PLACE_PLAIN)
-            continue;
-        if (mode != WAGMA_PLACE_AUTO && best.ptr[0])
+    for (int candidate : (mode == WAGMA_PLACE_AUTO ? auto_order : fixed_order)) {
+        if (candidate < 0 || (mode != WAGMA_PLACE_AUTO && best.ptr[0]))
             break;  // a fixed mode: the first placement that worked
         size_t free_b = 0, total_b = 0;
         if (best.ptr[0] && (hipMemGetInfo(&free_b, &total_b) != hipSuccess || free_b < 4 * bytes + (size_t(4) << 30)))
             break;  // no room for a second set to compare with
         ArraySet trial;
         bool ok = false;
-        if (candidate == WAGMA_PLACE_ARRAYS && mode == WAGMA_PLACE_AUTO)
-            continue;  // the timed search covers what the probe-guided one finds
         if (candidate == WAGMA_PLACE_SEARCH)
             ok = place_search(ctx, bytes, debug, trial);
         else if (candidate == WAGMA_PLACE_CHUNKS)
