@@ -280,7 +280,6 @@ int step_flat(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub, co
         kind = FlatKernel::streamed;
     else if (p.members > kRegisterRows)
         kind = FlatKernel::cooperative;
-    p.log2_chunks = kind == FlatKernel::streamed ? exact_log2(p.members / streamed_chunk(lag)) : 0;
     p.stripe_log2 = ctx->opt_stripe_log2;
     p.xcd_chunk_log2 = ctx->opt_xcd_chunk_log2;
     p.map = ctx->opt_map;
@@ -298,24 +297,30 @@ int step_flat(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub, co
         // pub in three regions all shapes are within 1 % of each other, in an order that changes
         // with the box and the workload.  A caller's arrays get shape 3, within 0.6 % of the best
         // in every case measured; the library's own arrays get what wagma_alloc_buffers measured on
-        // them (a forced iteration is that measurement itself).  The kernel that deals a group's
-        // rows out to the wavefronts of a workgroup: with two wavefronts the split shape gains up to
-        // 24 % on arrays in one region and stays within 3 % elsewhere, with four or eight it loses
-        // 12 % on arrays in three regions: a caller's arrays get it for groups of 16 only.  The
-        // row-streaming kernel keeps the 4 KiB stripe with runs of 4 tiles per XCD.
+        // them (a forced iteration is that measurement itself).  Groups of 16 to 64 rows, dealt out
+        // to the wavefronts of a workgroup: with two wavefronts the split shape gains up to 24 % on
+        // arrays in one region and stays within 3 % elsewhere; with four or eight the kernel runs
+        // at 5100 GB/s on arrays in one region and at 6380 on arrays in three with its first
+        // shape, at 5600 on both with the split one, and the row-streaming kernel with shape 3 at
+        // 6180 on both: a caller's arrays get the split shape for groups of 16 and the
+        // row-streaming kernel for larger ones.  For groups above 64 rows the row-streaming kernel
+        // keeps the 4 KiB stripe with runs of 4 tiles per XCD.
         const bool own = force != Force::none || (ctx->placed[0] && w == ctx->placed[0] && g == ctx->placed[1] &&
                                                   m == ctx->placed[2] && pub == ctx->placed[3]);
         LaunchShape shape = {0u, ctx->opt_stripe_log2, 2};
         if (kind == FlatKernel::in_registers)
             shape = kLaunchShapes[own ? ctx->placed_shape : kForeignShape];
         else if (kind == FlatKernel::cooperative)
-            shape = kCoopShapes[own ? ctx->placed_coop_shape : (p.members == 16 ? 1 : 0)];
+            shape = kCoopShapes[own ? ctx->placed_coop_shape : (p.members == 16 ? 1 : 2)];
+        if (shape.row_streaming)
+            kind = FlatKernel::streamed;
         p.map = shape.map;
         p.stripe_log2 = shape.stripe_log2;
         p.xcd_chunk_log2 = shape.xcd_chunk_log2;
     }
     if (p.xcd_chunk_log2 < 0)
         p.xcd_chunk_log2 = 0;  // a forced map: unused
+    p.log2_chunks = kind == FlatKernel::streamed ? exact_log2(p.members / streamed_chunk(lag)) : 0;
     // tiles is rounded up to whole stripes and whole XCD rounds (the surplus lanes find col >= nvec)
     p.tiles = (p.nvec + kBlock - 1) / kBlock;
     int round_log2 = p.stripe_log2;

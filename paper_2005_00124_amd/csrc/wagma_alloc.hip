@@ -478,8 +478,9 @@ int* shape_setting(wagma_ctx* ctx, bool global, int* count)
 }
 
 // What a placement is judged by: milliseconds per iteration over a period of tau iterations,
-// every kernel with the better of its first and of its caller-array launch shape (which of the
-// two wins depends on the placement, so a placement is not judged with one of them alone).
+// the kernel that holds a group in registers with the better of its first and of its caller-array
+// launch shape, the one for larger groups with the best of its three (which wins depends on the
+// placement, so a placement is not judged with one of them alone).
 // 0 on failure.
 double time_placement(wagma_ctx* ctx, const ArraySet& set)
 {
@@ -490,7 +491,10 @@ double time_placement(wagma_ctx* ctx, const ArraySet& set)
         if (!setting)
             return time_steps(ctx, set, global);
         double best = 0.0;
-        for (int shape : {0, count == wagma_detail::kNumLaunchShapes ? wagma_detail::kForeignShape : 1}) {
+        const bool in_registers = setting == &ctx->placed_shape;
+        for (int shape : {0, in_registers ? wagma_detail::kForeignShape : 1, in_registers ? -1 : 2}) {
+            if (shape < 0)
+                break;
             *setting = shape;
             const double t = time_steps(ctx, set, global);
             if (t > 0.0 && (best == 0.0 || t < best))

@@ -63,6 +63,7 @@ namespace wagma_detail {
 struct LaunchShape {
     uint64_t map;
     int stripe_log2, xcd_chunk_log2;
+    bool row_streaming = false;  // kCoopShapes only: run the row-streaming kernel instead
 };
 // The shapes wagma_alloc_buffers times on its arrays.  Bits of the slice number from bit 4 up
 // (l = bits 4, 5 of the lane, w = wavefront, x = XCD, t = later tile bits):
@@ -79,11 +80,13 @@ constexpr LaunchShape kLaunchShapes[kNumLaunchShapes] = {
     {0u, 2, 2}, {0u, 2, 0}, {0x7328965410ull, 0, 0}, {0x4916328507ull, 0, 0}, {0x5936218407ull, 0, 0},
     {0x5329618470ull, 0, 0}};
 constexpr int kForeignShape = 3;  // for arrays the library did not place
-// The kernel for groups of 16 to 64 rows:
+// Groups of 16 to 64 rows (and the global iteration of 16 to 64 processes):
 //   0  l4 l5 t3 t4 w0 w1 t5 x0 x1 x2   1 KiB per wavefront, 4 KiB stripe, runs of 8 tiles per XCD
 //   1  l4 x0 x1 t4 w0 t5 t3 l5 w1 x2   a wavefront takes 512 B and the 512 B that lie 32 KiB further on
-constexpr int kNumCoopShapes = 2;
-constexpr LaunchShape kCoopShapes[kNumCoopShapes] = {{0u, 2, 3}, {0x5369218470ull, 0, 0}};
+//   2  the row-streaming kernel with shape 3 of the list above
+constexpr int kNumCoopShapes = 3;
+constexpr LaunchShape kCoopShapes[kNumCoopShapes] = {
+    {0u, 2, 3}, {0x5369218470ull, 0, 0}, {0x4916328507ull, 0, 0, true}};
 
 
 // Records a failed HIP call for wagma_last_hip_error (per thread) and returns WAGMA_EHIP.

@@ -527,7 +527,7 @@ def test_every_placement_mode_gives_the_same_bits(mode):
             mask = ctx.stale_mask(wl.seed, t, wl.stale_threshold)
             if t >= 4:
                 ctx.debug_set_option(lw.WAGMA_DEBUG_PLACED_SHAPE, others[t % 5])
-                ctx.debug_set_option(lw.WAGMA_DEBUG_PLACED_COOP_SHAPE, t % 2)
+                ctx.debug_set_option(lw.WAGMA_DEBUG_PLACED_COOP_SHAPE, t % 3)
             ctx.step(w, g, m, pub, mask, wl.lr, wl.mu, t)
             orc.step_f32(P, S, wl.tau, t, ow, og, om, opub, mask, wl.lr, wl.mu)
             torch.cuda.synchronize()
