@@ -314,6 +314,8 @@ int step_flat(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub, co
             shape = kCoopShapes[own ? ctx->placed_coop_shape : (p.members == 16 ? 1 : 2)];
         if (shape.row_streaming)
             kind = FlatKernel::streamed;
+        if (shape.map != 0 && p.nvec <= 64 * kBlock)
+            shape = LaunchShape{0u, 2, 0};  // rows shorter than one block of a map (256 KiB): no padding to it
         p.map = shape.map;
         p.stripe_log2 = shape.stripe_log2;
         p.xcd_chunk_log2 = shape.xcd_chunk_log2;
