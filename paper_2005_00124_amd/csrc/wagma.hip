@@ -303,11 +303,12 @@ int step_flat(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub, co
         // at 5100 GB/s on arrays in one region and at 6380 on arrays in three with its first
         // shape, at 5600 on both with the split one, and the row-streaming kernel with shape 3 at
         // 6180 on both: a caller's arrays get the split shape for groups of 16 and the
-        // row-streaming kernel for larger ones.  For groups above 64 rows the row-streaming kernel
-        // keeps the 4 KiB stripe with runs of 4 tiles per XCD.
+        // row-streaming kernel for larger ones.  Groups above 64 rows always run the row-streaming
+        // kernel, with shape 3 too (against the 4 KiB stripe with runs of 4 tiles per XCD: 6180
+        // against 4970 … 5080 GB/s on arrays in one region, 6180 against 6220 on arrays in three).
         const bool own = force != Force::none || (ctx->placed[0] && w == ctx->placed[0] && g == ctx->placed[1] &&
                                                   m == ctx->placed[2] && pub == ctx->placed[3]);
-        LaunchShape shape = {0u, ctx->opt_stripe_log2, 2};
+        LaunchShape shape = kLaunchShapes[kForeignShape];
         if (kind == FlatKernel::in_registers)
             shape = kLaunchShapes[own ? ctx->placed_shape : kForeignShape];
         else if (kind == FlatKernel::cooperative)
