@@ -324,15 +324,11 @@ int step_flat(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub, co
     if (p.xcd_chunk_log2 < 0)
         p.xcd_chunk_log2 = 0;  // a forced map: unused
     p.log2_chunks = kind == FlatKernel::streamed ? exact_log2(p.members / streamed_chunk(lag)) : 0;
-    // tiles is rounded up to whole stripes and whole XCD rounds (the surplus lanes find col >= nvec)
+    // tiles is rounded up to whole rounds of the launch shape (the surplus lanes find col >= nvec)
     p.tiles = (p.nvec + kBlock - 1) / kBlock;
-    int round_log2 = p.stripe_log2;
-    if (p.xcd_chunk_log2 > 0 && p.xcd_chunk_log2 + 3 > round_log2)
-        round_log2 = p.xcd_chunk_log2 + 3;
+    int round_log2 = wagma_detail::round_log2_of(p.map, p.stripe_log2, p.xcd_chunk_log2);
     if (kind == FlatKernel::cooperative && round_log2 < 3)
         round_log2 = 3;  // its workgroups take the tiles in rounds of 8
-    if (p.map != 0)
-        round_log2 = 6;  // a map permutes the slices of 64 tiles among themselves
     p.tiles = ((p.tiles + (int64_t(1) << round_log2) - 1) >> round_log2) << round_log2;
     p.blocks = (int64_t)(ctx->P / p.members) * p.tiles;
     if (kind == FlatKernel::cooperative)
@@ -892,21 +888,11 @@ int wagma_debug_set_option(wagma_ctx* ctx, int option, int64_t value)
             return WAGMA_EINVAL;
         ctx->placed_coop_shape = (int)value;
         return WAGMA_OK;
-    case WAGMA_DEBUG_MAP: {
-        if (value < 0 || value > 0xffffffffffll)
-            return WAGMA_EINVAL;
-        unsigned seen = 0;
-        for (int k = 0; k < 10 && value != 0; ++k) {
-            const unsigned field = (unsigned)(value >> (4 * k)) & 15u;
-            if (field > 9u)
-                return WAGMA_EINVAL;
-            seen |= 1u << field;
-        }
-        if (value != 0 && seen != 0x3ffu)
+    case WAGMA_DEBUG_MAP:
+        if (value < 0 || !wagma_detail::valid_map((uint64_t)value))
             return WAGMA_EINVAL;
         ctx->opt_map = (uint64_t)value;
         return WAGMA_OK;
-    }
     default:
         return wagma_set_option(ctx, option, value);
     }

@@ -9,6 +9,7 @@
 #include <cstdint>
 
 #include "wagma.h"
+#include "wagma_shapes.h"
 
 struct VmmArrays;  // arrays built from 1 GiB physical chunks (wagma_alloc.hip)
 
@@ -57,37 +58,6 @@ extern "C" int wagma_debug_set_option(wagma_ctx* ctx, int option, int64_t value)
 extern "C" int wagma_debug_get_option(const wagma_ctx* ctx, int option, int64_t* value);
 
 namespace wagma_detail {
-
-// How the column tiles of a row are dealt out to workgroups (hence XCDs) and wavefronts: either
-// a map (slice_of in wagma_kernels.h) or, with map == 0, stripe and XCD run length.
-struct LaunchShape {
-    uint64_t map;
-    int stripe_log2, xcd_chunk_log2;
-    bool row_streaming = false;  // kCoopShapes only: run the row-streaming kernel instead
-};
-// The shapes wagma_alloc_buffers times on its arrays.  Bits of the slice number from bit 4 up
-// (l = bits 4, 5 of the lane, w = wavefront, x = XCD, t = later tile bits):
-//   0  l4 l5 t3 t4 w0 w1 x0 x1 x2 t5   a wavefront takes 1 KiB, the wavefronts of a workgroup 4 KiB
-//                                      apart, runs of 4 tiles per XCD
-//   1  l4 l5 x0 x1 w0 w1 x2 t3 t4 t5   as 0, tile by tile round the XCDs
-//   2  l4 l5 t3 t4 w0 w1 x0 t5 x2 x1   as 0 with the upper XCD bits further up
-//   3  l5 t3 x0 x1 t5 w0 x2 l4 w1 t4   a wavefront takes 512 B and the 512 B that lie 32 KiB further on,
-//                                      the wavefronts of a workgroup 8 KiB and 64 KiB apart
-//   4  l5 x0 x1 t3 w0 t5 x2 l4 w1 t4   as 3, other places for the XCD bits
-//   5  l4 x0 t3 t4 w0 t5 x1 l5 w1 x2   as 3, the other lane bit chooses the piece; other places for the rest
-constexpr int kNumLaunchShapes = 6;
-constexpr LaunchShape kLaunchShapes[kNumLaunchShapes] = {
-    {0u, 2, 2}, {0u, 2, 0}, {0x7328965410ull, 0, 0}, {0x4916328507ull, 0, 0}, {0x5936218407ull, 0, 0},
-    {0x5329618470ull, 0, 0}};
-constexpr int kForeignShape = 3;  // for arrays the library did not place
-// Groups of 16 to 64 rows (and the global iteration of 16 to 64 processes):
-//   0  l4 l5 t3 t4 w0 w1 t5 x0 x1 x2   1 KiB per wavefront, 4 KiB stripe, runs of 8 tiles per XCD
-//   1  l4 x0 x1 t4 w0 t5 t3 l5 w1 x2   a wavefront takes 512 B and the 512 B that lie 32 KiB further on
-//   2  the row-streaming kernel with shape 3 of the list above
-constexpr int kNumCoopShapes = 3;
-constexpr LaunchShape kCoopShapes[kNumCoopShapes] = {
-    {0u, 2, 3}, {0x5369218470ull, 0, 0}, {0x4916328507ull, 0, 0, true}};
-
 
 // Records a failed HIP call for wagma_last_hip_error (per thread) and returns WAGMA_EHIP.
 int hip_failed(hipError_t e);

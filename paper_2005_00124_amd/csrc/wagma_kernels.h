@@ -8,6 +8,7 @@
 #include <cstdint>
 
 #include "wagma.h"
+#include "wagma_shapes.h"
 
 namespace {
 
@@ -373,38 +374,13 @@ __device__ __forceinline__ void streamed_body(const StepParams& p, const int32_t
 constexpr int kBlock = 256;  // threads per workgroup of every step kernel
 
 // Which 16-byte column slice of a row lane `lane` of wavefront `wave` of the workgroup for column
-// tile `tile` takes.  Workgroup b runs on XCD b mod 8, so bits [0,3) of `tile` are the XCD.
-//   map == 0: a wavefront takes 64 consecutive slices (1 KiB); each XCD takes runs of
-//     2^xcd_chunk_log2 consecutive tiles (the XCD number moves from tile bits [0,3) up to bits
-//     [j, j+3)), and the four wavefronts of a workgroup work 2^stripe_log2 KiB apart inside
-//     4 << stripe_log2 KiB.
-//   map != 0: ten 4-bit fields, a permutation of 0..9.  With y = (tile << 2 | wave) << 2 | lane >> 4,
-//     bit k of y becomes bit 4 + field[k] of the slice number and the higher bits of y stay; 16
-//     lanes always take 16 consecutive slices (256 B).  A field of the two lane bits that is not
-//     0 or 1 splits a wavefront's 1 KiB into pieces that lie apart.
-__device__ __forceinline__ int64_t mapped_slice(uint64_t map, int64_t tile, int64_t wave, int64_t lane)
-{
-    const int64_t y = (((tile << 2) | wave) << 2) | (lane >> 4);
-    int64_t upper = y & ~int64_t(0x3ff);
-#pragma unroll
-    for (int k = 0; k < 10; ++k)
-        upper |= ((y >> k) & 1) << ((map >> (4 * k)) & 15u);
-    return (upper << 4) | (lane & 15);
-}
-
+// tile `tile` takes: by the launch shape's map, or by its stripe and XCD run length
+// (wagma_shapes.h).
 __device__ __forceinline__ int64_t slice_of(const StepParams& p, int64_t tile, int64_t wave, int64_t lane)
 {
     if (p.map != 0)
-        return mapped_slice(p.map, tile, wave, lane);
-    if (p.xcd_chunk_log2 > 0) {
-        const int j = p.xcd_chunk_log2;
-        const int64_t xcd = tile & (kNumXcd - 1);
-        const int64_t hi = tile >> 3;
-        tile = ((hi >> j) << (j + 3)) | (xcd << j) | (hi & ((int64_t(1) << j) - 1));
-    }
-    const int64_t super = tile >> p.stripe_log2;
-    const int64_t within = tile & ((int64_t(1) << p.stripe_log2) - 1);
-    return ((((super * 4 + wave) << p.stripe_log2) + within) << 6) | lane;
+        return wagma_detail::mapped_slice(p.map, tile, wave, lane);
+    return wagma_detail::striped_slice(p.stripe_log2, p.xcd_chunk_log2, tile, wave, lane);
 }
 
 __device__ __forceinline__ bool decode_block(const StepParams& p, int64_t& group, int64_t& col)
@@ -484,7 +460,7 @@ __device__ __forceinline__ int64_t tensor_slice(const StepParams& p, const TileR
 {
     if (ref.tile_in_block == 0)
         return (int64_t)ref.first_slice + wave * 64 + lane;
-    return (int64_t)ref.first_slice + mapped_slice(p.map, ref.tile_in_block - 1, wave, lane);
+    return (int64_t)ref.first_slice + wagma_detail::mapped_slice(p.map, ref.tile_in_block - 1, wave, lane);
 }
 
 // Per-tensor layout.  Workgroup b owns tile b % tiles of group b / tiles; the tile table
