@@ -32,9 +32,9 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 # only.  workload -> (bytes per launch, the file under profiles/ that holds the figure).
 MEASURED_TRAFFIC = {
     2: (10.116e9, "group_step_S4__resnet50-25.6M_P16_S4.md"),
-    3: (24.015e9, "group_step_S4__transformer-base-61.4M_P16_S4.md"),
+    3: (24.017e9, "group_step_S4__transformer-base-61.4M_P16_S4.md"),
     4: (40.94e9, "group_step_S8__resnet50-25.6M_P64_S8.md"),
-    5: (166.39e9, "group_step_S8__transformer-big-210.8M_P32_S8.md"),
+    5: (166.38e9, "group_step_S8__transformer-big-210.8M_P32_S8.md"),
 }
 MEASURED_TRAFFIC_PER_TENSOR = {4: (40.964e9, "group_step_S8_per_tensor__resnet50-25.6M_P64_S8.md")}
 # option number -> value the profiles were taken with (the library's defaults at that time)
