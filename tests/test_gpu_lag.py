@@ -139,10 +139,11 @@ def test_training_run_with_back_to_back_steps(P, S, n, tau, iters):
         say("  busy process-iterations %d, late %d of %d" % (seen_busy, seen_late, P * iters))
 
 
-@pytest.mark.parametrize("P,S", [(4, 2), (16, 8), (32, 16)])
+@pytest.mark.parametrize("P,S", [(4, 2), (16, 8), (32, 16), (32, 32)])
 def test_step_tensors_lag(P, S):
-    """Per-tensor layout: ragged tensors between sentinels, late and busy processes."""
-    sizes = [1, 7, 64, 1030, 5, 4096, 333]
+    """Per-tensor layout: ragged tensors between sentinels (one with a whole 256 KiB block, which the
+    plan deals out by the launch shape's map), late and busy processes."""
+    sizes = [1, 7, 64, 1030, 5, 4096, 333, 65536 + 4 * 70 + 3]
     n = sum(sizes)
     tau = 4
     say("lag tensors P=%d S=%d" % (P, S))
