@@ -574,60 +574,46 @@ int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64
         if ((((uintptr_t)w[i]) | ((uintptr_t)g[i]) | ((uintptr_t)m[i]) | ((uintptr_t)pub[i])) & 15u)
             return WAGMA_EINVAL;
     }
-    // Every whole 256 KiB of a tensor (64 tiles of whole slices) becomes a mapped block: its slices
-    // are dealt out to the lanes of 64 workgroups by the launch shape for a caller's arrays (a
-    // plan's tensors are always the caller's), as in the flat layout; what is left of a tensor is
-    // cut into contiguous 4 KiB tiles.  That shape pairs pieces whose addresses differ in bit 15
-    // only, so the blocks begin on a 64 KiB boundary of the address space where the tensor crosses
-    // one at the same place in every process and array (`lead` slices into the tensor), else at
-    // the tensor's first element.  Forcing a stripe or an XCD run length switches the blocks off,
-    // forcing a map chooses theirs.
-    constexpr int64_t kBlockSlices = 64 * kTensorBlock;
+    // Every whole 256 KiB of a tensor becomes a mapped block whose slices are dealt out by the launch
+    // shape for a caller's arrays (a plan's tensors are always the caller's), as in the flat layout;
+    // the rest is contiguous 4 KiB tiles in runs of 8 per XCD (measured best: tile by tile is 2-5 %
+    // slower on every kind of array); wagma_tiles.h builds the table.  Forcing a stripe or an XCD
+    // run length switches the blocks off, forcing a map chooses theirs.
     const uint64_t block_map = ctx->opt_map != 0 ? ctx->opt_map
                                : (ctx->opt_xcd_chunk_log2 >= 0 || ctx->stripe_forced)
                                    ? 0
                                    : wagma_detail::kLaunchShapes[wagma_detail::kForeignShape].map;
-    auto blocks_of = [&](int k, int64_t& lead, int64_t& blocks) {
-        lead = 0;
-        blocks = 0;
-        if (block_map == 0)
-            return;
-        const uintptr_t phase = (uintptr_t)w[k] & 65535u;
-        bool same = true;
-        for (int r = 0; r < ctx->P && same; ++r) {
-            const size_t i = (size_t)r * T + k;
-            same = ((uintptr_t)w[i] & 65535u) == phase && ((uintptr_t)g[i] & 65535u) == phase &&
-                   ((uintptr_t)m[i] & 65535u) == phase && ((uintptr_t)pub[i] & 65535u) == phase;
-        }
-        const int64_t whole = sizes[k] / 4;
-        if (same)
-            lead = (int64_t)((65536u - phase) & 65535u) / 16;
-        if (whole - lead < kBlockSlices)
-            lead = 0;
-        blocks = (whole - lead) / kBlockSlices;
-    };
-    int64_t total = 0, mapped_tiles = 0, plain_tiles = 0;
+    const int xcd_chunk_log2 = ctx->opt_xcd_chunk_log2 < 0 ? 2 : ctx->opt_xcd_chunk_log2;
+    const int run_log2 = xcd_chunk_log2 > 0 ? (xcd_chunk_log2 < 7 ? xcd_chunk_log2 + 1 : 8) : 0;
+    int64_t total = 0;
     for (int k = 0; k < T; ++k) {
         if (sizes[k] < 1 || sizes[k] > kMaxN)
             return WAGMA_EINVAL;
         total += sizes[k];
-        int64_t lead, blocks;
-        blocks_of(k, lead, blocks);
-        mapped_tiles += 64 * blocks;
-        plain_tiles += (lead + kTensorBlock - 1) / kTensorBlock +
-                       ((sizes[k] + 3) / 4 - lead - blocks * kBlockSlices + kTensorBlock - 1) / kTensorBlock;
     }
-    // Workgroup b of a launch runs on XCD b mod 8.  The mapped blocks come first in the table (64
-    // slots each, so that the low three bits of a tile's number in its block are its XCD); of the
-    // contiguous tiles each XCD gets runs of consecutive ones (measured best: runs of 8; tile by
-    // tile is 2-5 % slower on every kind of array): that part of the table is padded with empty
-    // tiles to whole rounds of 8 runs and permuted below.
-    const int xcd_chunk_log2 = ctx->opt_xcd_chunk_log2 < 0 ? 2 : ctx->opt_xcd_chunk_log2;
-    const int run_log2 = xcd_chunk_log2 > 0 ? (xcd_chunk_log2 < 7 ? xcd_chunk_log2 + 1 : 8) : 0;
-    const int64_t round_tiles = int64_t(kNumXcd) << run_log2;
-    plain_tiles = (plain_tiles + round_tiles - 1) / round_tiles * round_tiles;
-    int64_t tiles = mapped_tiles + plain_tiles;
-    if (total != ctx->n || tiles * (int64_t)ctx->P > 0x7fffffff)
+    if (total != ctx->n)
+        return WAGMA_EINVAL;
+    std::vector<TileRef> table;
+    int64_t tiles = 0;
+    try {
+        // a tensor's address modulo 64 KiB, if it is the same in every process and array
+        std::vector<int> phase((size_t)T);
+        for (int k = 0; k < T; ++k) {
+            const uintptr_t first = (uintptr_t)w[k] & 65535u;
+            bool same = true;
+            for (int r = 0; r < ctx->P && same; ++r) {
+                const size_t i = (size_t)r * T + k;
+                same = ((uintptr_t)w[i] & 65535u) == first && ((uintptr_t)g[i] & 65535u) == first &&
+                       ((uintptr_t)m[i] & 65535u) == first && ((uintptr_t)pub[i] & 65535u) == first;
+            }
+            phase[(size_t)k] = same ? (int)first : -1;
+        }
+        wagma_detail::build_tile_table(T, sizes, phase.data(), block_map, run_log2, table);
+        tiles = (int64_t)table.size();
+    } catch (const std::bad_alloc&) {
+        return WAGMA_ENOMEM;
+    }
+    if (tiles * (int64_t)ctx->P > 0x7fffffff)
         return WAGMA_EINVAL;
     int device = -1;
     hipError_t e = hipGetDevice(&device);
@@ -659,43 +645,7 @@ int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64
                     to[(size_t)k * ctx->P + r] = from[a][(size_t)r * T + k];
         }
     }
-    TileRef* refs = (TileRef*)(host + 4 * table_bytes);
-    {
-        std::vector<TileRef> in_order;  // the contiguous tiles, tensor by tensor
-        try {
-            in_order.reserve((size_t)plain_tiles);
-        } catch (const std::bad_alloc&) {
-            std::free(host);
-            delete plan;
-            return WAGMA_ENOMEM;
-        }
-        int64_t at = 0;
-        for (int k = 0; k < T; ++k) {
-            const int64_t slices = (sizes[k] + 3) / 4;
-            int64_t lead, blocks;
-            blocks_of(k, lead, blocks);
-            // the tiles before the first block end where it begins: to them the tensor is that short
-            for (int64_t first = 0; first < lead; first += kTensorBlock)
-                in_order.push_back(TileRef{k, (uint32_t)(lead * 4), (uint32_t)first, 0u});
-            for (int64_t b = 0; b < blocks; ++b)
-                for (uint32_t j = 0; j < 64; ++j)
-                    refs[at++] = TileRef{k, (uint32_t)sizes[k], (uint32_t)(lead + b * kBlockSlices), j + 1};
-            for (int64_t first = lead + blocks * kBlockSlices; first < slices; first += kTensorBlock)
-                in_order.push_back(TileRef{k, (uint32_t)sizes[k], (uint32_t)first, 0u});
-        }
-        // an empty tile has size 0: every lane of it returns at once
-        while ((int64_t)in_order.size() < plain_tiles)
-            in_order.push_back(TileRef{0, 0u, 0u, 0u});
-        // slot i of this part (the tile of workgroups mapped_tiles + i, + tiles, ...) holds tile
-        // number `linear` of the walk: the XCD number i mod 8 (mapped_tiles is a multiple of 64)
-        // moves from bits [0,3) of the tile number up to bits [run_log2, run_log2 + 3)
-        for (int64_t i = 0; i < plain_tiles; ++i) {
-            const int64_t xcd = i & (kNumXcd - 1), hi = i >> 3;
-            const int64_t linear =
-                ((hi >> run_log2) << (run_log2 + 3)) | (xcd << run_log2) | (hi & ((int64_t(1) << run_log2) - 1));
-            refs[mapped_tiles + i] = in_order[(size_t)linear];
-        }
-    }
+    std::memcpy(host + 4 * table_bytes, table.data(), refs_bytes);
     char* dev = nullptr;
     e = hipMalloc((void**)&dev, blob_bytes);
     if (e == hipSuccess)

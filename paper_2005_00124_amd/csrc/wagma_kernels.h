@@ -9,6 +9,7 @@
 
 #include "wagma.h"
 #include "wagma_shapes.h"
+#include "wagma_tiles.h"
 
 namespace {
 
@@ -26,13 +27,7 @@ constexpr int streamed_stack_depth(bool lag) { return lag ? 8 : 7; }  // log2(WA
 constexpr int kNumXcd = 8;      // accelerator complex dies of an MI355X
 constexpr int64_t kMaxN = int64_t(1) << 31;
 
-struct TileRef {
-    int32_t tensor;         // which tensor a tile of the per-tensor layout belongs to
-    uint32_t size;          // floats in that tensor (0: an empty tile that pads the table)
-    uint32_t first_slice;   // first 16-byte slice of the tile inside that tensor, or of the block below
-    uint32_t tile_in_block; // 0: the tile is 256 consecutive slices.  k + 1: tile k of a block of 64 tiles
-                            // (256 KiB, whole slices only) whose slices are dealt out by the plan's map
-};
+using wagma_detail::TileRef;
 
 struct StepParams {
     float* w;
@@ -454,15 +449,6 @@ __global__ void __launch_bounds__(64 * OCTETS, OCTETS <= 4 ? 2 : 1) step_rows_co
     rows_average<8, NT, LAG, v4f>(p, member, at, w_prime, tree_sum<OCTETS, v4f>(sums));
 }
 
-// The 16-byte slice, inside its tensor, that lane `lane` of wavefront (or quarter) `wave` of a tile of
-// the per-tensor layout takes.
-__device__ __forceinline__ int64_t tensor_slice(const StepParams& p, const TileRef& ref, int64_t wave, int64_t lane)
-{
-    if (ref.tile_in_block == 0)
-        return (int64_t)ref.first_slice + wave * 64 + lane;
-    return (int64_t)ref.first_slice + wagma_detail::mapped_slice(p.map, ref.tile_in_block - 1, wave, lane);
-}
-
 // Per-tensor layout.  Workgroup b owns tile b % tiles of group b / tiles; the tile table
 // names the tensor, its size and the tile's first 16-byte slice inside it.  A lane whose slice is
 // cut off by the end of the tensor does the remaining 1..3 elements one by one; nothing
@@ -473,7 +459,7 @@ __global__ void __launch_bounds__(kBlock, 2) step_tensors_in_registers(const Ste
     const int64_t group = blockIdx.x / p.tiles;
     const TileRef ref = p.tile_ref[blockIdx.x % p.tiles];
     const int64_t size = ref.size;
-    const int64_t first = tensor_slice(p, ref, threadIdx.x >> 6, threadIdx.x & 63) * 4;
+    const int64_t first = wagma_detail::tensor_slice(p.map, ref, threadIdx.x >> 6, threadIdx.x & 63) * 4;
     if (first >= size)
         return;
     const int32_t* member = p.table + group * S;
@@ -494,7 +480,7 @@ __global__ void __launch_bounds__(kBlock, 2) step_tensors_streamed(const StepPar
     const int64_t group = blockIdx.x / p.tiles;
     const TileRef ref = p.tile_ref[blockIdx.x % p.tiles];
     const int64_t size = ref.size;
-    const int64_t first = tensor_slice(p, ref, threadIdx.x >> 6, threadIdx.x & 63) * 4;
+    const int64_t first = wagma_detail::tensor_slice(p.map, ref, threadIdx.x >> 6, threadIdx.x & 63) * 4;
     if (first >= size)
         return;
     const int32_t* member = p.table + group * p.members;
@@ -534,7 +520,7 @@ __global__ void __launch_bounds__(64 * OCTETS, OCTETS <= 4 ? 2 : 1) step_tensors
     if (ref.tile_in_block == 0 && first_slice * 4 >= size)
         return;  // the whole workgroup: this quarter lies beyond the tensor (or the tile is padding)
     const int octet = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int64_t first = tensor_slice(p, ref, quarter, lane) * 4;
+    const int64_t first = wagma_detail::tensor_slice(p.map, ref, quarter, lane) * 4;
     const bool whole = first + 4 <= size;      // the same lanes in every wavefront of the workgroup
     const bool cut = !whole && first < size;   // at most one lane, and only in the tensor's last quarter
     const int32_t* member = p.table + group * p.members + octet * 8;

@@ -1,0 +1,115 @@
+// CPU check of the tile table of libwagma's per-tensor layout (csrc/wagma_tiles.h, no HIP in it):
+// for lists of tensor sizes, address phases, maps and XCD run lengths, the lanes of the table's
+// tiles, taken the way the kernels take them (a lane owns the four floats of its slice, cut off at
+// the size its tile names), must touch every element of every tensor exactly once and nothing else.
+#include <cstdint>
+#include <cstdio>
+#include <vector>
+
+#include "wagma_tiles.h"
+
+using namespace wagma_detail;
+
+static int failures = 0;
+
+static void check(const char* what, const std::vector<int64_t>& sizes, const std::vector<int>& phase, uint64_t map,
+                  int run_log2)
+{
+    const int T = (int)sizes.size();
+    std::vector<TileRef> refs;
+    const int64_t mapped = build_tile_table(T, sizes.data(), phase.empty() ? nullptr : phase.data(), map, run_log2, refs);
+    const int64_t tiles = (int64_t)refs.size();
+    bool ok = mapped % 64 == 0 && (tiles - mapped) % (int64_t(8) << run_log2) == 0 && (map != 0 || mapped == 0);
+    std::vector<std::vector<unsigned char>> seen((size_t)T);
+    for (int k = 0; k < T; ++k)
+        seen[(size_t)k].assign((size_t)sizes[k], 0);
+    int64_t empty = 0;
+    for (int64_t t = 0; t < tiles && ok; ++t) {
+        const TileRef& ref = refs[(size_t)t];
+        if (ref.tensor < 0 || ref.tensor >= T || (int64_t)ref.size > sizes[(size_t)ref.tensor]) {
+            ok = false;
+            break;
+        }
+        if (ref.size == 0)
+            ++empty;
+        if (t < mapped) {
+            // tile j of a block sits in a slot that is j modulo 64, and a block begins on a 64 KiB
+            // boundary of the address space when the tensor's phase is known ...
+            ok = ok && ref.tile_in_block == (uint32_t)(t % 64) + 1 && (int64_t)ref.size == sizes[(size_t)ref.tensor] &&
+                 ((int64_t)ref.first_slice + kBlockSlices) * 4 <= (int64_t)ref.size;
+            if (!phase.empty() && phase[(size_t)ref.tensor] >= 0) {
+                // ... unless the tensor has no room for a block behind its first boundary: then its
+                // blocks begin at its first element
+                const int64_t lead = (int64_t)((65536 - phase[(size_t)ref.tensor]) & 65535) / 16;
+                if (sizes[(size_t)ref.tensor] / 4 - lead >= kBlockSlices)
+                    ok = ok && ((int64_t)phase[(size_t)ref.tensor] + (int64_t)ref.first_slice * 16) % 65536 == 0;
+                else
+                    ok = ok && (int64_t)ref.first_slice % kBlockSlices == 0;
+            }
+        } else {
+            ok = ok && ref.tile_in_block == 0;
+        }
+        for (int wave = 0; wave < 4 && ok; ++wave) {
+            for (int lane = 0; lane < 64; ++lane) {
+                const int64_t first = tensor_slice(map, ref, wave, lane) * 4;
+                if (first >= (int64_t)ref.size)
+                    continue;
+                for (int64_t e = first; e < first + 4 && e < (int64_t)ref.size; ++e) {
+                    if (seen[(size_t)ref.tensor][(size_t)e]++) {
+                        ok = false;
+                        break;
+                    }
+                }
+            }
+        }
+    }
+    for (int k = 0; k < T && ok; ++k)
+        for (int64_t e = 0; e < sizes[(size_t)k]; ++e)
+            if (seen[(size_t)k][(size_t)e] != 1) {
+                ok = false;
+                break;
+            }
+    // padding never exceeds one round of the XCD walk
+    ok = ok && empty < (int64_t(8) << run_log2);
+    if (!ok) {
+        std::printf("FAILED: %s (map %010llx run_log2 %d, %d tensors, first size %lld)\n", what, (unsigned long long)map,
+                    run_log2, T, (long long)sizes[0]);
+        ++failures;
+    }
+}
+
+int main()
+{
+    const uint64_t maps[] = {0, kLaunchShapes[kForeignShape].map, 0x9876543210ull, 0x0123456789ull, 0x5329618470ull};
+    const std::vector<std::vector<int64_t>> lists = {
+        {1},
+        {3, 1, 2},
+        {1023, 1024, 1025, 4096, 5},
+        {65536},                     // exactly one block
+        {65535, 65537, 65536 + 283}, // just below, just above
+        {262144 + 7, 64, 3 * 65536, 2 * 65536 - 1},
+        {9408, 64, 64, 4096, 36864, 16384, 147456, 589824, 2359296, 2048000, 1000},  // a convolutional net's mix
+    };
+    uint64_t seed = 12345;
+    for (const auto& sizes : lists) {
+        for (uint64_t map : maps) {
+            for (int run_log2 : {0, 1, 3, 5, 8}) {
+                check("no phases", sizes, {}, map, run_log2);
+                std::vector<int> phase(sizes.size());
+                // slice-aligned phases, some unknown (-1), some zero
+                for (size_t k = 0; k < sizes.size(); ++k) {
+                    seed = seed * 6364136223846793005ull + 1442695040888963407ull;
+                    const int pick = (int)(seed >> 60);
+                    phase[k] = pick == 0 ? -1 : pick == 1 ? 0 : (int)((seed >> 33) % 4096) * 16;
+                }
+                check("random phases", sizes, phase, map, run_log2);
+                std::fill(phase.begin(), phase.end(), 65536 - 16);
+                check("one slice before a boundary", sizes, phase, map, run_log2);
+                std::fill(phase.begin(), phase.end(), 16);
+                check("one slice after a boundary", sizes, phase, map, run_log2);
+            }
+        }
+    }
+    std::printf("%s\n", failures ? "failures" : "ok");
+    return failures ? 1 : 0;
+}
