@@ -120,6 +120,7 @@ void set_defaults(wagma_ctx* ctx, int P, int S, int G, int g, int64_t n, int tau
     ctx->stripe_forced = 0;
     ctx->opt_xcd_chunk_log2 = -1;
     ctx->opt_map = 0;
+    ctx->opt_tensor_tables = 0;
     ctx->placed_shape = 0;
     ctx->placed_coop_shape = 0;
     ctx->fixed_groups = 0;
@@ -177,27 +178,38 @@ struct wagma_tensors {
     float* const* tm;
     float* const* tpub;
     const TileRef* tile_ref;
+    const AffineTile* affine_tile;  // not NULL: the tensors are spaced alike in every array, and the tile
+                                    // table exists in this form too (the kernels then read nothing else)
     uint64_t map;       // how the slices of the mapped blocks of the tile table are dealt out (0: no such blocks)
 };
 
 namespace {
 constexpr int kTensorBlock = kBlock;  // threads per workgroup of the per-tensor kernels
 
-template <bool NT, bool LAG>
+template <bool NT, bool LAG, bool AFFINE>
 void launch_tensors(const StepParams& p, bool cooperative, unsigned grid, hipStream_t stream)
 {
     const dim3 g(grid), b(kTensorBlock);
     if (cooperative) {  // groups of 16: two wavefronts per group
-        hipLaunchKernelGGL((step_tensors_cooperative<2, NT, LAG>), g, dim3(128), 0, stream, p);
+        hipLaunchKernelGGL((step_tensors_cooperative<2, NT, LAG, AFFINE>), g, dim3(128), 0, stream, p);
         return;
     }
     switch (p.members) {
-    case 1: hipLaunchKernelGGL((step_tensors_in_registers<1, NT, LAG>), g, b, 0, stream, p); break;
-    case 2: hipLaunchKernelGGL((step_tensors_in_registers<2, NT, LAG>), g, b, 0, stream, p); break;
-    case 4: hipLaunchKernelGGL((step_tensors_in_registers<4, NT, LAG>), g, b, 0, stream, p); break;
-    case 8: hipLaunchKernelGGL((step_tensors_in_registers<8, NT, LAG>), g, b, 0, stream, p); break;
-    default: hipLaunchKernelGGL((step_tensors_streamed<NT, LAG>), g, b, 0, stream, p); break;
+    case 1: hipLaunchKernelGGL((step_tensors_in_registers<1, NT, LAG, AFFINE>), g, b, 0, stream, p); break;
+    case 2: hipLaunchKernelGGL((step_tensors_in_registers<2, NT, LAG, AFFINE>), g, b, 0, stream, p); break;
+    case 4: hipLaunchKernelGGL((step_tensors_in_registers<4, NT, LAG, AFFINE>), g, b, 0, stream, p); break;
+    case 8: hipLaunchKernelGGL((step_tensors_in_registers<8, NT, LAG, AFFINE>), g, b, 0, stream, p); break;
+    default: hipLaunchKernelGGL((step_tensors_streamed<NT, LAG, AFFINE>), g, b, 0, stream, p); break;
     }
+}
+
+template <bool NT, bool LAG>
+void launch_tensors(const StepParams& p, bool cooperative, unsigned grid, hipStream_t stream)
+{
+    if (p.affine_tile)
+        launch_tensors<NT, LAG, true>(p, cooperative, grid, stream);
+    else
+        launch_tensors<NT, LAG, false>(p, cooperative, grid, stream);
 }
 }  // namespace
 
@@ -622,10 +634,26 @@ int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64
     if (device != ctx->device)
         return WAGMA_EINVAL;
 
-    // blob layout: [4 pointer tables][tiles tile refs]; every part 16-byte aligned
-    const size_t table_bytes = (slots * sizeof(void*) + 15) / 16 * 16;
-    const size_t refs_bytes = (size_t)tiles * sizeof(TileRef);
-    const size_t blob_bytes = 4 * table_bytes + refs_bytes;
+    // Are the tensors spaced alike in every array: tensor k of process r a fixed number of floats,
+    // the same in all four arrays, behind that of process r - 1?  (A stack of the P replicas of a
+    // parameter, or views into P rows.)  Then every tile's entry also names its tensor's place, and
+    // the kernels look nothing else up.
+    bool affine = !ctx->opt_tensor_tables;
+    for (int k = 0; k < T && affine && ctx->P > 1; ++k) {
+        const void* const* arrays[4] = {(const void* const*)w, (const void* const*)g, (const void* const*)m,
+                                        (const void* const*)pub};
+        const intptr_t step = (intptr_t)w[(size_t)T + k] - (intptr_t)w[k];
+        for (int a = 0; a < 4 && affine; ++a)
+            for (int r = 1; r < ctx->P && affine; ++r)
+                affine = (intptr_t)arrays[a][(size_t)r * T + k] - (intptr_t)arrays[a][(size_t)(r - 1) * T + k] == step;
+    }
+
+    // blob layout: [4 pointer tables][tiles tile refs][tiles 64-byte entries, if the tensors are
+    // spaced alike]; every part 64-byte aligned
+    const size_t table_bytes = (slots * sizeof(void*) + 63) / 64 * 64;
+    const size_t refs_bytes = ((size_t)tiles * sizeof(TileRef) + 63) / 64 * 64;
+    const size_t affine_bytes = affine ? (size_t)tiles * sizeof(AffineTile) : 0;
+    const size_t blob_bytes = 4 * table_bytes + refs_bytes + affine_bytes;
     char* host = (char*)std::malloc(blob_bytes);
     wagma_tensors* plan = new (std::nothrow) wagma_tensors();
     if (!host || !plan) {
@@ -645,7 +673,16 @@ int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64
                     to[(size_t)k * ctx->P + r] = from[a][(size_t)r * T + k];
         }
     }
-    std::memcpy(host + 4 * table_bytes, table.data(), refs_bytes);
+    std::memcpy(host + 4 * table_bytes, table.data(), (size_t)tiles * sizeof(TileRef));
+    if (affine) {
+        AffineTile* entries = (AffineTile*)(host + 4 * table_bytes + refs_bytes);
+        for (int64_t i = 0; i < tiles; ++i) {
+            const TileRef& ref = table[(size_t)i];
+            const int k = ref.tensor;  // an empty tile names tensor 0 and touches nothing
+            const intptr_t step = ctx->P > 1 ? (intptr_t)w[(size_t)T + k] - (intptr_t)w[k] : 0;
+            entries[i] = AffineTile{ref, (int64_t)(step / (intptr_t)sizeof(float)), w[k], g[k], m[k], pub[k], 0};
+        }
+    }
     char* dev = nullptr;
     e = hipMalloc((void**)&dev, blob_bytes);
     if (e == hipSuccess)
@@ -667,6 +704,7 @@ int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64
     plan->tm = (float* const*)(dev + 2 * table_bytes);
     plan->tpub = (float* const*)(dev + 3 * table_bytes);
     plan->tile_ref = (const TileRef*)(dev + 4 * table_bytes);
+    plan->affine_tile = affine ? (const AffineTile*)(dev + 4 * table_bytes + refs_bytes) : nullptr;
     plan->map = block_map;
     *out = plan;
     return WAGMA_OK;
@@ -712,14 +750,16 @@ int wagma_step_tensors_lag(wagma_ctx* ctx, const wagma_tensors* plan, const uint
     p.tm = plan->tm;
     p.tpub = plan->tpub;
     p.tile_ref = plan->tile_ref;
+    p.affine_tile = plan->affine_tile;
     p.map = plan->map;
     p.num_ranks = ctx->P;
     p.tiles = plan->tiles;  // a multiple of 8 (whole XCD rounds)
     p.blocks = (int64_t)(ctx->P / p.members) * p.tiles;
     // Measured (bench.py --tensors --S k --tau 0): with 2 wavefronts per group the cooperative kernel
-    // beats the row-streaming one (6093 against 5916 GB/s); with 4 and 8 it loses (5157 against 5689,
-    // 4539 against 5617): a workgroup looks up its tile and its base pointers before its first
-    // load, and with one or three large workgroups per compute unit nothing covers that wait.
+    // beats the row-streaming one (6093 against 5916 GB/s through the pointer tables); with 4 and 8
+    // it loses, through the pointer tables (5157 against 5689, 4539 against 5617) and also where
+    // the tile's entry names the tensor's place (5944 against 6058, 5680 against 6100): on arrays
+    // that the library did not place the flat layout, too, takes the row-streaming kernel there.
     const bool cooperative = p.members == 2 * kRegisterRows && !ctx->opt_force_stream;
     if (cooperative)
         p.blocks *= 4;  // one workgroup per quarter tile
@@ -838,6 +878,11 @@ int wagma_debug_set_option(wagma_ctx* ctx, int option, int64_t value)
             return WAGMA_EINVAL;
         ctx->placed_coop_shape = (int)value;
         return WAGMA_OK;
+    case WAGMA_DEBUG_TENSOR_TABLES:
+        if (value != 0 && value != 1)
+            return WAGMA_EINVAL;
+        ctx->opt_tensor_tables = (int)value;
+        return WAGMA_OK;
     case WAGMA_DEBUG_MAP:
         if (value < 0 || !wagma_detail::valid_map((uint64_t)value))
             return WAGMA_EINVAL;
@@ -861,6 +906,7 @@ int wagma_debug_get_option(const wagma_ctx* ctx, int option, int64_t* value)
     case WAGMA_DEBUG_PLACED_SHAPE: *value = ctx->placed_shape; return WAGMA_OK;
     case WAGMA_DEBUG_PLACED_COOP_SHAPE: *value = ctx->placed_coop_shape; return WAGMA_OK;
     case WAGMA_DEBUG_MAP: *value = (int64_t)ctx->opt_map; return WAGMA_OK;
+    case WAGMA_DEBUG_TENSOR_TABLES: *value = ctx->opt_tensor_tables; return WAGMA_OK;
     default: return WAGMA_EINVAL;
     }
 }

@@ -27,6 +27,7 @@ constexpr int streamed_stack_depth(bool lag) { return lag ? 8 : 7; }  // log2(WA
 constexpr int kNumXcd = 8;      // accelerator complex dies of an MI355X
 constexpr int64_t kMaxN = int64_t(1) << 31;
 
+using wagma_detail::AffineTile;
 using wagma_detail::TileRef;
 
 struct StepParams {
@@ -56,6 +57,7 @@ struct StepParams {
     float* const* tm;
     float* const* tpub;
     const TileRef* tile_ref;     // [tiles]
+    const AffineTile* affine_tile;  // [tiles], for the kernels with AFFINE (they read neither the pointer tables nor tile_ref)
     int num_ranks;               // P: the device tables hold tensor k of all ranks side by side
 };
 
@@ -144,6 +146,42 @@ struct TensorAddr {
     __device__ __forceinline__ const float* g(int rank) const { return p.tg[slot(rank)] + lane_at; }
     __device__ __forceinline__ float* m(int rank) const { return p.tm[slot(rank)] + lane_at; }
     __device__ __forceinline__ float* pub(int rank) const { return p.tpub[slot(rank)] + lane_at; }
+};
+
+// Per-tensor layout with tensors spaced alike in every array: the tile's entry holds the tensor of
+// process 0 and the distance to the next process, nothing else is looked up.
+struct AffineAddr {
+    const AffineTile& t;
+    uint32_t lane_at;
+    __device__ __forceinline__ float* w(int rank) const { return t.w + (int64_t)rank * t.stride + lane_at; }
+    __device__ __forceinline__ const float* g(int rank) const { return t.g + (int64_t)rank * t.stride + lane_at; }
+    __device__ __forceinline__ float* m(int rank) const { return t.m + (int64_t)rank * t.stride + lane_at; }
+    __device__ __forceinline__ float* pub(int rank) const { return t.pub + (int64_t)rank * t.stride + lane_at; }
+};
+
+// What a workgroup of the per-tensor kernels looks up about its tile: the tile table's entry and
+// the way to its tensor's elements, through the pointer tables or (AFFINE) from the entry itself.
+template <bool AFFINE>
+struct TileOf;
+template <>
+struct TileOf<false> {
+    TileRef entry;
+    __device__ __forceinline__ TileOf(const StepParams& p, int64_t tile) : entry(p.tile_ref[tile]) {}
+    __device__ __forceinline__ const TileRef& ref() const { return entry; }
+    __device__ __forceinline__ TensorAddr at(const StepParams& p, uint32_t lane_at) const
+    {
+        return TensorAddr{p, entry.tensor, lane_at};
+    }
+};
+template <>
+struct TileOf<true> {
+    AffineTile entry;
+    __device__ __forceinline__ TileOf(const StepParams& p, int64_t tile) : entry(p.affine_tile[tile]) {}
+    __device__ __forceinline__ const TileRef& ref() const { return entry.ref; }
+    __device__ __forceinline__ AffineAddr at(const StepParams&, uint32_t lane_at) const
+    {
+        return AffineAddr{entry, lane_at};
+    }
 };
 
 // The work of registers_body (below) in two stages, for the kernel that deals a large group's rows
@@ -453,17 +491,18 @@ __global__ void __launch_bounds__(64 * OCTETS, OCTETS <= 4 ? 2 : 1) step_rows_co
 // names the tensor, its size and the tile's first 16-byte slice inside it.  A lane whose slice is
 // cut off by the end of the tensor does the remaining 1..3 elements one by one; nothing
 // beyond a tensor's last element is touched.
-template <int S, bool NT, bool LAG>
+template <int S, bool NT, bool LAG, bool AFFINE>
 __global__ void __launch_bounds__(kBlock, 2) step_tensors_in_registers(const StepParams p)
 {
     const int64_t group = blockIdx.x / p.tiles;
-    const TileRef ref = p.tile_ref[blockIdx.x % p.tiles];
+    const TileOf<AFFINE> tile(p, blockIdx.x % p.tiles);
+    const TileRef& ref = tile.ref();
     const int64_t size = ref.size;
     const int64_t first = wagma_detail::tensor_slice(p.map, ref, threadIdx.x >> 6, threadIdx.x & 63) * 4;
     if (first >= size)
         return;
     const int32_t* member = p.table + group * S;
-    TensorAddr at{p, ref.tensor, (uint32_t)first};
+    auto at = tile.at(p, (uint32_t)first);
     if (first + 4 <= size) {
         registers_body<S, NT, LAG, v4f>(p, member, at);
     } else {
@@ -474,17 +513,18 @@ __global__ void __launch_bounds__(kBlock, 2) step_tensors_in_registers(const Ste
     }
 }
 
-template <bool NT, bool LAG>
+template <bool NT, bool LAG, bool AFFINE>
 __global__ void __launch_bounds__(kBlock, 2) step_tensors_streamed(const StepParams p)
 {
     const int64_t group = blockIdx.x / p.tiles;
-    const TileRef ref = p.tile_ref[blockIdx.x % p.tiles];
+    const TileOf<AFFINE> tile(p, blockIdx.x % p.tiles);
+    const TileRef& ref = tile.ref();
     const int64_t size = ref.size;
     const int64_t first = wagma_detail::tensor_slice(p.map, ref, threadIdx.x >> 6, threadIdx.x & 63) * 4;
     if (first >= size)
         return;
     const int32_t* member = p.table + group * p.members;
-    TensorAddr at{p, ref.tensor, (uint32_t)first};
+    auto at = tile.at(p, (uint32_t)first);
     if (first + 4 <= size) {
         streamed_body<NT, LAG, v4f>(p, member, at);
     } else {
@@ -500,7 +540,7 @@ __global__ void __launch_bounds__(kBlock, 2) step_tensors_streamed(const StepPar
 // quarters of one tile.  The slice that a tensor's end cuts off is done element by element in up
 // to three more rounds; the number of rounds is the same for every wavefront of the workgroup
 // (they all work on the same slices), so every wavefront meets every barrier.
-template <int OCTETS, bool NT, bool LAG>
+template <int OCTETS, bool NT, bool LAG, bool AFFINE>
 __global__ void __launch_bounds__(64 * OCTETS, OCTETS <= 4 ? 2 : 1) step_tensors_cooperative(const StepParams p)
 {
     __shared__ v4f octet_sum[OCTETS][64];
@@ -511,7 +551,8 @@ __global__ void __launch_bounds__(64 * OCTETS, OCTETS <= 4 ? 2 : 1) step_tensors
     const int64_t per_group = p.tiles * 4;
     const int64_t group = b / per_group;
     const int64_t piece = b % per_group;
-    const TileRef ref = p.tile_ref[((piece >> 5) << 3) | (piece & 7)];
+    const TileOf<AFFINE> tile(p, ((piece >> 5) << 3) | (piece & 7));
+    const TileRef& ref = tile.ref();
     const int64_t size = ref.size;
     const int64_t quarter = (piece >> 3) & 3;
     // where a contiguous tile's quarter begins; in a mapped block (whole slices only, nothing cut
@@ -525,7 +566,7 @@ __global__ void __launch_bounds__(64 * OCTETS, OCTETS <= 4 ? 2 : 1) step_tensors
     const bool cut = !whole && first < size;   // at most one lane, and only in the tensor's last quarter
     const int32_t* member = p.table + group * p.members + octet * 8;
     {
-        const TensorAddr at{p, ref.tensor, (uint32_t)first};
+        const auto at = tile.at(p, (uint32_t)first);
         v4f w_prime[8];
         v4f mine = {0.f, 0.f, 0.f, 0.f};
         if (whole)
@@ -546,7 +587,7 @@ __global__ void __launch_bounds__(64 * OCTETS, OCTETS <= 4 ? 2 : 1) step_tensors
                            ? (int)(size % 4)
                            : 0;
     for (int k = 0; k < rounds; ++k) {
-        const TensorAddr at{p, ref.tensor, (uint32_t)(first + k)};
+        const auto at = tile.at(p, (uint32_t)(first + k));
         float w_prime[8];
         float mine = 0.f;
         if (cut)

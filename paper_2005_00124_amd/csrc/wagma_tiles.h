@@ -22,6 +22,21 @@ struct TileRef {
                             // (256 KiB, whole slices only) whose slices are dealt out by the plan's map
 };
 
+// A tile together with where its tensor lies, for plans whose tensors are spaced alike in every
+// array: tensor k of process r begins `stride` floats behind that of process r - 1 (a stack of the
+// P replicas of a parameter, or views into P rows).  One 64-byte entry per tile, so that a
+// workgroup knows its addresses after a single look-up.
+struct AffineTile {
+    TileRef ref;
+    int64_t stride;  // floats from the tensor of one process to that of the next, in all four arrays
+    float* w;        // the tensor of process 0
+    const float* g;
+    float* m;
+    float* pub;
+    int64_t unused;
+};
+static_assert(sizeof(AffineTile) == 64, "one entry is one 64-byte line");
+
 // The 16-byte slice, inside its tensor, that lane `lane` of wavefront (or quarter) `wave` of a tile
 // takes.
 WAGMA_SHAPES_FN int64_t tensor_slice(uint64_t map, const TileRef& ref, int64_t wave, int64_t lane)

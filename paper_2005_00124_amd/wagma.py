@@ -24,6 +24,7 @@ WAGMA_OPT_NONTEMPORAL, WAGMA_OPT_PLACEMENT = 2, 9
 # launch-shape switches outside the public header (csrc/wagma_internal.h): tests and measurements only
 WAGMA_DEBUG_FORCE_STREAM, WAGMA_DEBUG_STRIPE_LOG2, WAGMA_DEBUG_XCD_CHUNK_LOG2 = 3, 7, 8
 WAGMA_DEBUG_PLACED_SHAPE, WAGMA_DEBUG_MAP, WAGMA_DEBUG_PLACED_COOP_SHAPE = 10, 11, 12
+WAGMA_DEBUG_TENSOR_TABLES = 13
 WAGMA_PLACE_PLAIN, WAGMA_PLACE_ARRAYS, WAGMA_PLACE_CHUNKS, WAGMA_PLACE_AUTO, WAGMA_PLACE_SEARCH = 0, 1, 2, 3, 4
 
 # name -> (restype, argtypes): every symbol include/wagma.h declares

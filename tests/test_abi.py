@@ -49,7 +49,8 @@ def test_debug_switches_are_exported_but_not_in_the_public_header(lib):
     for name in libwagma.DEBUG_SYMBOLS:
         assert hasattr(lib, name) and name not in text and name in internal
     for name in ("WAGMA_DEBUG_FORCE_STREAM", "WAGMA_DEBUG_STRIPE_LOG2", "WAGMA_DEBUG_XCD_CHUNK_LOG2",
-                 "WAGMA_DEBUG_PLACED_SHAPE", "WAGMA_DEBUG_MAP", "WAGMA_DEBUG_PLACED_COOP_SHAPE"):
+                 "WAGMA_DEBUG_PLACED_SHAPE", "WAGMA_DEBUG_MAP", "WAGMA_DEBUG_PLACED_COOP_SHAPE",
+                 "WAGMA_DEBUG_TENSOR_TABLES"):
         value = re.search(r"#define\s+%s\s+(\d+)" % name, internal).group(1)
         assert int(value) == getattr(libwagma, name) and name not in text
     assert lib.wagma_debug_set_option(None, 3, 1) == libwagma.WAGMA_EINVAL

@@ -139,14 +139,17 @@ def test_training_run_with_back_to_back_steps(P, S, n, tau, iters):
         say("  busy process-iterations %d, late %d of %d" % (seen_busy, seen_late, P * iters))
 
 
+@pytest.mark.parametrize("stacked", [False, True])
 @pytest.mark.parametrize("P,S", [(4, 2), (16, 8), (32, 16), (32, 32)])
-def test_step_tensors_lag(P, S):
+def test_step_tensors_lag(P, S, stacked):
     """Per-tensor layout: ragged tensors between sentinels (one with a whole 256 KiB block, which the
-    plan deals out by the launch shape's map), late and busy processes."""
+    plan deals out by the launch shape's map), late and busy processes.  stacked: the P replicas of
+    a tensor lie equally far apart in one allocation (the plan then needs no pointer tables), else
+    every tensor of every process is an allocation of its own."""
     sizes = [1, 7, 64, 1030, 5, 4096, 333, 65536 + 4 * 70 + 3]
     n = sum(sizes)
     tau = 4
-    say("lag tensors P=%d S=%d" % (P, S))
+    say("lag tensors P=%d S=%d stacked=%s" % (P, S, stacked))
     rng = np.random.default_rng(P + S)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(3 + P)
@@ -154,12 +157,12 @@ def test_step_tensors_lag(P, S):
     SENTINEL = 12345.0
 
     def make(scale):
+        stacks = [torch.full((P, guard + (size + 3) // 4 * 4 + guard), SENTINEL, device="cuda") for size in sizes]
         out = []
-        for _ in range(P):
+        for p in range(P):
             per = []
-            for size in sizes:
-                pad = (size + 3) // 4 * 4
-                buf = torch.full((guard + pad + guard,), SENTINEL, device="cuda")
+            for k, size in enumerate(sizes):
+                buf = stacks[k][p] if stacked else torch.full((stacks[k].shape[1],), SENTINEL, device="cuda")
                 buf[guard:guard + size] = torch.randn(size, generator=gen, device="cuda") * scale
                 per.append(buf)
             out.append(per)

@@ -21,12 +21,15 @@ def bits(a):
     return np.ascontiguousarray(a).view(np.uint32)
 
 
-def make_arrays(P, sizes, gen, scale, arena=False):
-    """For every process a list of tensors, each inside its own guarded allocation; with `arena`,
-    views into one row per process (rows 64 KiB-multiples apart: a tensor then crosses the 64 KiB
-    boundaries of the address space at the same place in every process), sentinels between them."""
+def make_arrays(P, sizes, gen, scale, layout="separate"):
+    """For every process a list of tensors with sentinels around each.  layout "separate": every
+    tensor of every process in an allocation of its own; "arena": views into one row per process
+    (rows 64 KiB-multiples apart: a tensor then crosses the 64 KiB boundaries of the address space
+    at the same place in every process); "stacked": the P replicas of a tensor side by side in one
+    allocation.  In the last two the replicas of a tensor lie equally far apart, in every array
+    alike: the plan then finds its tensors without the pointer tables."""
     arrays, guards = [], []
-    if arena:
+    if layout == "arena":
         row = (sum(sizes) + (len(sizes) + 1) * GUARD + 16383) // 16384 * 16384
         slab = torch.full((P, row), 777.0, device="cuda")
         for p in range(P):
@@ -39,10 +42,12 @@ def make_arrays(P, sizes, gen, scale, arena=False):
                 at += size + GUARD + (-size) % 4
             arrays.append(tensors)
         return arrays, guards
-    for _p in range(P):
+    stacks = [torch.full((P, size + (-size) % 4 + 2 * GUARD), 777.0, device="cuda") for size in sizes] \
+        if layout == "stacked" else None
+    for p in range(P):
         tensors = []
-        for size in sizes:
-            buf = torch.full((size + 2 * GUARD,), 777.0, device="cuda")
+        for k, size in enumerate(sizes):
+            buf = stacks[k][p, :size + 2 * GUARD] if stacks else torch.full((size + 2 * GUARD,), 777.0, device="cuda")
             t = buf[GUARD:GUARD + size]          # 32-byte offset: still 16-byte aligned
             t.normal_(0.0, scale, generator=gen)
             tensors.append(t)
@@ -56,8 +61,8 @@ def to_rows(arrays):
     return np.stack([torch.cat(t).cpu().numpy() for t in arrays])
 
 
-def run_tensor_case(P, S, sizes, tau, iters, q, seed, fixed_groups=False, options=(), arena=False):
-    say("tensor case P=%d S=%d T=%d n=%d tau=%d iters=%d q=%.2f seed=%d" % (P, S, len(sizes), sum(sizes), tau, iters, q, seed))
+def run_tensor_case(P, S, sizes, tau, iters, q, seed, fixed_groups=False, options=(), layout="separate"):
+    say("tensor case P=%d S=%d T=%d n=%d tau=%d iters=%d q=%.2f seed=%d %s" % (P, S, len(sizes), sum(sizes), tau, iters, q, seed, layout))
     n = sum(sizes)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(seed)
@@ -66,7 +71,7 @@ def run_tensor_case(P, S, sizes, tau, iters, q, seed, fixed_groups=False, option
             ctx.set_grouping(lw.WAGMA_GROUPING_FIXED)
         for option, value in options:
             ctx.debug_set_option(option, value)
-        (w, gw), (g, gg), (m, gm), (pub, gp) = (make_arrays(P, sizes, gen, s, arena) for s in (0.05, 0.01, 0.01, 0.05))
+        (w, gw), (g, gg), (m, gm), (pub, gp) = (make_arrays(P, sizes, gen, s, layout) for s in (0.05, 0.01, 0.01, 0.05))
         ow, om, opub = to_rows(w), to_rows(m), to_rows(pub)
         thr = min(int(q * 2 ** 32), 2 ** 32 - 1)
         with ctx.tensor_plan(w, g, m, pub) as plan:
@@ -93,10 +98,11 @@ def run_tensor_case(P, S, sizes, tau, iters, q, seed, fixed_groups=False, option
 RAGGED = [1, 2, 3, 4, 5, 7, 64, 255, 257, 1000, 1023, 1025, 4099, 70001]
 
 
+@pytest.mark.parametrize("layout", ["separate", "stacked"])
 @pytest.mark.parametrize("P,S", [(1, 1), (2, 2), (4, 2), (8, 4), (16, 4), (64, 8), (32, 16), (64, 64), (128, 32)])
-def test_tensors_bit_exact(P, S):
+def test_tensors_bit_exact(P, S, layout):
     sizes = RAGGED if P <= 16 else RAGGED[:-1]
-    run_tensor_case(P, S, sizes, tau=3, iters=5, q=0.3, seed=100 + P + S)
+    run_tensor_case(P, S, sizes, tau=3, iters=5, q=0.3, seed=100 + P + S, layout=layout)
 
 
 def test_tensors_variants():
@@ -109,17 +115,46 @@ def test_tensors_variants():
 BLOCKS = [65536, 3, 65536 + 4 * 300 + 2, 2 * 65536 + 1, 65535, 5]   # whole 256 KiB blocks, with and without a rest
 
 
+@pytest.mark.parametrize("layout", ["separate", "stacked"])
 @pytest.mark.parametrize("P,S", [(16, 4), (32, 8), (16, 16), (32, 32), (8, 1)])
-def test_tensors_with_mapped_blocks(P, S):
+def test_tensors_with_mapped_blocks(P, S, layout):
     """Every whole 256 KiB of a tensor is dealt out by the launch shape's map, the rest in 4 KiB tiles."""
-    run_tensor_case(P, S, BLOCKS, tau=3, iters=4, q=0.3, seed=300 + P + S)
+    run_tensor_case(P, S, BLOCKS, tau=3, iters=4, q=0.3, seed=300 + P + S, layout=layout)
 
 
 @pytest.mark.parametrize("P,S", [(16, 4), (32, 8), (16, 16), (32, 32)])
 def test_tensors_blocks_on_address_boundaries(P, S):
     """Tensors that are views into rows 64 KiB-multiples apart: the mapped blocks begin on a 64 KiB
     boundary of the address space, the slices before it are contiguous tiles."""
-    run_tensor_case(P, S, [70001, 65536 + 8, 3, 2 * 65536 + 20000, 1000], tau=3, iters=4, q=0.3, seed=500 + P + S, arena=True)
+    run_tensor_case(P, S, [70001, 65536 + 8, 3, 2 * 65536 + 20000, 1000], tau=3, iters=4, q=0.3, seed=500 + P + S, layout="arena")
+
+
+def test_tensors_spaced_alike_through_the_pointer_tables():
+    """Views into rows again, with the plan told to look its tensors up in the pointer tables as it
+    does for tensors that are not spaced alike."""
+    for P, S in ((32, 8), (16, 16), (32, 32)):
+        run_tensor_case(P, S, [70001, 65536 + 8, 3, 1000], tau=3, iters=3, q=0.3, seed=600 + P + S, layout="arena",
+                        options=((lw.WAGMA_DEBUG_TENSOR_TABLES, 1),))
+
+
+def test_tensors_spaced_alike_but_not_in_every_array():
+    """The replicas of a tensor equally far apart in w, m and pub and not in g: the pointer tables."""
+    P, S, sizes = 8, 4, [1000, 70001, 3]
+    n = sum(sizes)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(77)
+    with lw.Wagma(P, S, n, 0) as ctx:
+        (w, _), (m, _), (pub, _) = (make_arrays(P, sizes, gen, s, "stacked") for s in (0.05, 0.01, 0.05))
+        g, _ = make_arrays(P, sizes, gen, 0.01, "separate")
+        ow, og, om, opub = (to_rows(x) for x in (w, g, m, pub))
+        with ctx.tensor_plan(w, g, m, pub) as plan:
+            for t in range(3):
+                mask = ctx.stale_mask(5, t, 1 << 30)
+                plan.step(mask, LR, MU, t)
+                orc.step_f32(P, S, 0, t, ow, og, om, opub, mask, LR, MU)
+                torch.cuda.synchronize()
+                for have, want, what in ((w, ow, "w"), (m, om, "m"), (pub, opub, "pub")):
+                    assert np.array_equal(bits(to_rows(have)), bits(want)), "%s differs at t=%d" % (what, t)
 
 
 def test_tensors_block_options():
