@@ -159,6 +159,10 @@ int wagma_step(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub,
  * wagma_tensors_create copies the tables to the device (allocation, copy and synchronisation
  * happen here, none in the step); the plan refers to ctx and to the tensors, which must stay
  * where they are while the plan is used.  Destroy the plan before its context.
+ * Any placement of the tensors gives the same results.  Fastest (2 to 10 % over the general
+ * case, more with larger groups) is one where the P replicas of a tensor lie equally far apart,
+ * by the same distance in w, g, m and pub: a parameter stacked to [P, ...], or views into P rows.
+ * wagma_tensors_create recognises that by itself and the step then reads no pointer tables.
  */
 typedef struct wagma_tensors wagma_tensors;
 int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64_t* sizes,
