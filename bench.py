@@ -36,7 +36,8 @@ MEASURED_TRAFFIC = {
     4: (40.94e9, "group_step_S8__resnet50-25.6M_P64_S8.md"),
     5: (166.38e9, "group_step_S8__transformer-big-210.8M_P32_S8.md"),
 }
-MEASURED_TRAFFIC_PER_TENSOR = {4: (40.935e9, "group_step_S8_per_tensor__resnet50-25.6M_P64_S8.md")}
+# --tensors --tensor-layout stacked (as views into rows the tensors are joined and the step is the flat one)
+MEASURED_TRAFFIC_PER_TENSOR = {4: (40.939e9, "group_step_S8_per_tensor__resnet50-25.6M_P64_S8.md")}
 # option number -> value the profiles were taken with (the library's defaults at that time)
 PROFILE_OPTIONS = {"nontemporal": 1, "force_stream": 0, "stripe_log2": 2, "xcd_chunk_log2": -1, "map": 0}
 
@@ -261,6 +262,10 @@ def main() -> int:
                     help="ordinary torch allocations instead of the library's HBM-region-aware allocator")
     ap.add_argument("--tensors", action="store_true",
                     help="time wagma_step_tensors on the workload's tensor list (views into the same rows)")
+    ap.add_argument("--tensor-layout", choices=("views", "stacked", "separate"), default="views",
+                    help="with --tensors, where the tensors lie: views into the rows of the flat arrays, back to "
+                         "back (the library joins them); every parameter stacked to its own [P, size] torch "
+                         "allocation; or every tensor of every replica a torch allocation of its own")
     ap.add_argument("--graph", action="store_true",
                     help="capture the K steps in one HIP graph and time its replay (for launch-bound sizes)")
     ap.add_argument("--lag", type=int, default=None, metavar="TOLERANCE_MS",
@@ -358,8 +363,25 @@ def main() -> int:
                         at += size
                     out.append(row)
                 return out
-            plan = ctx.tensor_plan(views(w), views(g), views(m), views(pub))
-            log("per-tensor layout: %d tensors per replica" % len(sizes))
+            if args.tensor_layout == "views":
+                lists = [views(w), views(g), views(m), views(pub)]
+            else:
+                # the tensors live in torch allocations of their own (the flat arrays stay unused);
+                # the bandwidth does not depend on the values: small normal numbers, as in the rows
+                lists = []
+                for scale in (0.05, 0.01, 0.01, 0.05):
+                    if args.tensor_layout == "stacked":
+                        stacks = [torch.empty((P, size + (-size) % 4), device="cuda").normal_(0.0, scale)
+                                  for size in sizes]
+                        lists.append([[stack[p, :size] for stack, size in zip(stacks, sizes)] for p in range(P)])
+                    else:
+                        per = [[torch.empty(size, device="cuda") for size in sizes] for p in range(P)]
+                        every = [t for row in per for t in row]
+                        torch._foreach_zero_(every)          # P x T allocations, filled by a few launches
+                        torch._foreach_add_(every, scale)
+                        lists.append(per)
+            plan = ctx.tensor_plan(*lists)
+            log("per-tensor layout (%s): %d tensors per replica" % (args.tensor_layout, len(sizes)))
 
         def step(t):
             b = None if busy_masks is None else busy_masks[t]
@@ -404,7 +426,10 @@ def main() -> int:
                 "avg_launch_ms": dom_ms / len(dom_ts), "launches": len(dom_ts),
                 "algorithmic_bytes_per_launch": sum(bytes_of[t] for t in dom_ts) / len(dom_ts),
                 "traffic": None, "traffic_source": None}
-    stored = (MEASURED_TRAFFIC_PER_TENSOR if args.tensors else MEASURED_TRAFFIC).get(wl.index)
+    if args.tensors:
+        stored = MEASURED_TRAFFIC_PER_TENSOR.get(wl.index) if args.tensor_layout == "stacked" else None
+    else:
+        stored = MEASURED_TRAFFIC.get(wl.index)
     if (stored and grp and defaults_match and not args.opt and not args.ld and args.lag is None
             and not custom and not args.graph):
         # HBM bytes of such a launch as the counters measured them in the profiled run; stale
@@ -423,7 +448,7 @@ def main() -> int:
                    % (args.lag, sum(late) / max(1, P * len(grp)), sum(busy) / max(1, P * len(grp))),
                    "global_steps_in_run": len(glb),
                    "options": args.opt, "allocation": placement,
-                   "layout": "per-tensor" if args.tensors else "flat rows",
+                   "layout": "per-tensor (%s)" % args.tensor_layout if args.tensors else "flat rows",
                    "launch": "one HIP graph of K steps" if args.graph else "one launch per step"},
         "hbm_gbs_all_steps": sum(bytes_of) / ((grp_ms + glb_ms) * 1e-3) / 1e9,
         "group_step_ms": (grp_ms / len(grp)) if grp else None,

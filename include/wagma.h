@@ -159,10 +159,16 @@ int wagma_step(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub,
  * wagma_tensors_create copies the tables to the device (allocation, copy and synchronisation
  * happen here, none in the step); the plan refers to ctx and to the tensors, which must stay
  * where they are while the plan is used.  Destroy the plan before its context.
- * Any placement of the tensors gives the same results.  Fastest (2 to 10 % over the general
- * case, more with larger groups) is one where the P replicas of a tensor lie equally far apart,
- * by the same distance in w, g, m and pub: a parameter stacked to [P, ...], or views into P rows.
- * wagma_tensors_create recognises that by itself and the step then reads no pointer tables.
+ * Any placement of the tensors gives the same results; wagma_tensors_create recognises by
+ * itself what makes the step faster:
+ *   - tensors that follow one another without a gap, in every array of every process (views into
+ *     one buffer per process), count as one tensor: a model that is views into P rows, back to
+ *     back, runs at the rate of wagma_step;
+ *   - where the P replicas of a tensor lie equally far apart, by the same distance in w, g, m
+ *     and pub (a parameter stacked to [P, ...], views into P rows), the step reads no pointer
+ *     tables: 2 to 10 % faster, more with larger groups;
+ *   - large tensors that begin at the same address modulo 64 KiB in every process and array
+ *     (a distance between replicas that is a multiple of 64 KiB, or allocations of their own).
  */
 typedef struct wagma_tensors wagma_tensors;
 int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64_t* sizes,

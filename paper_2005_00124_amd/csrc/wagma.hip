@@ -571,21 +571,13 @@ int wagma_step_static(int P, int S, int64_t n, int tau, int64_t ld, float* w, co
 
 // ---- per-tensor layout ------------------------------------------------------------------
 
-int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64_t* sizes,
-                         float* const* w, const float* const* g, float* const* m, float* const* pub)
+namespace {
+
+// The plan for T tensors as they are given (arguments already checked: see wagma_tensors_create).
+int create_plan(wagma_ctx* ctx, wagma_tensors** out, int T, const int64_t* sizes, float* const* w,
+                const float* const* g, float* const* m, float* const* pub)
 {
-    if (!out)
-        return WAGMA_EINVAL;
-    *out = nullptr;
-    if (!ctx || T < 1 || T > (1 << 20) || !sizes || !w || !g || !m || !pub)
-        return WAGMA_EINVAL;
     const size_t slots = (size_t)ctx->P * (size_t)T;
-    for (size_t i = 0; i < slots; ++i) {
-        if (!w[i] || !g[i] || !m[i] || !pub[i])
-            return WAGMA_EINVAL;
-        if ((((uintptr_t)w[i]) | ((uintptr_t)g[i]) | ((uintptr_t)m[i]) | ((uintptr_t)pub[i])) & 15u)
-            return WAGMA_EINVAL;
-    }
     // Every whole 256 KiB of a tensor becomes a mapped block whose slices are dealt out by the launch
     // shape for a caller's arrays (a plan's tensors are always the caller's), as in the flat layout;
     // the rest is contiguous 4 KiB tiles in runs of 8 per XCD (measured best: tile by tile is 2-5 %
@@ -597,14 +589,6 @@ int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64
                                    : wagma_detail::kLaunchShapes[wagma_detail::kForeignShape].map;
     const int xcd_chunk_log2 = ctx->opt_xcd_chunk_log2 < 0 ? 2 : ctx->opt_xcd_chunk_log2;
     const int run_log2 = xcd_chunk_log2 > 0 ? (xcd_chunk_log2 < 7 ? xcd_chunk_log2 + 1 : 8) : 0;
-    int64_t total = 0;
-    for (int k = 0; k < T; ++k) {
-        if (sizes[k] < 1 || sizes[k] > kMaxN)
-            return WAGMA_EINVAL;
-        total += sizes[k];
-    }
-    if (total != ctx->n)
-        return WAGMA_EINVAL;
     std::vector<TileRef> table;
     int64_t tiles = 0;
     try {
@@ -708,6 +692,73 @@ int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64
     plan->map = block_map;
     *out = plan;
     return WAGMA_OK;
+}
+
+}  // namespace
+
+int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64_t* sizes,
+                         float* const* w, const float* const* g, float* const* m, float* const* pub)
+{
+    if (!out)
+        return WAGMA_EINVAL;
+    *out = nullptr;
+    if (!ctx || T < 1 || T > (1 << 20) || !sizes || !w || !g || !m || !pub)
+        return WAGMA_EINVAL;
+    const size_t slots = (size_t)ctx->P * (size_t)T;
+    for (size_t i = 0; i < slots; ++i) {
+        if (!w[i] || !g[i] || !m[i] || !pub[i])
+            return WAGMA_EINVAL;
+        if ((((uintptr_t)w[i]) | ((uintptr_t)g[i]) | ((uintptr_t)m[i]) | ((uintptr_t)pub[i])) & 15u)
+            return WAGMA_EINVAL;
+    }
+    int64_t total = 0;
+    for (int k = 0; k < T; ++k) {
+        if (sizes[k] < 1 || sizes[k] > kMaxN)
+            return WAGMA_EINVAL;
+        total += sizes[k];
+    }
+    if (total != ctx->n)
+        return WAGMA_EINVAL;
+    if (ctx->opt_tensor_tables)
+        return create_plan(ctx, out, T, sizes, w, g, m, pub);
+    // The step works element by element and knows no tensor boundaries: tensors that follow one
+    // another without a gap, in every array of every process (views into one buffer per process),
+    // are one tensor to it.  Fewer, longer tensors leave fewer short ends outside the mapped blocks.
+    try {
+        const void* const* arrays[4] = {(const void* const*)w, (const void* const*)g, (const void* const*)m,
+                                        (const void* const*)pub};
+        std::vector<int> first_of;  // joined tensor j begins with tensor first_of[j]
+        std::vector<int64_t> joined_sizes;
+        for (int k = 0; k < T; ++k) {
+            bool joins = k > 0;
+            for (int a = 0; a < 4 && joins; ++a)
+                for (int r = 0; r < ctx->P && joins; ++r) {
+                    const size_t i = (size_t)r * T + k;
+                    joins = (uintptr_t)arrays[a][i] == (uintptr_t)arrays[a][i - 1] + (uintptr_t)sizes[k - 1] * sizeof(float);
+                }
+            if (joins) {
+                joined_sizes.back() += sizes[k];
+            } else {
+                first_of.push_back(k);
+                joined_sizes.push_back(sizes[k]);
+            }
+        }
+        const int J = (int)first_of.size();
+        if (J == T)
+            return create_plan(ctx, out, T, sizes, w, g, m, pub);
+        std::vector<const void*> joined[4];
+        for (int a = 0; a < 4; ++a) {
+            joined[a].resize((size_t)ctx->P * J);
+            for (int r = 0; r < ctx->P; ++r)
+                for (int j = 0; j < J; ++j)
+                    joined[a][(size_t)r * J + j] = arrays[a][(size_t)r * T + first_of[(size_t)j]];
+        }
+        return create_plan(ctx, out, J, joined_sizes.data(), (float* const*)joined[0].data(),
+                           (const float* const*)joined[1].data(), (float* const*)joined[2].data(),
+                           (float* const*)joined[3].data());
+    } catch (const std::bad_alloc&) {
+        return WAGMA_ENOMEM;
+    }
 }
 
 int wagma_tensors_destroy(wagma_tensors* plan)

@@ -22,15 +22,19 @@ def bits(a):
 
 
 def make_arrays(P, sizes, gen, scale, layout="separate"):
-    """For every process a list of tensors with sentinels around each.  layout "separate": every
-    tensor of every process in an allocation of its own; "arena": views into one row per process
-    (rows 64 KiB-multiples apart: a tensor then crosses the 64 KiB boundaries of the address space
-    at the same place in every process); "stacked": the P replicas of a tensor side by side in one
-    allocation.  In the last two the replicas of a tensor lie equally far apart, in every array
-    alike: the plan then finds its tensors without the pointer tables."""
-    arrays, guards = [], []
-    if layout == "arena":
-        row = (sum(sizes) + (len(sizes) + 1) * GUARD + 16383) // 16384 * 16384
+    """For every process a list of tensors, and the sentinels around them (views that must still
+    hold 777 at the end).  layout "separate": every tensor of every process in an allocation of
+    its own; "arena": views into one row per process with sentinels between them (rows 64
+    KiB-multiples apart: a tensor then crosses the 64 KiB boundaries of the address space at the same
+    place in every process); "packed": views into one row per process, back to back (a tensor whose
+    size is no multiple of 4 is followed by 1..3 sentinels, the others by the next tensor: the plan
+    joins those); "stacked": the P replicas of a tensor side by side in one allocation.  In the last
+    three the replicas of a tensor lie equally far apart, in every array alike: the plan then finds
+    its tensors without the pointer tables."""
+    arrays, sentinels = [], []
+    if layout in ("arena", "packed"):
+        gap = GUARD if layout == "arena" else 0
+        row = (sum(size + (-size) % 4 + gap for size in sizes) + 2 * GUARD + 16383) // 16384 * 16384
         slab = torch.full((P, row), 777.0, device="cuda")
         for p in range(P):
             tensors, at = [], GUARD
@@ -38,22 +42,25 @@ def make_arrays(P, sizes, gen, scale, layout="separate"):
                 t = slab[p, at:at + size]
                 t.normal_(0.0, scale, generator=gen)
                 tensors.append(t)
-                guards.append(slab[p, at - GUARD:at + size + GUARD])
-                at += size + GUARD + (-size) % 4
+                sentinels.append(slab[p, at - GUARD:at] if at == GUARD or gap else slab[p, at:at])
+                at += size
+                sentinels.append(slab[p, at:at + (-size) % 4 + gap])
+                at += (-size) % 4 + gap
+            sentinels.append(slab[p, at:])
             arrays.append(tensors)
-        return arrays, guards
+        return arrays, sentinels
     stacks = [torch.full((P, size + (-size) % 4 + 2 * GUARD), 777.0, device="cuda") for size in sizes] \
         if layout == "stacked" else None
     for p in range(P):
         tensors = []
         for k, size in enumerate(sizes):
-            buf = stacks[k][p, :size + 2 * GUARD] if stacks else torch.full((size + 2 * GUARD,), 777.0, device="cuda")
+            buf = stacks[k][p] if stacks else torch.full((size + 2 * GUARD,), 777.0, device="cuda")
             t = buf[GUARD:GUARD + size]          # 32-byte offset: still 16-byte aligned
             t.normal_(0.0, scale, generator=gen)
             tensors.append(t)
-            guards.append(buf)
+            sentinels += [buf[:GUARD], buf[GUARD + size:]]
         arrays.append(tensors)
-    return arrays, guards
+    return arrays, sentinels
 
 
 def to_rows(arrays):
@@ -90,9 +97,8 @@ def run_tensor_case(P, S, sizes, tau, iters, q, seed, fixed_groups=False, option
                     h = to_rows(have)
                     assert np.array_equal(bits(h), bits(want)), "%s differs at t=%d" % (what, t)
         assert np.array_equal(bits(to_rows(g)), bits(og)), "g was written"
-        for buf in gw + gg + gm + gp:
-            assert bool((buf[:GUARD] == 777.0).all()) and bool((buf[-GUARD:] == 777.0).all()), \
-                "an element outside a tensor was written"
+        for sentinel in gw + gg + gm + gp:
+            assert bool((sentinel == 777.0).all()), "an element outside a tensor was written"
 
 
 RAGGED = [1, 2, 3, 4, 5, 7, 64, 255, 257, 1000, 1023, 1025, 4099, 70001]
@@ -127,6 +133,21 @@ def test_tensors_blocks_on_address_boundaries(P, S):
     """Tensors that are views into rows 64 KiB-multiples apart: the mapped blocks begin on a 64 KiB
     boundary of the address space, the slices before it are contiguous tiles."""
     run_tensor_case(P, S, [70001, 65536 + 8, 3, 2 * 65536 + 20000, 1000], tau=3, iters=4, q=0.3, seed=500 + P + S, layout="arena")
+
+
+@pytest.mark.parametrize("P,S", [(16, 4), (32, 8), (16, 16), (32, 32)])
+def test_tensors_back_to_back_are_joined(P, S):
+    """Views into one row per process, back to back: the plan treats tensors without a gap between
+    them as one (here 4 + 2 + 2 tensors become three), which moves the tiles and the mapped blocks
+    but not a single bit of the result."""
+    run_tensor_case(P, S, [1000, 64, 70000, 4097, 36864, 5, 65536 + 20, 3], tau=3, iters=4, q=0.3,
+                    seed=700 + P + S, layout="packed")
+
+
+def test_tensors_back_to_back_taken_one_by_one():
+    """The same views with the plan told to take the tensor list as it is."""
+    run_tensor_case(32, 8, [1000, 64, 70000, 4097, 36864, 5, 65536 + 20, 3], tau=3, iters=3, q=0.3, seed=777,
+                    layout="packed", options=((lw.WAGMA_DEBUG_TENSOR_TABLES, 1),))
 
 
 def test_tensors_spaced_alike_through_the_pointer_tables():
