@@ -618,18 +618,18 @@ int create_plan(wagma_ctx* ctx, wagma_tensors** out, int T, const int64_t* sizes
     if (device != ctx->device)
         return WAGMA_EINVAL;
 
-    // Are the tensors spaced alike in every array: tensor k of process r a fixed number of floats,
-    // the same in all four arrays, behind that of process r - 1?  (A stack of the P replicas of a
-    // parameter, or views into P rows.)  Then every tile's entry also names its tensor's place, and
-    // the kernels look nothing else up.
-    bool affine = !ctx->opt_tensor_tables;
-    for (int k = 0; k < T && affine && ctx->P > 1; ++k) {
+    // Where the replicas of every tensor are spaced alike in all four arrays, every tile's entry
+    // also names its tensor's place, and the kernels look nothing else up.
+    std::vector<int64_t> step_bytes;
+    bool affine = false;
+    if (!ctx->opt_tensor_tables) {
         const void* const* arrays[4] = {(const void* const*)w, (const void* const*)g, (const void* const*)m,
                                         (const void* const*)pub};
-        const intptr_t step = (intptr_t)w[(size_t)T + k] - (intptr_t)w[k];
-        for (int a = 0; a < 4 && affine; ++a)
-            for (int r = 1; r < ctx->P && affine; ++r)
-                affine = (intptr_t)arrays[a][(size_t)r * T + k] - (intptr_t)arrays[a][(size_t)(r - 1) * T + k] == step;
+        try {
+            affine = wagma_detail::spaced_alike(ctx->P, T, arrays, step_bytes);
+        } catch (const std::bad_alloc&) {
+            return WAGMA_ENOMEM;
+        }
     }
 
     // blob layout: [4 pointer tables][tiles tile refs][tiles 64-byte entries, if the tensors are
@@ -663,8 +663,7 @@ int create_plan(wagma_ctx* ctx, wagma_tensors** out, int T, const int64_t* sizes
         for (int64_t i = 0; i < tiles; ++i) {
             const TileRef& ref = table[(size_t)i];
             const int k = ref.tensor;  // an empty tile names tensor 0 and touches nothing
-            const intptr_t step = ctx->P > 1 ? (intptr_t)w[(size_t)T + k] - (intptr_t)w[k] : 0;
-            entries[i] = AffineTile{ref, (int64_t)(step / (intptr_t)sizeof(float)), w[k], g[k], m[k], pub[k], 0};
+            entries[i] = AffineTile{ref, step_bytes[(size_t)k] / (int64_t)sizeof(float), w[k], g[k], m[k], pub[k], 0};
         }
     }
     char* dev = nullptr;
@@ -727,22 +726,9 @@ int wagma_tensors_create(wagma_ctx* ctx, wagma_tensors** out, int T, const int64
     try {
         const void* const* arrays[4] = {(const void* const*)w, (const void* const*)g, (const void* const*)m,
                                         (const void* const*)pub};
-        std::vector<int> first_of;  // joined tensor j begins with tensor first_of[j]
+        std::vector<int> first_of;
         std::vector<int64_t> joined_sizes;
-        for (int k = 0; k < T; ++k) {
-            bool joins = k > 0;
-            for (int a = 0; a < 4 && joins; ++a)
-                for (int r = 0; r < ctx->P && joins; ++r) {
-                    const size_t i = (size_t)r * T + k;
-                    joins = (uintptr_t)arrays[a][i] == (uintptr_t)arrays[a][i - 1] + (uintptr_t)sizes[k - 1] * sizeof(float);
-                }
-            if (joins) {
-                joined_sizes.back() += sizes[k];
-            } else {
-                first_of.push_back(k);
-                joined_sizes.push_back(sizes[k]);
-            }
-        }
+        wagma_detail::join_tensors(ctx->P, T, sizes, arrays, first_of, joined_sizes);
         const int J = (int)first_of.size();
         if (J == T)
             return create_plan(ctx, out, T, sizes, w, g, m, pub);

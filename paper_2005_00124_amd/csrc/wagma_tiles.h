@@ -4,6 +4,7 @@
 #ifndef WAGMA_TILES_H
 #define WAGMA_TILES_H
 
+#include <cstddef>
 #include <cstdint>
 #include <vector>
 
@@ -106,6 +107,48 @@ inline int64_t build_tile_table(int T, const int64_t* sizes, const int* phase, u
         refs[(size_t)(mapped_tiles + i)] = in_order[(size_t)linear];
     }
     return mapped_tiles;
+}
+
+// The step works element by element and knows no tensor boundaries: tensors that follow one
+// another without a gap, in every array of every process (views into one buffer per process), are
+// one tensor to it.  arrays[a][r * T + k] is tensor k of process r in array a (w, g, m, pub).
+// Joined tensor j begins with tensor first_of[j] and has joined_sizes[j] floats.
+inline void join_tensors(int P, int T, const int64_t* sizes, const void* const* const arrays[4],
+                         std::vector<int>& first_of, std::vector<int64_t>& joined_sizes)
+{
+    first_of.clear();
+    joined_sizes.clear();
+    for (int k = 0; k < T; ++k) {
+        bool joins = k > 0;
+        for (int a = 0; a < 4 && joins; ++a)
+            for (int r = 0; r < P && joins; ++r) {
+                const size_t i = (size_t)r * T + k;
+                joins = (uintptr_t)arrays[a][i] == (uintptr_t)arrays[a][i - 1] + (uintptr_t)sizes[k - 1] * sizeof(float);
+            }
+        if (joins) {
+            joined_sizes.back() += sizes[k];
+        } else {
+            first_of.push_back(k);
+            joined_sizes.push_back(sizes[k]);
+        }
+    }
+}
+
+// Are the tensors spaced alike in every array: tensor k of process r a fixed number of bytes, the
+// same in all four arrays, behind that of process r - 1?  (A stack of the P replicas of a
+// parameter, or views into P rows.)  step_bytes[k] is that distance (0 with one process).
+inline bool spaced_alike(int P, int T, const void* const* const arrays[4], std::vector<int64_t>& step_bytes)
+{
+    step_bytes.assign((size_t)T, 0);
+    for (int k = 0; k < T && P > 1; ++k) {
+        const intptr_t step = (intptr_t)arrays[0][(size_t)T + k] - (intptr_t)arrays[0][k];
+        for (int a = 0; a < 4; ++a)
+            for (int r = 1; r < P; ++r)
+                if ((intptr_t)arrays[a][(size_t)r * T + k] - (intptr_t)arrays[a][(size_t)(r - 1) * T + k] != step)
+                    return false;
+        step_bytes[(size_t)k] = (int64_t)step;
+    }
+    return true;
 }
 
 }  // namespace wagma_detail

@@ -1,7 +1,8 @@
 """The tile table of the per-tensor layout (csrc/wagma_tiles.h: which workgroup takes which slices of
 which tensor) on the CPU: the header has no HIP in it, so a small driver (tests/tiles_host.cpp, built
 with the address and undefined-behaviour sanitizers) checks here that for mixes of tensor sizes,
-address phases, maps and XCD run lengths every element of every tensor belongs to exactly one lane."""
+address phases, maps and XCD run lengths every element of every tensor belongs to exactly one lane, and
+that tensors are joined, and taken as spaced alike, exactly when their pointers say so."""
 import os
 import subprocess
 

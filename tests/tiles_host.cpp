@@ -2,6 +2,7 @@
 // for lists of tensor sizes, address phases, maps and XCD run lengths, the lanes of the table's
 // tiles, taken the way the kernels take them (a lane owns the four floats of its slice, cut off at
 // the size its tile names), must touch every element of every tensor exactly once and nothing else.
+// Also: which tensors a plan joins, and when it counts the replicas of the tensors as spaced alike.
 #include <cstdint>
 #include <cstdio>
 #include <vector>
@@ -78,8 +79,90 @@ static void check(const char* what, const std::vector<int64_t>& sizes, const std
     }
 }
 
+// Pointer sets made of plain numbers: array a of process r begins at base[a] + r * row_bytes, and
+// tensor k lies offset[k] bytes into it.
+struct Pointers {
+    std::vector<const void*> at[4];
+    const void* const* arrays[4];
+    Pointers(int P, const std::vector<int64_t>& offset, int64_t row_bytes)
+    {
+        const int T = (int)offset.size();
+        for (int a = 0; a < 4; ++a) {
+            at[a].resize((size_t)P * T);
+            for (int r = 0; r < P; ++r)
+                for (int k = 0; k < T; ++k)
+                    at[a][(size_t)r * T + k] = (const void*)(uintptr_t)(0x100000000ull * (a + 1) + r * row_bytes + offset[(size_t)k]);
+            arrays[a] = at[a].data();
+        }
+    }
+};
+
+static void expect(bool ok, const char* what)
+{
+    if (!ok) {
+        std::printf("FAILED: %s\n", what);
+        ++failures;
+    }
+}
+
+static void check_joining()
+{
+    const int P = 3;
+    const std::vector<int64_t> sizes = {100, 64, 7, 8, 12, 4};
+    // 100 and 64 back to back; 7 follows 64 at once but leaves a gap (its 28 bytes are padded to 32);
+    // 8 and 12 back to back; 4 after a gap of one slice
+    const std::vector<int64_t> offset = {0, 400, 656, 688, 720, 784};
+    std::vector<int> first_of;
+    std::vector<int64_t> joined;
+    {
+        Pointers p(P, offset, 4096);
+        join_tensors(P, (int)sizes.size(), sizes.data(), p.arrays, first_of, joined);
+        expect(first_of == std::vector<int>({0, 3, 5}) && joined == std::vector<int64_t>({171, 20, 4}), "joining back-to-back tensors");
+        std::vector<int64_t> step;
+        expect(spaced_alike(P, (int)sizes.size(), p.arrays, step) && step == std::vector<int64_t>(6, 4096), "rows spaced alike");
+        // one process of one array holds tensor 1 elsewhere: nothing joins it, and the spacing is gone
+        p.at[2][(size_t)1 * sizes.size() + 1] = (const void*)((uintptr_t)p.at[2][(size_t)1 * sizes.size() + 1] + 16);
+        join_tensors(P, (int)sizes.size(), sizes.data(), p.arrays, first_of, joined);
+        expect(first_of == std::vector<int>({0, 1, 2, 3, 5}) && joined == std::vector<int64_t>({100, 64, 7, 20, 4}),
+               "a gap in one process of one array");
+        expect(!spaced_alike(P, (int)sizes.size(), p.arrays, step), "spacing broken in one array");
+    }
+    {
+        // the same distance within every array, but another one in g: not alike
+        Pointers p(P, offset, 4096);
+        for (int r = 0; r < P; ++r)
+            for (size_t k = 0; k < sizes.size(); ++k)
+                p.at[1][(size_t)r * sizes.size() + k] = (const void*)(uintptr_t)(0x900000000ull + r * 8192 + offset[k]);
+        std::vector<int64_t> step;
+        expect(!spaced_alike(P, (int)sizes.size(), p.arrays, step), "another distance in one array");
+        join_tensors(P, (int)sizes.size(), sizes.data(), p.arrays, first_of, joined);
+        expect(first_of == std::vector<int>({0, 3, 5}), "joining does not need equal distances");
+    }
+    {
+        // one process: always spaced alike, distance 0; a negative distance is a distance too
+        Pointers one(1, offset, 4096);
+        std::vector<int64_t> step;
+        expect(spaced_alike(1, (int)sizes.size(), one.arrays, step) && step == std::vector<int64_t>(6, 0), "one process");
+        Pointers back(P, offset, -8192);
+        expect(spaced_alike(P, (int)sizes.size(), back.arrays, step) && step == std::vector<int64_t>(6, -8192), "rows in descending order");
+    }
+    {
+        // stacked parameters: every tensor its own distance
+        const int T = 3;
+        Pointers p(2, {0, 0, 0}, 0);
+        const int64_t bases[T] = {0x1000, 0x20000, 0x300000}, dist[T] = {400, 4096, 65536};
+        for (int a = 0; a < 4; ++a)
+            for (int r = 0; r < 2; ++r)
+                for (int k = 0; k < T; ++k)
+                    p.at[a][(size_t)r * T + k] = (const void*)(uintptr_t)(0x100000000ull * (a + 1) + bases[k] + r * dist[k]);
+        std::vector<int64_t> step;
+        expect(spaced_alike(2, T, p.arrays, step) && step == std::vector<int64_t>({400, 4096, 65536}), "stacked parameters");
+    }
+}
+
 int main()
 {
+    check_joining();
     const uint64_t maps[] = {0, kLaunchShapes[kForeignShape].map, 0x9876543210ull, 0x0123456789ull, 0x5329618470ull};
     const std::vector<std::vector<int64_t>> lists = {
         {1},
