@@ -492,7 +492,9 @@ def main() -> int:
         summary = {wl.index: {"workload": wl.name, "value": out["value"], "ms_per_step": out["ms_per_step"],
                               "group_step_gbs": roofline["achieved"], "frac": roofline["frac"],
                               "global_step_gbs": out["global_step_gbs"]}}
-        for k in range(1, len(wk.WORKLOADS) + 1):
+        # the largest first: how much of a box's memory earlier processes have used and given back
+        # shows in the rates (workload 5 as the first process on a box: 0.82; after the others: 0.79)
+        for k in range(len(wk.WORKLOADS), 0, -1):
             if k == wl.index:
                 continue
             log("workload %d ..." % k)
@@ -506,7 +508,7 @@ def main() -> int:
                 o = json.loads(line[-1])
                 summary[k] = {"workload": o["config"]["workload"], "value": o["value"], "ms_per_step": o["ms_per_step"],
                               "group_step_gbs": o["roofline"]["achieved"], "frac": o["roofline"]["frac"],
-                              "global_step_gbs": o["global_step_gbs"]}
+                              "global_step_gbs": o["global_step_gbs"], "allocation": o["config"]["allocation"]}
             except (RuntimeError, subprocess.TimeoutExpired, ValueError) as e:
                 summary[k] = {"error": str(e)[-300:]}
         out["workloads"] = {str(k): summary[k] for k in sorted(summary)}

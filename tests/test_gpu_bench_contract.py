@@ -37,3 +37,16 @@ def test_bench_json_contract():
     a = c["all_cores"]
     assert a["cores"] == 2 and a["value"] > 0 and a["sample"] and a["cpu_model"]
     assert r["traffic"] is None and r["traffic_source"] is None      # no counter run stored for workload 1
+
+
+@pytest.mark.parametrize("layout", ["views", "stacked", "separate"])
+def test_bench_per_tensor_layouts(layout):
+    """--tensors on the 161-tensor model of workload 2, in each of the three places the tensors can lie."""
+    out = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--workload", "2", "--steps", "4",
+                          "--warmup", "1", "--no-cpu-baseline", "--no-extras", "--tensors", "--tensor-layout", layout],
+                         capture_output=True, text=True, cwd=ROOT, timeout=600)
+    assert out.returncode == 0, out.stderr[-2000:]
+    d = json.loads([l for l in out.stdout.splitlines() if l.strip()][-1])
+    assert d["config"]["layout"] == "per-tensor (%s)" % layout
+    assert d["value"] > 0 and 0.3 < d["roofline"]["frac"] < 1.0
+    assert d["roofline"]["traffic"] is None      # the stored counter figure is workload 4's, stacked
