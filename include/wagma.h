@@ -165,8 +165,10 @@ int wagma_step(wagma_ctx* ctx, float* w, const float* g, float* m, float* pub,
  *     one buffer per process), count as one tensor: a model that is views into P rows, back to
  *     back, runs at the rate of wagma_step;
  *   - where the P replicas of a tensor lie equally far apart, by the same distance in w, g, m
- *     and pub (a parameter stacked to [P, ...], views into P rows), the step reads no pointer
- *     tables: 2 to 10 % faster, more with larger groups;
+ *     and pub (a parameter stacked to [P, ...], views into P rows), the step computes every
+ *     address from one table entry per 4 KiB tile; else it reads the tensors' pointers from a
+ *     table laid out by the places of the group schedule (the same rate for groups of up to 8,
+ *     a few per cent less for larger ones);
  *   - large tensors that begin at the same address modulo 64 KiB in every process and array
  *     (a distance between replicas that is a multiple of 64 KiB, or allocations of their own).
  */

@@ -172,19 +172,20 @@ struct wagma_tensors {
     wagma_ctx* ctx;
     int T;
     int64_t tiles;      // workgroups per group
-    void* d_blob;       // one device allocation: four pointer tables ([T][P]), the tile table
-    float* const* tw;
-    const float* const* tg;
-    float* const* tm;
-    float* const* tpub;
+    void* d_blob;       // one device allocation: the tile table, and either its 64-byte entries or the pointers by place
     const TileRef* tile_ref;
     const AffineTile* affine_tile;  // not NULL: the tensors are spaced alike in every array, and the tile
                                     // table exists in this form too (the kernels then read nothing else)
+    const SlotPointers* slot_ptrs;  // not NULL: [period + 1][units][P], every tensor's pointers by the places
+                                    // of each row of the schedule table (instead of the pointer tables)
+    int64_t units;                  // mapped blocks + tensors
+    int64_t mapped_tiles;           // the first so many tiles of the tile table belong to mapped blocks
     uint64_t map;       // how the slices of the mapped blocks of the tile table are dealt out (0: no such blocks)
 };
 
 namespace {
 constexpr int kTensorBlock = kBlock;  // threads per workgroup of the per-tensor kernels
+constexpr int64_t kMaxByPlaceBytes = int64_t(4) << 30;  // a plan's pointers by place may take no more than this
 
 template <bool NT, bool LAG, bool AFFINE>
 void launch_tensors(const StepParams& p, bool cooperative, unsigned grid, hipStream_t stream)
@@ -577,7 +578,6 @@ namespace {
 int create_plan(wagma_ctx* ctx, wagma_tensors** out, int T, const int64_t* sizes, float* const* w,
                 const float* const* g, float* const* m, float* const* pub)
 {
-    const size_t slots = (size_t)ctx->P * (size_t)T;
     // Every whole 256 KiB of a tensor becomes a mapped block whose slices are dealt out by the launch
     // shape for a caller's arrays (a plan's tensors are always the caller's), as in the flat layout;
     // the rest is contiguous 4 KiB tiles in runs of 8 per XCD (measured best: tile by tile is 2-5 %
@@ -590,7 +590,7 @@ int create_plan(wagma_ctx* ctx, wagma_tensors** out, int T, const int64_t* sizes
     const int xcd_chunk_log2 = ctx->opt_xcd_chunk_log2 < 0 ? 2 : ctx->opt_xcd_chunk_log2;
     const int run_log2 = xcd_chunk_log2 > 0 ? (xcd_chunk_log2 < 7 ? xcd_chunk_log2 + 1 : 8) : 0;
     std::vector<TileRef> table;
-    int64_t tiles = 0;
+    int64_t tiles = 0, mapped_tiles = 0;
     try {
         // a tensor's address modulo 64 KiB, if it is the same in every process and array
         std::vector<int> phase((size_t)T);
@@ -604,7 +604,7 @@ int create_plan(wagma_ctx* ctx, wagma_tensors** out, int T, const int64_t* sizes
             }
             phase[(size_t)k] = same ? (int)first : -1;
         }
-        wagma_detail::build_tile_table(T, sizes, phase.data(), block_map, run_log2, table);
+        mapped_tiles = wagma_detail::build_tile_table(T, sizes, phase.data(), block_map, run_log2, table);
         tiles = (int64_t)table.size();
     } catch (const std::bad_alloc&) {
         return WAGMA_ENOMEM;
@@ -619,25 +619,35 @@ int create_plan(wagma_ctx* ctx, wagma_tensors** out, int T, const int64_t* sizes
         return WAGMA_EINVAL;
 
     // Where the replicas of every tensor are spaced alike in all four arrays, every tile's entry
-    // also names its tensor's place, and the kernels look nothing else up.
+    // also names its tensor's place, and the kernels look nothing else up.  Else every tensor's
+    // pointers are laid out by the places of each row of the schedule table, once per mapped block
+    // and once per tensor: a workgroup of a mapped block then asks for them by its own number,
+    // together with its tile's entry and the ranks.
+    const void* const* arrays[4] = {(const void* const*)w, (const void* const*)g, (const void* const*)m,
+                                    (const void* const*)pub};
     std::vector<int64_t> step_bytes;
+    std::vector<SlotPointers> by_place;
     bool affine = false;
-    if (!ctx->opt_tensor_tables) {
-        const void* const* arrays[4] = {(const void* const*)w, (const void* const*)g, (const void* const*)m,
-                                        (const void* const*)pub};
-        try {
-            affine = wagma_detail::spaced_alike(ctx->P, T, arrays, step_bytes);
-        } catch (const std::bad_alloc&) {
-            return WAGMA_ENOMEM;
+    int64_t units = 0;
+    try {
+        affine = !ctx->opt_tensor_tables && wagma_detail::spaced_alike(ctx->P, T, arrays, step_bytes);
+        if (!affine) {
+            const int rows = ctx->period + 1;
+            if (((mapped_tiles >> 6) + T) * rows * ctx->P * (int64_t)sizeof(SlotPointers) > kMaxByPlaceBytes)
+                return WAGMA_ENOMEM;
+            units = wagma_detail::build_slot_pointers(ctx->P, T, rows, ctx->h_table, table, mapped_tiles, arrays,
+                                                      by_place);
         }
+    } catch (const std::bad_alloc&) {
+        return WAGMA_ENOMEM;
     }
 
-    // blob layout: [4 pointer tables][tiles tile refs][tiles 64-byte entries, if the tensors are
-    // spaced alike]; every part 64-byte aligned
-    const size_t table_bytes = (slots * sizeof(void*) + 63) / 64 * 64;
+    // blob layout: [tiles tile refs][tiles 64-byte entries, if the tensors are spaced alike, else
+    // the pointers by place]; every part 64-byte aligned
     const size_t refs_bytes = ((size_t)tiles * sizeof(TileRef) + 63) / 64 * 64;
     const size_t affine_bytes = affine ? (size_t)tiles * sizeof(AffineTile) : 0;
-    const size_t blob_bytes = 4 * table_bytes + refs_bytes + affine_bytes;
+    const size_t by_place_bytes = by_place.size() * sizeof(SlotPointers);
+    const size_t blob_bytes = refs_bytes + affine_bytes + by_place_bytes;
     char* host = (char*)std::malloc(blob_bytes);
     wagma_tensors* plan = new (std::nothrow) wagma_tensors();
     if (!host || !plan) {
@@ -646,25 +656,16 @@ int create_plan(wagma_ctx* ctx, wagma_tensors** out, int T, const int64_t* sizes
         return WAGMA_ENOMEM;
     }
     std::memset(host, 0, blob_bytes);
-    {
-        // the caller's tables are [P][T]; the device tables are [T][P]
-        const void* const* from[4] = {(const void* const*)w, (const void* const*)g, (const void* const*)m,
-                                      (const void* const*)pub};
-        for (int a = 0; a < 4; ++a) {
-            const void** to = (const void**)(host + (size_t)a * table_bytes);
-            for (int r = 0; r < ctx->P; ++r)
-                for (int k = 0; k < T; ++k)
-                    to[(size_t)k * ctx->P + r] = from[a][(size_t)r * T + k];
-        }
-    }
-    std::memcpy(host + 4 * table_bytes, table.data(), (size_t)tiles * sizeof(TileRef));
+    std::memcpy(host, table.data(), (size_t)tiles * sizeof(TileRef));
     if (affine) {
-        AffineTile* entries = (AffineTile*)(host + 4 * table_bytes + refs_bytes);
+        AffineTile* entries = (AffineTile*)(host + refs_bytes);
         for (int64_t i = 0; i < tiles; ++i) {
             const TileRef& ref = table[(size_t)i];
             const int k = ref.tensor;  // an empty tile names tensor 0 and touches nothing
             entries[i] = AffineTile{ref, step_bytes[(size_t)k] / (int64_t)sizeof(float), w[k], g[k], m[k], pub[k], 0};
         }
+    } else {
+        std::memcpy(host + refs_bytes, by_place.data(), by_place_bytes);
     }
     char* dev = nullptr;
     e = hipMalloc((void**)&dev, blob_bytes);
@@ -682,12 +683,11 @@ int create_plan(wagma_ctx* ctx, wagma_tensors** out, int T, const int64_t* sizes
     plan->T = T;
     plan->tiles = tiles;
     plan->d_blob = dev;
-    plan->tw = (float* const*)(dev + 0 * table_bytes);
-    plan->tg = (const float* const*)(dev + 1 * table_bytes);
-    plan->tm = (float* const*)(dev + 2 * table_bytes);
-    plan->tpub = (float* const*)(dev + 3 * table_bytes);
-    plan->tile_ref = (const TileRef*)(dev + 4 * table_bytes);
-    plan->affine_tile = affine ? (const AffineTile*)(dev + 4 * table_bytes + refs_bytes) : nullptr;
+    plan->tile_ref = (const TileRef*)dev;
+    plan->affine_tile = affine ? (const AffineTile*)(dev + refs_bytes) : nullptr;
+    plan->slot_ptrs = affine ? nullptr : (const SlotPointers*)(dev + refs_bytes);
+    plan->units = units;
+    plan->mapped_tiles = mapped_tiles;
     plan->map = block_map;
     *out = plan;
     return WAGMA_OK;
@@ -782,12 +782,11 @@ int wagma_step_tensors_lag(wagma_ctx* ctx, const wagma_tensors* plan, const uint
 
     StepParams p;
     const bool lag = fill_common(ctx, p, global != 0, late_mask, busy_mask, lr, mu, iter);
-    p.tw = plan->tw;
-    p.tg = plan->tg;
-    p.tm = plan->tm;
-    p.tpub = plan->tpub;
     p.tile_ref = plan->tile_ref;
     p.affine_tile = plan->affine_tile;
+    // this iteration's row of the schedule table, and the pointers laid out by its places
+    p.slot_ptrs = plan->slot_ptrs ? plan->slot_ptrs + (p.table - ctx->d_table) / ctx->P * plan->units * ctx->P : nullptr;
+    p.mapped_tiles = plan->mapped_tiles;
     p.map = plan->map;
     p.num_ranks = ctx->P;
     p.tiles = plan->tiles;  // a multiple of 8 (whole XCD rounds)

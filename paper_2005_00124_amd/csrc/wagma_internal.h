@@ -23,8 +23,8 @@ struct wagma_ctx {
     int stripe_forced;       // 1: opt_stripe_log2 was set through wagma_debug_set_option
     int opt_xcd_chunk_log2;  // -1: chosen per launch (see step_flat); >= 0: this value for every launch
     uint64_t opt_map;        // not 0: this tile-to-address map for every launch (see slice_of)
-    int opt_tensor_tables;   // 1: per-tensor plans take the tensor list as it is and look every tensor up in
-                             // the pointer tables, also where the tensors are spaced alike in every array
+    int opt_tensor_tables;   // 1: per-tensor plans take the tensor list as it is and find every tensor through
+                             // the pointers by place, also where the tensors are spaced alike in every array
     float* placed[4];        // w, g, m, pub handed out by wagma_alloc_buffers (or all NULL)
     int placed_shape;        // index into wagma_detail::kLaunchShapes: what wagma_alloc_buffers measured as
                              // best for steps on those arrays with the kernel that holds a group in registers
@@ -58,7 +58,8 @@ struct wagma_ctx {
                                         of a row; 0 (the default): no forced map */
 #define WAGMA_DEBUG_TENSOR_TABLES 13 /* 0/1: a per-tensor plan made after this takes the tensor list as it is given
                                         (tensors that follow one another without a gap are not joined) and finds
-                                        its tensors through the pointer tables even if they are spaced alike */
+                                        its tensors through the pointers laid out by place even if they are
+                                        spaced alike */
 extern "C" int wagma_debug_set_option(wagma_ctx* ctx, int option, int64_t value);
 extern "C" int wagma_debug_get_option(const wagma_ctx* ctx, int option, int64_t* value);
 

@@ -28,6 +28,7 @@ constexpr int kNumXcd = 8;      // accelerator complex dies of an MI355X
 constexpr int64_t kMaxN = int64_t(1) << 31;
 
 using wagma_detail::AffineTile;
+using wagma_detail::SlotPointers;
 using wagma_detail::TileRef;
 
 struct StepParams {
@@ -52,13 +53,11 @@ struct StepParams {
     int xcd_chunk_log2;    // log2 of the run of consecutive tiles one XCD works on (0: 1 tile)
     uint64_t map;          // not 0: replaces the two fields above, see slice_of()
     // per-tensor layout only (device tables)
-    float* const* tw;            // [T][P] base pointers, index tensor * P + rank
-    const float* const* tg;
-    float* const* tm;
-    float* const* tpub;
     const TileRef* tile_ref;     // [tiles]
-    const AffineTile* affine_tile;  // [tiles], for the kernels with AFFINE (they read neither the pointer tables nor tile_ref)
-    int num_ranks;               // P: the device tables hold tensor k of all ranks side by side
+    const AffineTile* affine_tile;  // [tiles], for the kernels with AFFINE (they read nothing else)
+    const SlotPointers* slot_ptrs;  // [units][P] of this iteration's schedule row, for the kernels without
+    int64_t mapped_tiles;           // the first so many tiles of the tile table belong to mapped blocks of 64
+    int num_ranks;               // P: places per unit in slot_ptrs
 };
 
 // Element types of the kernel bodies: v4f (one 16-byte column slice) and float
@@ -125,27 +124,15 @@ __device__ __forceinline__ V tree_sum(const V* c)
 
 // Where the lane's element of a rank's row lives.  Flat layout: P rows of ld floats; the row
 // base is wave-uniform and the lane adds its float index inside the row.
+// Every address functor names a member's row twice, by its place in the group (`slot`, counted from
+// the `member` pointer the kernel body was given) and by its rank; each uses what it needs.
 struct FlatAddr {
     const StepParams& p;
     uint32_t lane_at;  // float index inside the row
-    __device__ __forceinline__ float* w(int rank) const { return p.w + (int64_t)rank * p.ld + lane_at; }
-    __device__ __forceinline__ const float* g(int rank) const { return p.g + (int64_t)rank * p.ld + lane_at; }
-    __device__ __forceinline__ float* m(int rank) const { return p.m + (int64_t)rank * p.ld + lane_at; }
-    __device__ __forceinline__ float* pub(int rank) const { return p.pub + (int64_t)rank * p.ld + lane_at; }
-};
-
-// Per-tensor layout: a table of T x P base pointers per array (the P pointers of one tensor side
-// by side: a workgroup works on one tensor and looks up its members' ranks there, a few cache
-// lines that its wavefronts and its neighbours share); the lane adds its float index inside the tensor.
-struct TensorAddr {
-    const StepParams& p;
-    int tensor;
-    uint32_t lane_at;
-    __device__ __forceinline__ int64_t slot(int rank) const { return (int64_t)tensor * p.num_ranks + rank; }
-    __device__ __forceinline__ float* w(int rank) const { return p.tw[slot(rank)] + lane_at; }
-    __device__ __forceinline__ const float* g(int rank) const { return p.tg[slot(rank)] + lane_at; }
-    __device__ __forceinline__ float* m(int rank) const { return p.tm[slot(rank)] + lane_at; }
-    __device__ __forceinline__ float* pub(int rank) const { return p.tpub[slot(rank)] + lane_at; }
+    __device__ __forceinline__ float* w(int, int rank) const { return p.w + (int64_t)rank * p.ld + lane_at; }
+    __device__ __forceinline__ const float* g(int, int rank) const { return p.g + (int64_t)rank * p.ld + lane_at; }
+    __device__ __forceinline__ float* m(int, int rank) const { return p.m + (int64_t)rank * p.ld + lane_at; }
+    __device__ __forceinline__ float* pub(int, int rank) const { return p.pub + (int64_t)rank * p.ld + lane_at; }
 };
 
 // Per-tensor layout with tensors spaced alike in every array: the tile's entry holds the tensor of
@@ -153,34 +140,60 @@ struct TensorAddr {
 struct AffineAddr {
     const AffineTile& t;
     uint32_t lane_at;
-    __device__ __forceinline__ float* w(int rank) const { return t.w + (int64_t)rank * t.stride + lane_at; }
-    __device__ __forceinline__ const float* g(int rank) const { return t.g + (int64_t)rank * t.stride + lane_at; }
-    __device__ __forceinline__ float* m(int rank) const { return t.m + (int64_t)rank * t.stride + lane_at; }
-    __device__ __forceinline__ float* pub(int rank) const { return t.pub + (int64_t)rank * t.stride + lane_at; }
+    __device__ __forceinline__ float* w(int, int rank) const { return t.w + (int64_t)rank * t.stride + lane_at; }
+    __device__ __forceinline__ const float* g(int, int rank) const { return t.g + (int64_t)rank * t.stride + lane_at; }
+    __device__ __forceinline__ float* m(int, int rank) const { return t.m + (int64_t)rank * t.stride + lane_at; }
+    __device__ __forceinline__ float* pub(int, int rank) const { return t.pub + (int64_t)rank * t.stride + lane_at; }
+};
+
+// Per-tensor layout, any placement of the tensors: the plan holds, for every row of the schedule
+// table and every unit (a mapped block; or a tensor, for the tiles outside the blocks), the four
+// pointers of the unit's tensor for the P places of that schedule row, in the order of the row.  A
+// workgroup of a mapped block knows its unit and its first place from its number alone, so these
+// pointers are asked for together with the tile's entry and the ranks: nothing waits for anything
+// but the data.  The table is small enough to stay in the L2 (P x 32 bytes per unit and row).
+struct SlotAddr {
+    const SlotPointers* first;  // of the member that `member[0]` names
+    uint32_t lane_at;
+    __device__ __forceinline__ float* w(int slot, int) const { return first[slot].w + lane_at; }
+    __device__ __forceinline__ const float* g(int slot, int) const { return first[slot].g + lane_at; }
+    __device__ __forceinline__ float* m(int slot, int) const { return first[slot].m + lane_at; }
+    __device__ __forceinline__ float* pub(int slot, int) const { return first[slot].pub + lane_at; }
 };
 
 // What a workgroup of the per-tensor kernels looks up about its tile: the tile table's entry and
-// the way to its tensor's elements, through the pointer tables or (AFFINE) from the entry itself.
+// the way to its tensor's elements, from the entry itself where the tensors are spaced alike
+// (AFFINE), else through the pointers by place.
 template <bool AFFINE>
 struct TileOf;
-template <>
-struct TileOf<false> {
-    TileRef entry;
-    __device__ __forceinline__ TileOf(const StepParams& p, int64_t tile) : entry(p.tile_ref[tile]) {}
-    __device__ __forceinline__ const TileRef& ref() const { return entry; }
-    __device__ __forceinline__ TensorAddr at(const StepParams& p, uint32_t lane_at) const
-    {
-        return TensorAddr{p, entry.tensor, lane_at};
-    }
-};
 template <>
 struct TileOf<true> {
     AffineTile entry;
     __device__ __forceinline__ TileOf(const StepParams& p, int64_t tile) : entry(p.affine_tile[tile]) {}
     __device__ __forceinline__ const TileRef& ref() const { return entry.ref; }
-    __device__ __forceinline__ AffineAddr at(const StepParams&, uint32_t lane_at) const
+    __device__ __forceinline__ AffineAddr at(const StepParams&, const int32_t*, uint32_t lane_at) const
     {
         return AffineAddr{entry, lane_at};
+    }
+};
+template <>
+struct TileOf<false> {
+    TileRef entry;
+    int64_t unit;
+    // (a tile of a mapped block does not wait for its entry to know its unit)
+    __device__ __forceinline__ TileOf(const StepParams& p, int64_t tile) : entry(p.tile_ref[tile])
+    {
+        if (tile < p.mapped_tiles)
+            unit = tile >> 6;
+        else
+            unit = wagma_detail::unit_of_tile(tile, p.mapped_tiles, entry.tensor);
+    }
+    __device__ __forceinline__ const TileRef& ref() const { return entry; }
+    // `member` points into this iteration's row of the schedule table: its distance from the
+    // row's beginning is the place of the kernel body's first member
+    __device__ __forceinline__ SlotAddr at(const StepParams& p, const int32_t* member, uint32_t lane_at) const
+    {
+        return SlotAddr{p.slot_ptrs + unit * p.num_ranks + (member - p.table), lane_at};
     }
 };
 
@@ -204,15 +217,15 @@ __device__ __forceinline__ V rows_update(const StepParams& p, const int32_t* mem
         late[e] = is_late(p, rank[e]);
         busy[e] = LAG && is_busy(p, rank[e]);
         if (!busy[e]) {
-            w_prime[e] = load_v<NT, V>(at.w(rank[e]));
-            gv[e] = load_v<NT, V>(at.g(rank[e]));
-            mv[e] = load_v<NT, V>(at.m(rank[e]));
+            w_prime[e] = load_v<NT, V>(at.w(e, rank[e]));
+            gv[e] = load_v<NT, V>(at.g(e, rank[e]));
+            mv[e] = load_v<NT, V>(at.m(e, rank[e]));
         }
     }
 #pragma unroll
     for (int e = 0; e < S; ++e)
         if (late[e])
-            contrib[e] = load_v<NT, V>(at.pub(rank[e]));  // the send buffer of a late process
+            contrib[e] = load_v<NT, V>(at.pub(e, rank[e]));  // the send buffer of a late process
 
     // (Issuing the loads and stores one array at a time instead of row by row was measured:
     // no difference.)
@@ -222,8 +235,8 @@ __device__ __forceinline__ V rows_update(const StepParams& p, const int32_t* mem
             continue;
         const V m_new = fma_v(p.mu, mv[e], gv[e]);
         w_prime[e] = fma_v(-p.lr, m_new, w_prime[e]);  // W'
-        store_v<NT, V>(at.m(rank[e]), m_new);
-        store_v<NT, V>(at.pub(rank[e]), w_prime[e]);
+        store_v<NT, V>(at.m(e, rank[e]), m_new);
+        store_v<NT, V>(at.pub(e, rank[e]), w_prime[e]);
         if (!late[e])
             contrib[e] = w_prime[e];
     }
@@ -244,7 +257,7 @@ __device__ __forceinline__ void rows_average(const StepParams& p, const int32_t*
             out = (w_sum + w_prime[e]) / p.members_plus_1;
         else
             out = w_sum * p.inv_members;
-        store_v<NT, V>(at.w(rank), out);
+        store_v<NT, V>(at.w(e, rank), out);
     }
 }
 
@@ -262,15 +275,15 @@ __device__ __forceinline__ void registers_body(const StepParams& p, const int32_
         late[e] = is_late(p, rank[e]);
         busy[e] = LAG && is_busy(p, rank[e]);
         if (!busy[e]) {
-            wv[e] = load_v<NT, V>(at.w(rank[e]));
-            gv[e] = load_v<NT, V>(at.g(rank[e]));
-            mv[e] = load_v<NT, V>(at.m(rank[e]));
+            wv[e] = load_v<NT, V>(at.w(e, rank[e]));
+            gv[e] = load_v<NT, V>(at.g(e, rank[e]));
+            mv[e] = load_v<NT, V>(at.m(e, rank[e]));
         }
     }
 #pragma unroll
     for (int e = 0; e < S; ++e)
         if (late[e])
-            contrib[e] = load_v<NT, V>(at.pub(rank[e]));  // the send buffer of a late process
+            contrib[e] = load_v<NT, V>(at.pub(e, rank[e]));  // the send buffer of a late process
 
     // (Issuing the loads and stores one array at a time instead of row by row was measured:
     // no difference.)
@@ -280,8 +293,8 @@ __device__ __forceinline__ void registers_body(const StepParams& p, const int32_
             continue;
         const V m_new = fma_v(p.mu, mv[e], gv[e]);
         wv[e] = fma_v(-p.lr, m_new, wv[e]);  // W'
-        store_v<NT, V>(at.m(rank[e]), m_new);
-        store_v<NT, V>(at.pub(rank[e]), wv[e]);
+        store_v<NT, V>(at.m(e, rank[e]), m_new);
+        store_v<NT, V>(at.pub(e, rank[e]), wv[e]);
         if (!late[e])
             contrib[e] = wv[e];
     }
@@ -295,7 +308,7 @@ __device__ __forceinline__ void registers_body(const StepParams& p, const int32_
             out = (w_sum + wv[e]) / p.members_plus_1;
         else
             out = w_sum * p.inv_members;
-        store_v<NT, V>(at.w(rank[e]), out);
+        store_v<NT, V>(at.w(e, rank[e]), out);
     }
 }
 
@@ -318,9 +331,9 @@ __device__ __forceinline__ void streamed_body(const StepParams& p, const int32_t
             late[i] = is_late(p, rank[i]);
             busy[i] = LAG && is_busy(p, rank[i]);
             if (!busy[i]) {
-                wv[i] = load_v<NT, V>(at.w(rank[i]));
-                gv[i] = load_v<NT, V>(at.g(rank[i]));
-                mv[i] = load_v<NT, V>(at.m(rank[i]));
+                wv[i] = load_v<NT, V>(at.w(c * kChunk + i, rank[i]));
+                gv[i] = load_v<NT, V>(at.g(c * kChunk + i, rank[i]));
+                mv[i] = load_v<NT, V>(at.m(c * kChunk + i, rank[i]));
             }
         }
 #pragma unroll
@@ -330,7 +343,7 @@ __device__ __forceinline__ void streamed_body(const StepParams& p, const int32_t
                 // second pass.  After a non-temporal load the L2 lets go of it early and that
                 // last read goes out to memory again (measured: the late rows then cost twice
                 // their bytes, and 6 % of the time in the per-tensor layout).
-                contrib[i] = load_v<false, V>(at.pub(rank[i]));
+                contrib[i] = load_v<false, V>(at.pub(c * kChunk + i, rank[i]));
             }
 #pragma unroll
         for (int i = 0; i < kChunk; ++i) {
@@ -338,12 +351,12 @@ __device__ __forceinline__ void streamed_body(const StepParams& p, const int32_t
                 continue;
             const V m_new = fma_v(p.mu, mv[i], gv[i]);
             wv[i] = fma_v(-p.lr, m_new, wv[i]);
-            store_v<NT, V>(at.m(rank[i]), m_new);
+            store_v<NT, V>(at.m(c * kChunk + i, rank[i]), m_new);
             if (late[i]) {
                 // read again below: an ordinary store, so that the line may stay in the L2
-                store_v<false, V>(at.pub(rank[i]), wv[i]);
+                store_v<false, V>(at.pub(c * kChunk + i, rank[i]), wv[i]);
             } else {
-                store_v<NT, V>(at.pub(rank[i]), wv[i]);
+                store_v<NT, V>(at.pub(c * kChunk + i, rank[i]), wv[i]);
                 contrib[i] = wv[i];
             }
         }
@@ -383,7 +396,7 @@ __device__ __forceinline__ void streamed_body(const StepParams& p, const int32_t
             busy[i] = LAG && is_busy(p, rank[i]);
             late[i] = !busy[i] && is_late(p, rank[i]);
             if (late[i])
-                w_prime[i] = load_v<false, V>(at.pub(rank[i]));
+                w_prime[i] = load_v<false, V>(at.pub(c * kChunk + i, rank[i]));
         }
 #pragma unroll
         for (int i = 0; i < kChunk; ++i) {
@@ -392,7 +405,7 @@ __device__ __forceinline__ void streamed_body(const StepParams& p, const int32_t
             V out = fresh;
             if (late[i])
                 out = (w_sum + w_prime[i]) / p.members_plus_1;
-            store_v<NT, V>(at.w(rank[i]), out);
+            store_v<NT, V>(at.w(c * kChunk + i, rank[i]), out);
         }
     }
 }
@@ -502,7 +515,7 @@ __global__ void __launch_bounds__(kBlock, 2) step_tensors_in_registers(const Ste
     if (first >= size)
         return;
     const int32_t* member = p.table + group * S;
-    auto at = tile.at(p, (uint32_t)first);
+    auto at = tile.at(p, member, (uint32_t)first);
     if (first + 4 <= size) {
         registers_body<S, NT, LAG, v4f>(p, member, at);
     } else {
@@ -524,7 +537,7 @@ __global__ void __launch_bounds__(kBlock, 2) step_tensors_streamed(const StepPar
     if (first >= size)
         return;
     const int32_t* member = p.table + group * p.members;
-    auto at = tile.at(p, (uint32_t)first);
+    auto at = tile.at(p, member, (uint32_t)first);
     if (first + 4 <= size) {
         streamed_body<NT, LAG, v4f>(p, member, at);
     } else {
@@ -566,7 +579,7 @@ __global__ void __launch_bounds__(64 * OCTETS, OCTETS <= 4 ? 2 : 1) step_tensors
     const bool cut = !whole && first < size;   // at most one lane, and only in the tensor's last quarter
     const int32_t* member = p.table + group * p.members + octet * 8;
     {
-        const auto at = tile.at(p, (uint32_t)first);
+        const auto at = tile.at(p, member, (uint32_t)first);
         v4f w_prime[8];
         v4f mine = {0.f, 0.f, 0.f, 0.f};
         if (whole)
@@ -587,7 +600,7 @@ __global__ void __launch_bounds__(64 * OCTETS, OCTETS <= 4 ? 2 : 1) step_tensors
                            ? (int)(size % 4)
                            : 0;
     for (int k = 0; k < rounds; ++k) {
-        const auto at = tile.at(p, (uint32_t)(first + k));
+        const auto at = tile.at(p, member, (uint32_t)(first + k));
         float w_prime[8];
         float mine = 0.f;
         if (cut)

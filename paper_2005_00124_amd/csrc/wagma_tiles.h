@@ -38,6 +38,24 @@ struct AffineTile {
 };
 static_assert(sizeof(AffineTile) == 64, "one entry is one 64-byte line");
 
+// For plans whose tensors lie anywhere: the four pointers of one tensor of one process.  The plan
+// holds them by unit and by place: a unit is a mapped block (64 tiles of one tensor), or a tensor
+// (for its tiles outside the blocks); a place is a position in a row of the schedule table.
+struct SlotPointers {
+    float* w;
+    const float* g;
+    float* m;
+    float* pub;
+};
+static_assert(sizeof(SlotPointers) == 32, "four pointers");
+
+// The tile table begins with mapped_tiles tiles that belong to blocks of 64: such a tile knows its
+// unit from its number alone, the others from the tensor their entry names.
+WAGMA_SHAPES_FN int64_t unit_of_tile(int64_t tile, int64_t mapped_tiles, int tensor)
+{
+    return tile < mapped_tiles ? tile >> 6 : (mapped_tiles >> 6) + tensor;
+}
+
 // The 16-byte slice, inside its tensor, that lane `lane` of wavefront (or quarter) `wave` of a tile
 // takes.
 WAGMA_SHAPES_FN int64_t tensor_slice(uint64_t map, const TileRef& ref, int64_t wave, int64_t lane)
@@ -149,6 +167,29 @@ inline bool spaced_alike(int P, int T, const void* const* const arrays[4], std::
         step_bytes[(size_t)k] = (int64_t)step;
     }
     return true;
+}
+
+// The pointers by place: out[(row * units + unit) * P + place] holds the four pointers of the
+// unit's tensor for the process that stands at `place` in row `row` of the schedule table
+// (`schedule`: rows x P ranks).  Returns the number of units: the mapped blocks, then the T tensors.
+inline int64_t build_slot_pointers(int P, int T, int rows, const int32_t* schedule, const std::vector<TileRef>& refs,
+                                   int64_t mapped_tiles, const void* const* const arrays[4],
+                                   std::vector<SlotPointers>& out)
+{
+    const int64_t blocks = mapped_tiles >> 6;
+    const int64_t units = blocks + T;
+    out.resize((size_t)rows * (size_t)units * (size_t)P);
+    for (int row = 0; row < rows; ++row)
+        for (int64_t unit = 0; unit < units; ++unit) {
+            const size_t k = unit < blocks ? (size_t)refs[(size_t)unit * 64].tensor : (size_t)(unit - blocks);
+            SlotPointers* to = out.data() + ((size_t)row * (size_t)units + (size_t)unit) * (size_t)P;
+            for (int place = 0; place < P; ++place) {
+                const size_t i = (size_t)schedule[(size_t)row * P + place] * (size_t)T + k;
+                to[place] = SlotPointers{(float*)arrays[0][i], (const float*)arrays[1][i], (float*)arrays[2][i],
+                                         (float*)arrays[3][i]};
+            }
+        }
+    return units;
 }
 
 }  // namespace wagma_detail

@@ -139,17 +139,19 @@ def test_training_run_with_back_to_back_steps(P, S, n, tau, iters):
         say("  busy process-iterations %d, late %d of %d" % (seen_busy, seen_late, P * iters))
 
 
-@pytest.mark.parametrize("stacked", [False, True])
+@pytest.mark.parametrize("where", ["separate", "stacked", "stacked, by place"])
 @pytest.mark.parametrize("P,S", [(4, 2), (16, 8), (32, 16), (32, 32)])
-def test_step_tensors_lag(P, S, stacked):
+def test_step_tensors_lag(P, S, where):
     """Per-tensor layout: ragged tensors between sentinels (one with a whole 256 KiB block, which the
     plan deals out by the launch shape's map), late and busy processes.  stacked: the P replicas of
-    a tensor lie equally far apart in one allocation (the plan then needs no pointer tables), else
-    every tensor of every process is an allocation of its own."""
+    a tensor lie equally far apart in one allocation (the tile's entry names the tensor's place);
+    separate: every tensor of every process is an allocation of its own (pointers laid out by
+    place); stacked, by place: the first layout with the plan told to treat it like the second."""
+    stacked = where.startswith("stacked")
     sizes = [1, 7, 64, 1030, 5, 4096, 333, 65536 + 4 * 70 + 3]
     n = sum(sizes)
     tau = 4
-    say("lag tensors P=%d S=%d stacked=%s" % (P, S, stacked))
+    say("lag tensors P=%d S=%d %s" % (P, S, where))
     rng = np.random.default_rng(P + S)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(3 + P)
@@ -177,6 +179,8 @@ def test_step_tensors_lag(P, S, stacked):
 
     ow, og, om, opub = (flat(k).copy() for k in ("w", "g", "m", "pub"))
     with lw.Wagma(P, S, n, tau) as ctx:
+        if where == "stacked, by place":
+            ctx.debug_set_option(lw.WAGMA_DEBUG_TENSOR_TABLES, 1)
         plan = ctx.tensor_plan(views["w"], views["g"], views["m"], views["pub"])
         try:
             for t in range(6):

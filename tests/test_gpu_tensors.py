@@ -108,7 +108,7 @@ RAGGED = [1, 2, 3, 4, 5, 7, 64, 255, 257, 1000, 1023, 1025, 4099, 70001]
 @pytest.mark.parametrize("P,S", [(1, 1), (2, 2), (4, 2), (8, 4), (16, 4), (64, 8), (32, 16), (64, 64), (128, 32)])
 def test_tensors_bit_exact(P, S, layout):
     sizes = RAGGED if P <= 16 else RAGGED[:-1]
-    run_tensor_case(P, S, sizes, tau=3, iters=5, q=0.3, seed=100 + P + S, layout=layout)
+    run_tensor_case(P, S, sizes, tau=3, iters=8, q=0.3, seed=100 + P + S, layout=layout)
 
 
 def test_tensors_variants():
@@ -150,16 +150,16 @@ def test_tensors_back_to_back_taken_one_by_one():
                     layout="packed", options=((lw.WAGMA_DEBUG_TENSOR_TABLES, 1),))
 
 
-def test_tensors_spaced_alike_through_the_pointer_tables():
-    """Views into rows again, with the plan told to look its tensors up in the pointer tables as it
-    does for tensors that are not spaced alike."""
-    for P, S in ((32, 8), (16, 16), (32, 32)):
-        run_tensor_case(P, S, [70001, 65536 + 8, 3, 1000], tau=3, iters=3, q=0.3, seed=600 + P + S, layout="arena",
+def test_tensors_spaced_alike_found_by_place():
+    """Views into rows again, with the plan told to find its tensors as it does when they are not
+    spaced alike: through the pointers laid out by the places of the schedule table's rows."""
+    for P, S in ((32, 8), (16, 16), (32, 32), (128, 32)):
+        run_tensor_case(P, S, [70001, 65536 + 8, 3, 1000], tau=3, iters=8, q=0.3, seed=600 + P + S, layout="arena",
                         options=((lw.WAGMA_DEBUG_TENSOR_TABLES, 1),))
 
 
 def test_tensors_spaced_alike_but_not_in_every_array():
-    """The replicas of a tensor equally far apart in w, m and pub and not in g: the pointer tables."""
+    """The replicas of a tensor equally far apart in w, m and pub and not in g: pointers by place."""
     P, S, sizes = 8, 4, [1000, 70001, 3]
     n = sum(sizes)
     gen = torch.Generator(device="cuda")

@@ -160,9 +160,47 @@ static void check_joining()
     }
 }
 
+// The pointers by place must name, for every row of a schedule, every tile and every place, the
+// tensor of the tile's entry in the process that stands at that place.
+static void check_by_place()
+{
+    const int P = 8, rows = 3;
+    const std::vector<int64_t> sizes = {65536 + 40, 3, 2 * 65536, 5000, 70001};
+    const int T = (int)sizes.size();
+    std::vector<int64_t> offset(sizes.size());
+    for (size_t k = 0; k < sizes.size(); ++k)
+        offset[k] = 0x1000000 * (int64_t)k;
+    Pointers p(P, offset, 0x100000);
+    // three rows of a schedule: the identity, its reverse, and a shuffle
+    std::vector<int32_t> schedule;
+    for (int r = 0; r < P; ++r) schedule.push_back(r);
+    for (int r = 0; r < P; ++r) schedule.push_back(P - 1 - r);
+    for (int r = 0; r < P; ++r) schedule.push_back((r * 3 + 5) % P);
+    for (uint64_t map : {uint64_t(0), kLaunchShapes[kForeignShape].map}) {
+        std::vector<TileRef> refs;
+        const int64_t mapped = build_tile_table(T, sizes.data(), nullptr, map, 3, refs);
+        std::vector<SlotPointers> by_place;
+        const int64_t units = build_slot_pointers(P, T, rows, schedule.data(), refs, mapped, p.arrays, by_place);
+        bool ok = units == mapped / 64 + T && (int64_t)by_place.size() == rows * units * P;
+        for (int row = 0; row < rows && ok; ++row)
+            for (int64_t tile = 0; tile < (int64_t)refs.size() && ok; ++tile) {
+                const int64_t unit = unit_of_tile(tile, mapped, refs[(size_t)tile].tensor);
+                ok = unit >= 0 && unit < units;
+                for (int place = 0; place < P && ok; ++place) {
+                    const SlotPointers& have = by_place[(size_t)((row * units + unit) * P + place)];
+                    const size_t i = (size_t)schedule[(size_t)row * P + place] * T + (size_t)refs[(size_t)tile].tensor;
+                    ok = have.w == p.arrays[0][i] && have.g == p.arrays[1][i] && have.m == p.arrays[2][i] &&
+                         have.pub == p.arrays[3][i];
+                }
+            }
+        expect(ok, map ? "pointers by place, with mapped blocks" : "pointers by place, contiguous tiles only");
+    }
+}
+
 int main()
 {
     check_joining();
+    check_by_place();
     const uint64_t maps[] = {0, kLaunchShapes[kForeignShape].map, 0x9876543210ull, 0x0123456789ull, 0x5329618470ull};
     const std::vector<std::vector<int64_t>> lists = {
         {1},
