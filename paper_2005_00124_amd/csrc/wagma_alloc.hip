@@ -326,8 +326,8 @@ void release(ArraySet& set)
     set = ArraySet();
 }
 
-// arrays built chunk by chunk from all three regions (wagma_chunks.h)
-bool place_chunks(int device, size_t bytes, bool debug, ArraySet& out)
+// arrays built chunk by chunk (wagma_chunks.h): from all three regions in turn, or all from one
+bool place_chunks(int device, size_t bytes, bool debug, bool one_region, ArraySet& out)
 {
     const int per_array = (int)((bytes + wagma_placement::kChunkBytes - 1) / wagma_placement::kChunkBytes);
     if (4 * per_array > wagma_placement::kMaxChunks)
@@ -337,7 +337,7 @@ bool place_chunks(int device, size_t bytes, bool debug, ArraySet& out)
     VmmArrays* arrays = nullptr;
     if (memory && index && memory->init(device)) {
         memory->reserve = size_t(2) << 30;
-        auto* search = new (std::nothrow) wagma_placement::ChunkSearch<VmmMemory>(*memory, per_array);
+        auto* search = new (std::nothrow) wagma_placement::ChunkSearch<VmmMemory>(*memory, per_array, one_region);
         wagma_placement::ChunkPlan plan;
         plan.w = index;
         plan.g = index + per_array;
@@ -345,16 +345,16 @@ bool place_chunks(int device, size_t bytes, bool debug, ArraySet& out)
         plan.pub = index + 3 * per_array;
         if (search && search->run(plan)) {
             if (debug) {
-                std::fprintf(stderr, "wagma placement (chunks): %d examined, %d classes, %d of %d in pattern, "
-                                     "slow %.0f fast %.0f GB/s\n  classes:", plan.examined, plan.classes,
-                             plan.in_pattern, 4 * per_array, plan.slow_gbs, plan.fast_gbs);
+                std::fprintf(stderr, "wagma placement (chunks, %s): %d examined, %d classes, %d of %d in pattern, "
+                                     "slow %.0f fast %.0f GB/s\n  classes:", one_region ? "one region" : "three regions",
+                             plan.examined, plan.classes, plan.in_pattern, 4 * per_array, plan.slow_gbs, plan.fast_gbs);
                 for (int i = 0; i < search->chunks(); ++i)
                     std::fprintf(stderr, " %d", search->chunk_class(i));
                 std::fprintf(stderr, "\n");
             }
             arrays = memory->build(plan);
             out.examined = plan.examined;
-            out.regions = plan.classes < 3 ? (plan.classes < 1 ? 1 : plan.classes) : 3;
+            out.regions = one_region ? 1 : plan.classes < 3 ? (plan.classes < 1 ? 1 : plan.classes) : 3;
             out.g_with_w = 1;
             out.slow_gbs = plan.slow_gbs;
             out.fast_gbs = plan.fast_gbs;
@@ -620,18 +620,25 @@ int wagma_alloc_buffers(wagma_ctx* ctx, float** w, float** g, float** m, float**
 
     // With WAGMA_PLACE_AUTO: four ordinary allocations first, while the memory is as the caller
     // left it (on a GPU with untouched memory they lie in one HBM region, which the kernel that
-    // holds a group in registers likes best), then the timed search, then the arrays built from
-    // chunks (placement by whole arrays is left out: the timed search covers what it finds).  Each
-    // is judged with the step kernels themselves and must be 1 % faster than what is kept to
-    // replace it; at most two sets of arrays exist at a time.  A fixed mode takes that mode if it
-    // can be had, else ordinary allocations.
+    // holds a group in registers likes best); then arrays built from chunks of one region (what
+    // brings that back on a GPU whose memory has been in use: 0.80 -> 0.81 of peak on the
+    // headline workload); then arrays built from chunks of all three regions in turn (which the
+    // kernel for larger groups likes best), then the timed search (placement by whole arrays is
+    // left out: the timed search covers what it finds).  Each is judged with the step kernels
+    // themselves and must be 1 % faster than what is kept to replace it; at most two sets of
+    // arrays exist at a time.  WAGMA_PLACE_CHUNKS compares the two chunk patterns in the same
+    // manner; another fixed mode takes that mode if it can be had.  Ordinary allocations are what
+    // remains when nothing else could be had.
+    constexpr int kChunksOneRegion = 100;  // a candidate, not a mode: reported as WAGMA_PLACE_CHUNKS, one region
     const int mode = bytes >= wagma_placement::kPlacementMinBytes ? ctx->opt_placement : WAGMA_PLACE_PLAIN;
-    const int auto_order[3] = {WAGMA_PLACE_PLAIN, WAGMA_PLACE_SEARCH, WAGMA_PLACE_CHUNKS};
-    const int fixed_order[3] = {mode, WAGMA_PLACE_PLAIN, -1};
+    const int auto_order[4] = {WAGMA_PLACE_PLAIN, kChunksOneRegion, WAGMA_PLACE_CHUNKS, WAGMA_PLACE_SEARCH};
+    const int chunks_order[4] = {kChunksOneRegion, WAGMA_PLACE_CHUNKS, WAGMA_PLACE_PLAIN, -1};
+    const int fixed_order[4] = {mode, WAGMA_PLACE_PLAIN, -1, -1};
+    const bool compare = mode == WAGMA_PLACE_AUTO || mode == WAGMA_PLACE_CHUNKS;
     ArraySet best;
-    for (int candidate : (mode == WAGMA_PLACE_AUTO ? auto_order : fixed_order)) {
-        if (candidate < 0 || (mode != WAGMA_PLACE_AUTO && best.ptr[0]))
-            break;  // a fixed mode: the first placement that worked
+    for (int candidate : (mode == WAGMA_PLACE_AUTO ? auto_order : mode == WAGMA_PLACE_CHUNKS ? chunks_order : fixed_order)) {
+        if (candidate < 0 || (best.ptr[0] && (!compare || (mode == WAGMA_PLACE_CHUNKS && candidate == WAGMA_PLACE_PLAIN))))
+            break;  // a fixed mode: the first placement that worked; ordinary allocations only if none did
         size_t free_b = 0, total_b = 0;
         if (best.ptr[0] && (hipMemGetInfo(&free_b, &total_b) != hipSuccess || free_b < 4 * bytes + (size_t(4) << 30)))
             break;  // no room for a second set to compare with
@@ -639,8 +646,8 @@ int wagma_alloc_buffers(wagma_ctx* ctx, float** w, float** g, float** m, float**
         bool ok = false;
         if (candidate == WAGMA_PLACE_SEARCH)
             ok = place_search(ctx, bytes, debug, trial);
-        else if (candidate == WAGMA_PLACE_CHUNKS)
-            ok = place_chunks(device, bytes, debug, trial);
+        else if (candidate == WAGMA_PLACE_CHUNKS || candidate == kChunksOneRegion)
+            ok = place_chunks(device, bytes, debug, candidate == kChunksOneRegion, trial);
         else if (candidate == WAGMA_PLACE_ARRAYS)
             ok = place_arrays(bytes, debug, trial);
         else
@@ -649,7 +656,7 @@ int wagma_alloc_buffers(wagma_ctx* ctx, float** w, float** g, float** m, float**
             (void)hipGetLastError();
             continue;
         }
-        if (mode == WAGMA_PLACE_AUTO)
+        if (compare)
             trial.step_ms = time_placement(ctx, trial);
         if (debug)
             std::fprintf(stderr, "wagma placement: mode %d regions %d: %.3f ms per iteration\n", trial.mode,

@@ -105,7 +105,11 @@ struct ChunkPlan {
 template <typename Memory>
 class ChunkSearch {
 public:
-    ChunkSearch(Memory& memory, int chunks_per_array) : mem_(memory), k_(chunks_per_array) {}
+    // one_region: all chunks of all four arrays from one region instead of the pattern above
+    ChunkSearch(Memory& memory, int chunks_per_array, bool one_region = false)
+        : mem_(memory), k_(chunks_per_array), one_region_(one_region)
+    {
+    }
 
     // Fills plan.w/g/m/pub (arrays of chunks_per_array ints owned by the caller).  Returns
     // false if fewer than 4 * chunks_per_array chunks could be had at all.
@@ -113,16 +117,16 @@ public:
     {
         int need[3] = {0, 0, 0};
         for (int j = 0; j < k_; ++j) {
-            need[j % 3] += 2;        // w and g
-            need[(j + 1) % 3] += 1;  // m
-            need[(j + 2) % 3] += 1;  // pub
+            need[slot(j, 0)] += 2;  // w and g
+            need[slot(j, 1)] += 1;  // m
+            need[slot(j, 2)] += 1;  // pub
         }
         const size_t side = kChunkBytes / 2;
         while (n_ < kMaxChunks && !failed_ && !clusters_.full()) {
             // the three regions with the most chunks so far are the ones that will be used
             int top[3];
             top_classes(top);
-            bool enough = n_classes_ >= 3;
+            bool enough = n_classes_ >= (one_region_ ? 1 : 3);
             for (int r = 0; r < 3 && enough; ++r)
                 enough = count_[top[r]] >= need_sorted(need, r);
             if (enough)
@@ -188,7 +192,7 @@ public:
                         arrays[a][j] = -1;
                     if (arrays[a][j] >= 0)
                         continue;
-                    const int want = class_of_slot[(j + shift[a]) % 3];
+                    const int want = class_of_slot[slot(j, shift[a])];
                     const int got = take(pass == 0 ? want : -2);
                     arrays[a][j] = got;
                     if (pass == 0 && got >= 0)
@@ -205,6 +209,8 @@ public:
     bool chunk_used(int i) const { return used_[i]; }
 
 private:
+    // which of the three region slots of the pattern chunk j of an array with this shift asks for
+    int slot(int j, int shift) const { return one_region_ ? 0 : (j + shift) % 3; }
     static int need_sorted(const int need[3], int rank)
     {
         int s[3] = {need[0], need[1], need[2]};
@@ -293,6 +299,7 @@ private:
 
     Memory& mem_;
     int k_;
+    bool one_region_;
     RateClusters clusters_;
     char* chunk_[kMaxChunks];
     int class_[kMaxChunks];

@@ -131,10 +131,93 @@ void run(const char* name, SimMemory& mem, int k, bool expect_plan, int min_in_p
     delete search;
 }
 
+// The other pattern: all chunks of all four arrays from one region.
+void run_one_region(const char* name, SimMemory& mem, int k, bool expect_plan, int min_same_percent)
+{
+    std::vector<int> w(k), g(k), m(k), pub(k);
+    wagma_placement::ChunkPlan plan;
+    plan.w = w.data();
+    plan.g = g.data();
+    plan.m = m.data();
+    plan.pub = pub.data();
+    auto* search = new wagma_placement::ChunkSearch<SimMemory>(mem, k, true);
+    const bool ok = search->run(plan);
+    std::printf("%-44s plan %d  examined %3d  classes %d  in pattern %3d/%3d  probes %4ld  skipped %3.0f GiB\n", name,
+                (int)ok, plan.examined, plan.classes, plan.in_pattern, 4 * k, mem.probes, mem.skipped_gib);
+    check(ok == expect_plan, name, "plan / no plan");
+    if (ok) {
+        std::set<int> seen;
+        int in_region[8] = {0, 0, 0, 0, 0, 0, 0, 0}, mixed = 0;
+        for (int j = 0; j < k; ++j)
+            for (int idx : {w[j], g[j], m[j], pub[j]}) {
+                check(idx >= 0 && idx < plan.examined, name, "a slot without a chunk");
+                check(seen.insert(idx).second, name, "a chunk used twice");
+                if (idx >= 0) {
+                    ++in_region[mem.region_of_chunk(idx) & 7];
+                    mixed += (int)mem.mixed.count(idx);
+                }
+            }
+        int most = 0;
+        for (int c : in_region)
+            most = c > most ? c : most;
+        check(100 * (most - mixed) >= min_same_percent * 4 * k, name, "too few chunks from one region");
+    }
+    delete search;
+}
+
 }  // namespace
 
 int main()
 {
+    {
+        const std::vector<double> three = {0.0, 96.0, 192.0, 288.0};
+        for (int k : {2, 7, 20}) {
+            SimMemory mem;
+            mem.boundaries_gib = three;
+            char name[64];
+            std::snprintf(name, sizeof name, "one region: fresh memory, %d chunks per array", k);
+            run_one_region(name, mem, k, true, 100);
+        }
+        for (int seed = 1; seed <= 6; ++seed) {
+            SimMemory mem;
+            mem.boundaries_gib = three;
+            mem.noise = 0.04;
+            mem.straggler_every = 12.0;
+            mem.rng ^= (uint64_t)seed * 0x9E3779B97F4A7C15ull;
+            for (int i = 0; i < 200; ++i)
+                mem.scattered_gib.push_back((double)((i * (31 + 2 * seed)) % 280));
+            char name[64];
+            std::snprintf(name, sizeof name, "one region: scattered, noise, seed %d", seed);
+            run_one_region(name, mem, 7, true, 90);
+        }
+        {
+            SimMemory mem;
+            mem.boundaries_gib = three;
+            for (int i = 0; i < 160; ++i)
+                mem.scattered_gib.push_back((double)((i * 37) % 280));
+            mem.mixed = {0, 3, 4, 11, 30};
+            run_one_region("one region: scattered, some chunks mixed", mem, 7, true, 100);
+        }
+        {
+            SimMemory mem;
+            mem.boundaries_gib = {0.0, 288.0};
+            mem.straggler_every = 10.0;
+            run_one_region("one region: one region only", mem, 7, true, 100);
+        }
+        {
+            SimMemory mem;
+            mem.boundaries_gib = three;
+            mem.capacity_gib = 20.0;
+            run_one_region("one region: memory for 20 chunks, 28 needed", mem, 7, false, 0);
+        }
+        {
+            // a region too small to give all the chunks: the plan is filled up from the others
+            SimMemory mem;
+            mem.boundaries_gib = {0.0, 20.0, 40.0, 60.0};
+            mem.capacity_gib = 60.0;
+            run_one_region("one region: three regions of 20 chunks, 28 needed", mem, 7, true, 60);
+        }
+    }
     const std::vector<double> three = {0.0, 96.0, 192.0, 288.0};
     for (int k : {2, 7, 15, 26}) {
         SimMemory mem;
