@@ -29,6 +29,7 @@ namespace wagma_placement {
 constexpr size_t kChunkBytes = size_t(1) << 30;
 constexpr int kMaxChunks = 768;    // chunks examined at most
 constexpr int kMaxClasses = 6;     // regions told apart at most (three are used)
+constexpr int kRegionChunks = 88;  // chunks one region gives for certain (it holds about 96 GiB)
 constexpr size_t kSkipBytes = size_t(8) << 30;
 constexpr double kChunkMinSpread = 1.10;  // class means closer than this: only one cluster seen
 constexpr int kChunkWarmupProbes = 40;
@@ -129,6 +130,10 @@ public:
             bool enough = n_classes_ >= (one_region_ ? 1 : 3);
             for (int r = 0; r < 3 && enough; ++r)
                 enough = count_[top[r]] >= need_sorted(need, r);
+            // arrays that no single region can hold: once a region has given what a region has,
+            // the rest comes from the others
+            if (one_region_ && n_classes_ >= 1 && 4 * k_ > kRegionChunks)
+                enough = count_[top[0]] >= kRegionChunks && n_ >= 4 * k_;
             if (enough)
                 break;
             char* c = mem_.new_chunk();
@@ -193,7 +198,16 @@ public:
                     if (arrays[a][j] >= 0)
                         continue;
                     const int want = class_of_slot[slot(j, shift[a])];
-                    const int got = take(pass == 0 ? want : -2);
+                    int got = -1;
+                    if (pass == 0)
+                        got = take(want);
+                    // what the one region cannot give comes from the next largest, as few
+                    // regions as possible (ordinary allocations in untouched memory look like that)
+                    for (int r = 1; r < 3 && pass == 1 && one_region_ && got < 0; ++r)
+                        if (r < n_classes_)
+                            got = take(top[r]);
+                    if (pass == 1 && got < 0)
+                        got = take(-2);
                     arrays[a][j] = got;
                     if (pass == 0 && got >= 0)
                         ++plan.in_pattern;

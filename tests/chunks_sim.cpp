@@ -157,10 +157,19 @@ void run_one_region(const char* name, SimMemory& mem, int k, bool expect_plan, i
                     mixed += (int)mem.mixed.count(idx);
                 }
             }
-        int most = 0;
-        for (int c : in_region)
-            most = c > most ? c : most;
+        int most = 0, second = 0;
+        for (int c : in_region) {
+            if (c > most) {
+                second = most;
+                most = c;
+            } else if (c > second) {
+                second = c;
+            }
+        }
         check(100 * (most - mixed) >= min_same_percent * 4 * k, name, "too few chunks from one region");
+        // what the one region could not give comes from one other region, if that one has enough
+        if (min_same_percent < 100 && mem.noise < 0.035)
+            check(most + second == 4 * k, name, "the rest is spread over more than one other region");
     }
     delete search;
 }
@@ -209,6 +218,15 @@ int main()
             mem.boundaries_gib = three;
             mem.capacity_gib = 20.0;
             run_one_region("one region: memory for 20 chunks, 28 needed", mem, 7, false, 0);
+        }
+        {
+            // arrays larger than a region (workload 5: 27 chunks per array): the search ends once a
+            // region has given what a region has, the rest comes from one other region
+            SimMemory mem;
+            mem.boundaries_gib = three;
+            for (int i = 0; i < 280; ++i)
+                mem.scattered_gib.push_back((double)((i * 37) % 280));
+            run_one_region("one region: 108 chunks needed, regions of 96", mem, 27, true, 80);
         }
         {
             // a region too small to give all the chunks: the plan is filled up from the others
