@@ -11,6 +11,10 @@
 // and g lies with w, whatever the size of the arrays, and every region carries a third of
 // the load.  This also works where whole arrays cannot be had cleanly: arrays of tens of
 // GiB, or a GPU whose free memory is scattered over the regions.
+// A second pattern takes every chunk of every array from ONE region (the class with the most
+// chunks; arrays larger than a region go on with the next largest): what ordinary allocations
+// look like on a GPU with untouched memory, rebuilt where the memory has been in use.  Which of
+// the two the step runs faster on depends on its kernel (wagma_alloc_buffers times both).
 //
 // A Memory object provides
 //   char*  new_chunk()                   maps one more physical chunk, nullptr when out of room
