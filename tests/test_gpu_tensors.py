@@ -208,20 +208,25 @@ def test_plan_validation():
             plan.destroy()
 
 
-def test_tensor_views_of_workload_2_equal_the_flat_path():
-    """ResNet-50-shaped tensor list (161 tensors) as views into flat rows: the per-tensor entry
-    point and the flat entry point give the same bits on the whole model, and both match the
-    oracle on a column sample."""
+@pytest.mark.parametrize("where", ["views", "views, as given", "stacked"])
+def test_tensors_of_workload_2_equal_the_flat_path(where):
+    """ResNet-50-shaped tensor list (161 tensors): the per-tensor entry point and the flat entry
+    point give the same bits on the whole model, and both match the oracle on a column sample.
+    views: the tensors are views into flat rows, back to back (the plan joins them into one);
+    views, as given: the same with the plan told to keep the 161 tensors and to find them through
+    the pointers by place; stacked: every parameter in a [P, size] allocation of its own (161 tile
+    entries name their tensor's place)."""
     wl = wk.workload(2)
     P, S, n = wl.P, wl.S, wl.n
     tensors = wl.tensors()
     sizes = [int(np.prod(t[1])) for t in tensors]
     assert len(sizes) == 161 and sum(sizes) == n
-    say("workload 2 per-tensor vs flat:", wl.name)
+    say("workload 2 per-tensor (%s) vs flat:" % where, wl.name)
     with lw.Wagma(P, S, n, wl.tau) as ctx:
+        if where == "views, as given":
+            ctx.debug_set_option(lw.WAGMA_DEBUG_TENSOR_TABLES, 1)
         flat = ctx.alloc()
         wk.fill_initial_state(wl, flat[0], flat[2], flat[3])
-        twin = [x.clone() for x in flat]
 
         def views(buf):
             out = []
@@ -232,19 +237,43 @@ def test_tensor_views_of_workload_2_equal_the_flat_path():
                     at += s
                 out.append(row)
             return out
+
+        if where == "stacked":
+            stacks = [[torch.empty((P, s + (-s) % 4), device="cuda") for s in sizes] for _ in range(4)]
+            lists = [[[st[p, :s] for st, s in zip(per_array, sizes)] for p in range(P)] for per_array in stacks]
+
+            def put(a):          # flat array a -> the tensors of array a
+                at = 0
+                for st, s in zip(stacks[a], sizes):
+                    st[:, :s].copy_(flat[a][:, at:at + s])
+                    at += s
+
+            def get(a):          # the tensors of array a as a (P, n) matrix
+                return torch.cat([st[:, :s] for st, s in zip(stacks[a], sizes)], dim=1)
+            for a in (0, 2, 3):
+                put(a)
+        else:
+            twin = [x.clone() for x in flat]
+            lists = [views(x) for x in twin]
+
+            def put(a):
+                twin[a].copy_(flat[a])
+
+            def get(a):
+                return twin[a][:, :n]
         cols = wk.sample_columns(n, 20000, wl.seed).cuda()
         ow, om, opub = (np.ascontiguousarray(x[:, cols].cpu().numpy()) for x in (flat[0], flat[2], flat[3]))
-        with ctx.tensor_plan(*[views(x) for x in twin]) as plan:
+        with ctx.tensor_plan(*lists) as plan:
             for t in range(12):
                 wk.fill_gradients(wl, t, flat[1])
-                twin[1].copy_(flat[1])
+                put(1)
                 mask = ctx.stale_mask(wl.seed, t, wl.stale_threshold)
                 ctx.step(*flat, mask, wl.lr, wl.mu, t)
                 plan.step(mask, wl.lr, wl.mu, t)
                 orc.step_f32(P, S, wl.tau, t, ow, np.ascontiguousarray(flat[1][:, cols].cpu().numpy()), om, opub,
                              mask, wl.lr, wl.mu)
                 torch.cuda.synchronize()
-                for a, b, what in zip(flat, twin, "wgmp"):
-                    assert torch.equal(a[:, :n], b[:, :n]), "%s differs between the layouts at t=%d" % (what, t)
-                assert np.array_equal(bits(twin[0][:, cols].cpu().numpy()), bits(ow))
-                assert np.array_equal(bits(twin[3][:, cols].cpu().numpy()), bits(opub))
+                for a, what in enumerate("wgmp"):
+                    assert torch.equal(flat[a][:, :n], get(a)), "%s differs between the layouts at t=%d" % (what, t)
+                assert np.array_equal(bits(get(0)[:, cols].cpu().numpy()), bits(ow))
+                assert np.array_equal(bits(get(3)[:, cols].cpu().numpy()), bits(opub))
