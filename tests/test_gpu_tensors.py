@@ -208,14 +208,15 @@ def test_plan_validation():
             plan.destroy()
 
 
-@pytest.mark.parametrize("where", ["views", "views, as given", "stacked"])
+@pytest.mark.parametrize("where", ["views", "views, as given", "stacked", "separate"])
 def test_tensors_of_workload_2_equal_the_flat_path(where):
     """ResNet-50-shaped tensor list (161 tensors): the per-tensor entry point and the flat entry
     point give the same bits on the whole model, and both match the oracle on a column sample.
     views: the tensors are views into flat rows, back to back (the plan joins them into one);
     views, as given: the same with the plan told to keep the 161 tensors and to find them through
     the pointers by place; stacked: every parameter in a [P, size] allocation of its own (161 tile
-    entries name their tensor's place)."""
+    entries name their tensor's place); separate: every tensor of every process in an allocation of
+    its own (pointers by place)."""
     wl = wk.workload(2)
     P, S, n = wl.P, wl.S, wl.n
     tensors = wl.tensors()
@@ -238,8 +239,31 @@ def test_tensors_of_workload_2_equal_the_flat_path(where):
                 out.append(row)
             return out
 
-        if where == "stacked":
-            stacks = [[torch.empty((P, s + (-s) % 4), device="cuda") for s in sizes] for _ in range(4)]
+        if where in ("stacked", "separate"):
+            if where == "stacked":
+                stacks = [[torch.empty((P, s + (-s) % 4), device="cuda") for s in sizes] for _ in range(4)]
+            else:   # a list of P one-row tensors behaves like a [P, size] tensor in what follows
+                class Rows:
+                    def __init__(self, s):
+                        self.rows = [torch.empty(s, device="cuda") for _ in range(P)]
+
+                    def __getitem__(self, key):
+                        p, cols = key
+                        if isinstance(p, slice):
+                            return Block(self.rows, cols)
+                        return self.rows[p][cols]
+
+                class Block:
+                    def __init__(self, rows, cols):
+                        self.rows, self.cols = rows, cols
+
+                    def copy_(self, src):
+                        for p, row in enumerate(self.rows):
+                            row[self.cols].copy_(src[p])
+
+                    def gather(self):
+                        return torch.stack([row[self.cols] for row in self.rows])
+                stacks = [[Rows(s) for s in sizes] for _ in range(4)]
             lists = [[[st[p, :s] for st, s in zip(per_array, sizes)] for p in range(P)] for per_array in stacks]
 
             def put(a):          # flat array a -> the tensors of array a
@@ -249,7 +273,8 @@ def test_tensors_of_workload_2_equal_the_flat_path(where):
                     at += s
 
             def get(a):          # the tensors of array a as a (P, n) matrix
-                return torch.cat([st[:, :s] for st, s in zip(stacks[a], sizes)], dim=1)
+                parts = [st[:, :s] for st, s in zip(stacks[a], sizes)]
+                return torch.cat([x.gather() if where == "separate" else x for x in parts], dim=1)
             for a in (0, 2, 3):
                 put(a)
         else:
