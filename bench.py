@@ -271,6 +271,10 @@ def main() -> int:
     ap.add_argument("--lag", type=int, default=None, metavar="TOLERANCE_MS",
                     help="lateness deeper than one iteration: wagma_lag_masks with this tolerance drive "
                          "wagma_step_lag instead of the workload's Bernoulli mask")
+    ap.add_argument("--use-memory-first", action="store_true",
+                    help="before anything is allocated, make the GPU's memory one that has been in use: 120 "
+                         "allocations of 0.2 to 3.5 GiB, half of them freed in random order, 20 more, then all "
+                         "given back (what ordinary allocations return afterwards is mixed over the HBM regions)")
     ap.add_argument("--no-extras", action="store_true",
                     help="the headline run only: no plain-allocation leg, no other workloads")
     ap.add_argument("--no-counters", action="store_true",
@@ -310,13 +314,33 @@ def main() -> int:
         wl = dataclasses.replace(wl, **custom)
         wl = dataclasses.replace(wl, name="%s with %s" % (wl.name, ", ".join("%s=%d" % kv for kv in custom.items())))
     variant = bool(custom or args.opt or args.ld or args.tensors or args.graph or args.lag is not None
-                   or args.plain_alloc)
+                   or args.plain_alloc or args.use_memory_first)
     extras = not args.no_extras and not variant and args.workload == 4
     K = wl.iters if args.steps is None else args.steps
     W = args.warmup
     P, S, n = wl.P, wl.S, wl.n
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.use_memory_first:
+        import random
+        rnd = random.Random(1)
+        free_bytes = torch.cuda.mem_get_info()[0]
+        held, total = [], 0
+        for _ in range(120):
+            size = int(rnd.uniform(0.2, 3.5) * 2 ** 30)
+            if total + size > 0.8 * free_bytes:
+                break
+            held.append(torch.empty(size, dtype=torch.uint8, device=dev).fill_(1))
+            total += size
+        rnd.shuffle(held)
+        del held[:len(held) // 2]
+        more = [torch.empty(int(rnd.uniform(0.2, 3.5) * 2 ** 30), dtype=torch.uint8, device=dev).fill_(2)
+                for _ in range(20)]
+        torch.cuda.synchronize()
+        del held, more
+        torch.cuda.empty_cache()
+        log("the GPU's memory has been used: %.0f GB allocated, freed in random order" % (total / 1e9))
 
     ctx = lw.Wagma(P, S, n, wl.tau)
     if args.ld:
