@@ -135,14 +135,14 @@ int oracle_grouping_unionfind(int P, int S, int64_t t, int32_t *rep)
  * The bit positions of the butterfly phases executed in iteration t, in the
  * order Algorithm 1 visits them.  bits[] must hold log2(S) entries.
  */
-static void phase_bits(int global_phases, int group_phases, int64_t t, int *bits)
+static void phase_bits(int log2_P, int log2_S, int64_t t, int *bits)
 {
-    int shift = 0;
-    if (global_phases > 0)
-        shift = (int)((t * (int64_t)group_phases) % global_phases);
-    for (int r = 0; r < group_phases; ++r) {
-        bits[r] = shift;
-        shift = (shift + 1) % global_phases;
+    int bit = 0;
+    if (log2_P > 0)
+        bit = (int)((t * (int64_t)log2_S) % log2_P);
+    for (int r = 0; r < log2_S; ++r) {
+        bits[r] = bit;
+        bit = (bit + 1) % log2_P;
     }
 }
 
@@ -157,15 +157,15 @@ static void phase_bits(int global_phases, int group_phases, int64_t t, int *bits
  */
 int oracle_member_table(int P, int S, int64_t t, int32_t *table)
 {
-    int global_phases = exact_log2(P);
-    int group_phases = exact_log2(S);
+    int log2_P = exact_log2(P);
+    int log2_S = exact_log2(S);
     int bits[32];
-    if (global_phases < 0 || group_phases < 0 || S > P || t < 0 || !table)
+    if (log2_P < 0 || log2_S < 0 || S > P || t < 0 || !table)
         return ORACLE_EINVAL;
-    phase_bits(global_phases, group_phases, t, bits);
+    phase_bits(log2_P, log2_S, t, bits);
 
     int all_bits = 0;
-    for (int r = 0; r < group_phases; ++r)
+    for (int r = 0; r < log2_S; ++r)
         all_bits |= 1 << bits[r];
 
     int k = 0;
@@ -174,7 +174,7 @@ int oracle_member_table(int P, int S, int64_t t, int32_t *table)
             continue; /* not the smallest member of its group */
         for (int e = 0; e < S; ++e) {
             int p = base;
-            for (int r = 0; r < group_phases; ++r)
+            for (int r = 0; r < log2_S; ++r)
                 if ((e >> r) & 1)
                     p |= 1 << bits[r];
             table[k * S + e] = p;

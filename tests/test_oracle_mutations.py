@@ -42,7 +42,7 @@ MUTATIONS = [
      "w[(int64_t)p * ld + j] = (w_sum + w_prime[p]) * (1.0f / (float)(S + 1));",
      pins.test_stale_divisor_is_a_true_division),
     ("member digits in reverse phase order",
-     "p |= 1 << bits[r];\n            table", "p |= 1 << bits[group_phases - 1 - r];\n            table",
+     "p |= 1 << bits[r];\n            table", "p |= 1 << bits[log2_S - 1 - r];\n            table",
      pins.test_alg1_phase_bits_wrap_order),
     ("send buffer gets W instead of W'",
      "        for (int i = 0; i < P; ++i)\n            pub[(int64_t)i * ld + j] = w_prime[i];",
