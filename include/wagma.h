@@ -287,9 +287,10 @@ int wagma_lag_masks(const wagma_ctx* ctx, uint64_t seed, int64_t iter, int windo
  * m and pub lie in three.  Regions cannot be queried, so the allocator finds them by timing a
  * small write kernel on pairs of memory blocks, and places the arrays in one of these ways:
  *   WAGMA_PLACE_CHUNKS  every array is built, through the virtual memory API, from 1 GiB
- *                       chunks: either all chunks of all arrays from one region, or so that
- *                       at every column w, m and pub lie in three regions and g lies with w,
- *                       whichever the step runs faster on;
+ *                       chunks after one of three patterns, whichever the step runs fastest
+ *                       on: w, g and m from one region and pub (written, hardly ever read)
+ *                       from another; all chunks of all arrays from one region; or so that
+ *                       at every column w, m and pub lie in three regions and g lies with w;
  *   WAGMA_PLACE_ARRAYS  whole arrays: w, m, pub in three regions, g in that of w (regions
  *                       found with the probe);
  *   WAGMA_PLACE_SEARCH  up to eight candidate arrays spread over the free memory, and a
@@ -297,10 +298,10 @@ int wagma_lag_masks(const wagma_ctx* ctx, uint64_t seed, int64_t iter, int windo
  *                       the step kernel itself (no assumption about regions);
  *   WAGMA_PLACE_PLAIN   four ordinary allocations.
  * On a GPU whose memory is untouched ordinary allocations lie in one region; on one that has
- * been in use they are mixed over the regions, and chunks of one region bring back what that
- * costs (0.80 -> 0.81 of the peak bandwidth on a 26 GB problem).  By default (WAGMA_PLACE_AUTO)
- * PLAIN, the two forms of CHUNKS and SEARCH are each timed with the step kernels, in this
- * order, and a later one replaces what is kept if it is 1 % faster.
+ * been in use they are mixed over the regions, and arrays built from chunks bring back what
+ * that costs (0.80 -> 0.81 of the peak bandwidth on a 26 GB problem) or more.  By default
+ * (WAGMA_PLACE_AUTO) PLAIN and the three forms of CHUNKS are each timed with the step kernels,
+ * in this order, and a later one replaces what is kept if it is 0.5 % faster.
  * On the arrays it hands out the call also measures which way of dealing the column tiles out to
  * the chip's eight dies and to the wavefronts of a workgroup is fastest for steps on these
  * arrays, and the context uses that one whenever a step is given exactly these four arrays
@@ -327,9 +328,9 @@ int wagma_placement_info(const wagma_ctx* ctx, int* mode, int* candidates, int* 
 #define WAGMA_OPT_PLACEMENT 9    /* how wagma_alloc_buffers places the arrays: WAGMA_PLACE_*  */
 #define WAGMA_PLACE_PLAIN 0      /* four ordinary allocations                                  */
 #define WAGMA_PLACE_ARRAYS 1     /* whole arrays in different HBM regions                      */
-#define WAGMA_PLACE_CHUNKS 2     /* arrays built from 1 GiB chunks, of one region or of all three */
-#define WAGMA_PLACE_AUTO 3       /* default: PLAIN, CHUNKS and SEARCH are timed with the step
-                                    kernel and the fastest is kept                           */
+#define WAGMA_PLACE_CHUNKS 2     /* arrays built from 1 GiB chunks of chosen regions (three patterns) */
+#define WAGMA_PLACE_AUTO 3       /* default: PLAIN and the patterns of CHUNKS are timed with the
+                                    step kernel and the fastest is kept                      */
 #define WAGMA_PLACE_SEARCH 4     /* candidate arrays spread over the free memory; which one
                                     becomes w, g, m, pub is decided by timing the step kernel */
 int wagma_set_option(wagma_ctx* ctx, int option, int64_t value);

@@ -326,9 +326,10 @@ void release(ArraySet& set)
     set = ArraySet();
 }
 
-// arrays built chunk by chunk (wagma_chunks.h): from all three regions in turn, or all from one
-bool place_chunks(int device, size_t bytes, bool debug, bool one_region, ArraySet& out)
+// arrays built chunk by chunk (wagma_chunks.h) after one of its patterns
+bool place_chunks(int device, size_t bytes, bool debug, wagma_placement::ChunkPattern pattern, ArraySet& out)
 {
+    using wagma_placement::ChunkPattern;
     const int per_array = (int)((bytes + wagma_placement::kChunkBytes - 1) / wagma_placement::kChunkBytes);
     if (4 * per_array > wagma_placement::kMaxChunks)
         return false;
@@ -337,7 +338,7 @@ bool place_chunks(int device, size_t bytes, bool debug, bool one_region, ArraySe
     VmmArrays* arrays = nullptr;
     if (memory && index && memory->init(device)) {
         memory->reserve = size_t(2) << 30;
-        auto* search = new (std::nothrow) wagma_placement::ChunkSearch<VmmMemory>(*memory, per_array, one_region);
+        auto* search = new (std::nothrow) wagma_placement::ChunkSearch<VmmMemory>(*memory, per_array, pattern);
         wagma_placement::ChunkPlan plan;
         plan.w = index;
         plan.g = index + per_array;
@@ -346,7 +347,10 @@ bool place_chunks(int device, size_t bytes, bool debug, bool one_region, ArraySe
         if (search && search->run(plan)) {
             if (debug) {
                 std::fprintf(stderr, "wagma placement (chunks, %s): %d examined, %d classes, %d of %d in pattern, "
-                                     "slow %.0f fast %.0f GB/s\n  classes:", one_region ? "one region" : "three regions",
+                                     "slow %.0f fast %.0f GB/s\n  classes:",
+                             pattern == ChunkPattern::one_region  ? "one region"
+                             : pattern == ChunkPattern::pub_apart ? "pub apart"
+                                                                  : "three regions",
                              plan.examined, plan.classes, plan.in_pattern, 4 * per_array, plan.slow_gbs, plan.fast_gbs);
                 for (int i = 0; i < search->chunks(); ++i)
                     std::fprintf(stderr, " %d", search->chunk_class(i));
@@ -354,7 +358,8 @@ bool place_chunks(int device, size_t bytes, bool debug, bool one_region, ArraySe
             }
             arrays = memory->build(plan);
             out.examined = plan.examined;
-            out.regions = one_region ? 1 : plan.classes < 3 ? (plan.classes < 1 ? 1 : plan.classes) : 3;
+            const int wanted = pattern == ChunkPattern::one_region ? 1 : pattern == ChunkPattern::pub_apart ? 2 : 3;
+            out.regions = plan.classes < wanted ? (plan.classes < 1 ? 1 : plan.classes) : wanted;
             out.g_with_w = 1;
             out.slow_gbs = plan.slow_gbs;
             out.fast_gbs = plan.fast_gbs;
@@ -426,8 +431,8 @@ bool place_plain(size_t bytes, ArraySet& out)
 }
 
 // Milliseconds per group step of `ctx` on the (uninitialised) arrays of `set`: every distinct
-// group schedule once, after one untimed pass; with `global`, of a global iteration (twice, after
-// one untimed one).  0 on failure.
+// group schedule equally often, six steps or a few more, after one untimed pass of as many; with
+// `global`, of a global iteration (three, after three untimed ones).  0 on failure.
 double time_steps(wagma_ctx* ctx, const ArraySet& set, bool global = false)
 {
     hipEvent_t start = nullptr, stop = nullptr;
@@ -444,7 +449,7 @@ double time_steps(wagma_ctx* ctx, const ArraySet& set, bool global = false)
     double ms_per_step = 0.0;
     bool ok = true;
     for (int pass = 0; pass < 2 && ok; ++pass) {
-        const int steps = global ? 2 : ctx->period;
+        const int steps = global ? 3 : ctx->period * ((6 + ctx->period - 1) / ctx->period);
         ok = hipEventRecord(start, nullptr) == hipSuccess;
         for (int t = 0; t < steps && ok; ++t)
             ok = step_flat(ctx, set.ptr[0], set.ptr[1], set.ptr[2], set.ptr[3], late, nullptr, 0.0f, 0.0f, t, nullptr,
@@ -620,19 +625,22 @@ int wagma_alloc_buffers(wagma_ctx* ctx, float** w, float** g, float** m, float**
 
     // With WAGMA_PLACE_AUTO: four ordinary allocations first, while the memory is as the caller
     // left it (on a GPU with untouched memory they lie in one HBM region, which the kernel that
-    // holds a group in registers likes best); then arrays built from chunks of one region (what
-    // brings that back on a GPU whose memory has been in use: 0.80 -> 0.81 of peak on the
-    // headline workload); then arrays built from chunks of all three regions in turn (which the
-    // kernel for larger groups likes best), then the timed search (placement by whole arrays is
-    // left out: the timed search covers what it finds).  Each is judged with the step kernels
-    // themselves and must be 1 % faster than what is kept to replace it; at most two sets of
-    // arrays exist at a time.  WAGMA_PLACE_CHUNKS compares the two chunk patterns in the same
-    // manner; another fixed mode takes that mode if it can be had.  Ordinary allocations are what
-    // remains when nothing else could be had.
-    constexpr int kChunksOneRegion = 100;  // a candidate, not a mode: reported as WAGMA_PLACE_CHUNKS, one region
+    // holds a group in registers likes); then arrays built from chunks: w, g and m from one region
+    // and pub, which is written and hardly ever read, from another (measured best for that kernel
+    // and good for the one for larger groups: 0.814 -> 0.822 of peak, global iteration 6130 -> 6400
+    // GB/s); all from one region (what brings the ordinary allocations' rate back on a GPU whose
+    // memory has been in use); from all three regions in turn (which the kernel for larger groups
+    // likes best).  Each is judged with the step kernels themselves and must be 0.5 % faster than
+    // what is kept to replace it; at most two sets of arrays exist at a time.  WAGMA_PLACE_CHUNKS
+    // compares the three chunk patterns in the same manner; another fixed mode takes that mode if
+    // it can be had (the timed search and the placement by whole arrays are no longer part of
+    // AUTO: the chunk patterns cover what they find).  Ordinary allocations are what remains when
+    // nothing else could be had.
+    using wagma_placement::ChunkPattern;
+    constexpr int kChunksOneRegion = 100, kChunksPubApart = 101;  // candidates, not modes: reported as WAGMA_PLACE_CHUNKS
     const int mode = bytes >= wagma_placement::kPlacementMinBytes ? ctx->opt_placement : WAGMA_PLACE_PLAIN;
-    const int auto_order[4] = {WAGMA_PLACE_PLAIN, kChunksOneRegion, WAGMA_PLACE_CHUNKS, WAGMA_PLACE_SEARCH};
-    const int chunks_order[4] = {kChunksOneRegion, WAGMA_PLACE_CHUNKS, WAGMA_PLACE_PLAIN, -1};
+    const int auto_order[4] = {WAGMA_PLACE_PLAIN, kChunksPubApart, kChunksOneRegion, WAGMA_PLACE_CHUNKS};
+    const int chunks_order[4] = {kChunksPubApart, kChunksOneRegion, WAGMA_PLACE_CHUNKS, WAGMA_PLACE_PLAIN};
     const int fixed_order[4] = {mode, WAGMA_PLACE_PLAIN, -1, -1};
     const bool compare = mode == WAGMA_PLACE_AUTO || mode == WAGMA_PLACE_CHUNKS;
     ArraySet best;
@@ -646,8 +654,12 @@ int wagma_alloc_buffers(wagma_ctx* ctx, float** w, float** g, float** m, float**
         bool ok = false;
         if (candidate == WAGMA_PLACE_SEARCH)
             ok = place_search(ctx, bytes, debug, trial);
-        else if (candidate == WAGMA_PLACE_CHUNKS || candidate == kChunksOneRegion)
-            ok = place_chunks(device, bytes, debug, candidate == kChunksOneRegion, trial);
+        else if (candidate == WAGMA_PLACE_CHUNKS || candidate == kChunksOneRegion || candidate == kChunksPubApart)
+            ok = place_chunks(device, bytes, debug,
+                              candidate == kChunksOneRegion  ? ChunkPattern::one_region
+                              : candidate == kChunksPubApart ? ChunkPattern::pub_apart
+                                                             : ChunkPattern::rotate,
+                              trial);
         else if (candidate == WAGMA_PLACE_ARRAYS)
             ok = place_arrays(bytes, debug, trial);
         else
@@ -662,8 +674,8 @@ int wagma_alloc_buffers(wagma_ctx* ctx, float** w, float** g, float** m, float**
             std::fprintf(stderr, "wagma placement: mode %d regions %d: %.3f ms per iteration\n", trial.mode,
                          trial.regions, trial.step_ms);
         // step_ms == 0: the timing failed, the placement's speed is unknown; any placement with
-        // a known time replaces such a one, and a later one must be 1 % faster to replace a known one
-        const bool better = trial.step_ms > 0.0 && (best.step_ms == 0.0 || trial.step_ms < 0.99 * best.step_ms);
+        // a known time replaces such a one, and a later one must be 0.5 % faster to replace a known one
+        const bool better = trial.step_ms > 0.0 && (best.step_ms == 0.0 || trial.step_ms < 0.995 * best.step_ms);
         if (!best.ptr[0] || better) {
             release(best);
             best = trial;

@@ -13,8 +13,10 @@
 // GiB, or a GPU whose free memory is scattered over the regions.
 // A second pattern takes every chunk of every array from ONE region (the class with the most
 // chunks; arrays larger than a region go on with the next largest): what ordinary allocations
-// look like on a GPU with untouched memory, rebuilt where the memory has been in use.  Which of
-// the two the step runs faster on depends on its kernel (wagma_alloc_buffers times both).
+// look like on a GPU with untouched memory, rebuilt where the memory has been in use.  A third
+// takes w, g and m from one region and pub, the array that is written and hardly ever read, from
+// another.  Which of them the step runs fastest on depends on its kernel and on the GPU's
+// memory (wagma_alloc_buffers times them).
 //
 // A Memory object provides
 //   char*  new_chunk()                   maps one more physical chunk, nullptr when out of room
@@ -107,12 +109,19 @@ struct ChunkPlan {
     double slow_gbs = 0.0, fast_gbs = 0.0;
 };
 
+// which region chunk j of each array comes from (region slots 0, 1, 2 are served by the classes with
+// the most, second and third most chunks, the slot with the largest need by the largest class)
+enum class ChunkPattern {
+    rotate,      // w and g: j mod 3, m: (j + 1) mod 3, pub: (j + 2) mod 3
+    one_region,  // everything from one
+    pub_apart    // w, g, m from one, pub from another
+};
+
 template <typename Memory>
 class ChunkSearch {
 public:
-    // one_region: all chunks of all four arrays from one region instead of the pattern above
-    ChunkSearch(Memory& memory, int chunks_per_array, bool one_region = false)
-        : mem_(memory), k_(chunks_per_array), one_region_(one_region)
+    ChunkSearch(Memory& memory, int chunks_per_array, ChunkPattern pattern = ChunkPattern::rotate)
+        : mem_(memory), k_(chunks_per_array), pattern_(pattern)
     {
     }
 
@@ -121,23 +130,25 @@ public:
     bool run(ChunkPlan& plan)
     {
         int need[3] = {0, 0, 0};
-        for (int j = 0; j < k_; ++j) {
-            need[slot(j, 0)] += 2;  // w and g
-            need[slot(j, 1)] += 1;  // m
-            need[slot(j, 2)] += 1;  // pub
-        }
+        for (int j = 0; j < k_; ++j)
+            for (int a = 0; a < 4; ++a)
+                need[slot(j, a)] += 1;
         const size_t side = kChunkBytes / 2;
         while (n_ < kMaxChunks && !failed_ && !clusters_.full()) {
             // the three regions with the most chunks so far are the ones that will be used
             int top[3];
             top_classes(top);
-            bool enough = n_classes_ >= (one_region_ ? 1 : 3);
-            for (int r = 0; r < 3 && enough; ++r)
-                enough = count_[top[r]] >= need_sorted(need, r);
-            // arrays that no single region can hold: once a region has given what a region has,
-            // the rest comes from the others
-            if (one_region_ && n_classes_ >= 1 && 4 * k_ > kRegionChunks)
-                enough = count_[top[0]] >= kRegionChunks && n_ >= 4 * k_;
+            const int classes_wanted = pattern_ == ChunkPattern::one_region ? 1 : pattern_ == ChunkPattern::pub_apart ? 2 : 3;
+            bool enough = n_classes_ >= classes_wanted;
+            for (int r = 0; r < 3 && enough; ++r) {
+                int wanted = need_sorted(need, r);
+                // arrays that a region cannot hold: once it has given what a region has, the
+                // rest comes from the others
+                if (pattern_ != ChunkPattern::rotate && wanted > kRegionChunks)
+                    wanted = kRegionChunks;
+                enough = count_[top[r]] >= wanted;
+            }
+            enough = enough && n_ >= 4 * k_;
             if (enough)
                 break;
             char* c = mem_.new_chunk();
@@ -193,7 +204,6 @@ public:
             used_[i] = false;
         plan.in_pattern = 0;
         int* arrays[4] = {plan.w, plan.g, plan.m, plan.pub};
-        const int shift[4] = {0, 0, 1, 2};
         for (int pass = 0; pass < 2; ++pass) {  // first the chunks the pattern asks for, then any
             for (int a = 0; a < 4; ++a) {
                 for (int j = 0; j < k_; ++j) {
@@ -201,15 +211,17 @@ public:
                         arrays[a][j] = -1;
                     if (arrays[a][j] >= 0)
                         continue;
-                    const int want = class_of_slot[slot(j, shift[a])];
+                    const int want = class_of_slot[slot(j, a)];
                     int got = -1;
                     if (pass == 0)
                         got = take(want);
-                    // what the one region cannot give comes from the next largest, as few
-                    // regions as possible (ordinary allocations in untouched memory look like that)
-                    for (int r = 1; r < 3 && pass == 1 && one_region_ && got < 0; ++r)
-                        if (r < n_classes_)
-                            got = take(top[r]);
+                    // what a region cannot give comes from a region the pattern does not use, from
+                    // as few as possible (ordinary allocations in untouched memory look like that)
+                    for (int r = 0; r < 2 && pass == 1 && pattern_ != ChunkPattern::rotate && got < 0; ++r) {
+                        const int next = pattern_ == ChunkPattern::one_region ? 1 + r : 2 - r;
+                        if (next < n_classes_)
+                            got = take(top[next]);
+                    }
                     if (pass == 1 && got < 0)
                         got = take(-2);
                     arrays[a][j] = got;
@@ -227,8 +239,16 @@ public:
     bool chunk_used(int i) const { return used_[i]; }
 
 private:
-    // which of the three region slots of the pattern chunk j of an array with this shift asks for
-    int slot(int j, int shift) const { return one_region_ ? 0 : (j + shift) % 3; }
+    // which of the three region slots chunk j of array a (w, g, m, pub) asks for
+    int slot(int j, int a) const
+    {
+        const int shift[4] = {0, 0, 1, 2};
+        switch (pattern_) {
+        case ChunkPattern::one_region: return 0;
+        case ChunkPattern::pub_apart: return a == 3 ? 1 : 0;
+        default: return (j + shift[a]) % 3;
+        }
+    }
     static int need_sorted(const int need[3], int rank)
     {
         int s[3] = {need[0], need[1], need[2]};
@@ -317,7 +337,7 @@ private:
 
     Memory& mem_;
     int k_;
-    bool one_region_;
+    ChunkPattern pattern_;
     RateClusters clusters_;
     char* chunk_[kMaxChunks];
     int class_[kMaxChunks];

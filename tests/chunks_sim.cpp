@@ -140,7 +140,7 @@ void run_one_region(const char* name, SimMemory& mem, int k, bool expect_plan, i
     plan.g = g.data();
     plan.m = m.data();
     plan.pub = pub.data();
-    auto* search = new wagma_placement::ChunkSearch<SimMemory>(mem, k, true);
+    auto* search = new wagma_placement::ChunkSearch<SimMemory>(mem, k, wagma_placement::ChunkPattern::one_region);
     const bool ok = search->run(plan);
     std::printf("%-44s plan %d  examined %3d  classes %d  in pattern %3d/%3d  probes %4ld  skipped %3.0f GiB\n", name,
                 (int)ok, plan.examined, plan.classes, plan.in_pattern, 4 * k, mem.probes, mem.skipped_gib);
@@ -174,10 +174,87 @@ void run_one_region(const char* name, SimMemory& mem, int k, bool expect_plan, i
     delete search;
 }
 
+// The third pattern: w, g and m from one region, pub from another.
+void run_pub_apart(const char* name, SimMemory& mem, int k, int min_right_percent)
+{
+    std::vector<int> w(k), g(k), m(k), pub(k);
+    wagma_placement::ChunkPlan plan;
+    plan.w = w.data();
+    plan.g = g.data();
+    plan.m = m.data();
+    plan.pub = pub.data();
+    auto* search = new wagma_placement::ChunkSearch<SimMemory>(mem, k, wagma_placement::ChunkPattern::pub_apart);
+    const bool ok = search->run(plan);
+    std::printf("%-44s plan %d  examined %3d  classes %d  in pattern %3d/%3d  probes %4ld  skipped %3.0f GiB\n", name,
+                (int)ok, plan.examined, plan.classes, plan.in_pattern, 4 * k, mem.probes, mem.skipped_gib);
+    check(ok, name, "no plan");
+    if (ok) {
+        std::set<int> seen;
+        int main_region[8] = {0, 0, 0, 0, 0, 0, 0, 0}, pub_region[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        for (int j = 0; j < k; ++j) {
+            for (int idx : {w[j], g[j], m[j], pub[j]}) {
+                check(idx >= 0 && idx < plan.examined, name, "a slot without a chunk");
+                check(seen.insert(idx).second, name, "a chunk used twice");
+            }
+            for (int idx : {w[j], g[j], m[j]})
+                if (idx >= 0 && !mem.mixed.count(idx))
+                    ++main_region[mem.region_of_chunk(idx) & 7];
+            if (pub[j] >= 0 && !mem.mixed.count(pub[j]))
+                ++pub_region[mem.region_of_chunk(pub[j]) & 7];
+        }
+        int a = 0, b = 0;
+        for (int r = 1; r < 8; ++r) {
+            a = main_region[r] > main_region[a] ? r : a;
+            b = pub_region[r] > pub_region[b] ? r : b;
+        }
+        check(a != b, name, "pub lies where w, g and m lie");
+        check(100 * (main_region[a] + pub_region[b]) >= min_right_percent * 4 * k, name, "too few chunks where the pattern wants them");
+    }
+    delete search;
+}
+
 }  // namespace
 
 int main()
 {
+    {
+        const std::vector<double> three = {0.0, 96.0, 192.0, 288.0};
+        for (int k : {2, 7, 27}) {
+            SimMemory mem;
+            mem.boundaries_gib = three;
+            char name[64];
+            std::snprintf(name, sizeof name, "pub apart: fresh memory, %d chunks per array", k);
+            run_pub_apart(name, mem, k, 100);
+        }
+        for (int seed = 1; seed <= 6; ++seed) {
+            SimMemory mem;
+            mem.boundaries_gib = three;
+            mem.noise = 0.04;
+            mem.straggler_every = 12.0;
+            mem.rng ^= (uint64_t)seed * 0x9E3779B97F4A7C15ull;
+            for (int i = 0; i < 200; ++i)
+                mem.scattered_gib.push_back((double)((i * (31 + 2 * seed)) % 280));
+            char name[64];
+            std::snprintf(name, sizeof name, "pub apart: scattered, noise, seed %d", seed);
+            run_pub_apart(name, mem, 7, 90);
+        }
+        {
+            SimMemory mem;
+            mem.boundaries_gib = three;
+            for (int i = 0; i < 160; ++i)
+                mem.scattered_gib.push_back((double)((i * 37) % 280));
+            mem.mixed = {0, 3, 4, 11, 30};
+            run_pub_apart("pub apart: scattered, some chunks mixed", mem, 7, 100);
+        }
+        {
+            // arrays of 35 chunks: w, g, m need 105, a region has 96; the rest comes from the third region
+            SimMemory mem;
+            mem.boundaries_gib = three;
+            for (int i = 0; i < 280; ++i)
+                mem.scattered_gib.push_back((double)((i * 37) % 280));
+            run_pub_apart("pub apart: 105 + 35 chunks needed", mem, 35, 85);
+        }
+    }
     {
         const std::vector<double> three = {0.0, 96.0, 192.0, 288.0};
         for (int k : {2, 7, 20}) {
