@@ -430,6 +430,8 @@ def main() -> int:
         bufs = ctx.alloc_placed()     # w, m, pub in different HBM regions
         info = ctx.placement_info()
         placement = "wagma_alloc_buffers: %(mode)s placement, %(candidates)d memory blocks examined" % info
+        if info["mode"] == "chunks":   # which of the three chunk patterns: pub apart 2, one region 1, three regions 3
+            placement += ", w, m and pub in %d region%s" % (info["regions"], "" if info["regions"] == 1 else "s")
         placement += ", launch shapes %d (group rows in registers) and %d (rows over a workgroup) measured best on them" % (
             ctx.debug_get_option(lw.WAGMA_DEBUG_PLACED_SHAPE), ctx.debug_get_option(lw.WAGMA_DEBUG_PLACED_COOP_SHAPE))
         log("placement:", info)
